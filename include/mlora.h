@@ -1,0 +1,163 @@
+/*
+ * mlora -- batched multi-adapter LoRA apply for one MI355X (gfx950).
+ *
+ * The operation (standard LoRA update, which the paper adopts through its LoRA citation in
+ * Section 1 and Related Work; per-token adapter choice from the serving path of Sections 3.4
+ * and 4, where a request decodes with the adapter resident in its GPU batch slot):
+ *
+ *     y[t, :] += (alpha_s / r_s) * B_s * (A_s * x[t, :])          s = a(t) >= 0
+ *
+ * with A_s [r_s, d_in] and B_s [d_out, r_s] in the PEFT export layout (Section 3.3), kept in
+ * slot tables allocated at a configured maximum rank into which smaller adapters are padded
+ * (Section 3.2).  bf16 in, fp32 accumulate, one round-to-nearest-even back to bf16.
+ *
+ * Conventions for every entry point
+ *   - extern "C"; returns an int32 status (0 = MLORA_OK, negative = error); never throws.
+ *   - Pointers named *_dev / x / y / token_slot / topk_ids are DEVICE pointers owned by the
+ *     caller; everything else is a HOST pointer.  `stream` is a hipStream_t passed as void*
+ *     (NULL = the default stream).  Calls only enqueue work; they do not synchronise the
+ *     stream (lora_apply_segmented may wait for its own previous small host-to-device copy).
+ *   - bf16 tensors are row-major with 16-byte aligned rows; d_in and d_out are multiples of 8;
+ *     ldx / ldy are row strides in elements (multiples of 8).
+ *   - A slot index of -1, an index outside [0, n_slots), or a slot that holds no adapter
+ *     (never uploaded, or evicted) leaves the row bit-identical.
+ *   - A site's tables may be read by applies on one stream at a time; uploading into a slot
+ *     that an unfinished apply on another stream reads is a caller error.
+ */
+#ifndef MLORA_H
+#define MLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MLORA_OK            =  0,
+    MLORA_E_INVALID     = -1,   /* null pointer, negative size, bad descriptor            */
+    MLORA_E_SHAPE       = -2,   /* rank outside [1, r_max], misaligned strides or widths  */
+    MLORA_E_SLOT        = -3,   /* slot outside [0, n_slots)                              */
+    MLORA_E_SEGMENTS    = -4,   /* offsets not monotone, not starting at 0 or ending at T */
+    MLORA_E_HIP         = -5,   /* a HIP runtime call or launch failed                    */
+    MLORA_E_UNSUPPORTED = -6    /* e.g. MoE call on a dense site, batch larger than plan  */
+};
+
+#define MLORA_MAX_RANK 64       /* r_max is rounded up to a power of two <= 64 in the tables */
+#define MLORA_CHUNK     8       /* rows of one adapter handled together by one workgroup   */
+
+/* One LoRA-targeted projection (a "site"): its slot tables and their shape limits
+ * (Section 3.2: a worker advertises adapter-shape limits and allocates slots at them). */
+typedef struct {
+    int32_t d_in, d_out;
+    int32_t r_max;              /* largest rank a slot can hold, 1..64                     */
+    int32_t n_slots;            /* resident adapters (the same-batch window is <= 64)      */
+    int32_t n_experts;          /* 0 = dense site; > 0 = packed per-expert tables          */
+    int32_t device;             /* HIP device ordinal                                      */
+} mlora_site_desc;
+
+typedef struct mlora_site mlora_site;   /* opaque, host-side handle                        */
+typedef struct mlora_plan mlora_plan;   /* opaque: one batch's rows grouped by adapter     */
+
+const char *mlora_status_str(int32_t status);
+
+/* Sizes in bytes of the four device buffers a site needs.
+ *   a_tab: [n_slots, max(n_experts,1), r_pad, d_in]  bf16   (r_pad = r_max rounded to 2^k)
+ *   b_tab: [n_slots, max(n_experts,1), d_out, r_pad] bf16
+ *   meta : rank int32[n_slots] | scale fp32[n_slots] | catalog_id int64[n_slots]
+ *   scratch: private grouping buffers for the entry points that take no explicit plan.
+ * Errors: MLORA_E_INVALID (null, non-positive sizes), MLORA_E_SHAPE (d_in/d_out not a
+ * multiple of 8, r_max outside 1..64). */
+int32_t mlora_site_bytes(const mlora_site_desc *desc, size_t *a_tab, size_t *b_tab,
+                         size_t *meta, size_t *scratch);
+
+/* Binds caller-allocated device buffers (256-byte aligned, sizes from mlora_site_bytes) to a
+ * new site and marks every slot empty (enqueued on the default stream, then synchronised once).
+ * The caller keeps ownership of the buffers and must keep them alive until destroy. */
+int32_t mlora_site_create(const mlora_site_desc *desc, void *a_tab_dev, void *b_tab_dev,
+                          void *meta_dev, void *scratch_dev, mlora_site **out);
+void    mlora_site_destroy(mlora_site *site);   /* frees host state only */
+
+/* Copies one adapter into slot `slot` (the last hop of an adapter load, Sections 3.4 and 4:
+ * an exported revision becomes an engine-local adapter in a GPU slot).
+ *   A: [r, d_in] (MoE site: [n_experts, r, d_in]); B: [d_out, r] (MoE: [n_experts, d_out, r]),
+ *   bf16, contiguous, host memory if src_on_device == 0 else device memory.
+ * Rows/columns r..r_pad-1 are zero-filled; rank[slot] = r, scale[slot] = alpha / r,
+ * catalog_id[slot] = catalog_id.  Asynchronous on `stream`; a host source must stay valid
+ * until the stream has passed this point.
+ * Errors: MLORA_E_SLOT, MLORA_E_SHAPE (r < 1 or r > r_max), MLORA_E_INVALID, MLORA_E_HIP. */
+int32_t lora_slots_upload(mlora_site *site, int32_t slot, int64_t catalog_id,
+                          const void *A, const void *B, int32_t r, float alpha,
+                          int32_t src_on_device, void *stream);
+/* Marks the slot empty (rank 0): rows that point at it are left untouched (an adapter is
+ * visible to traffic only while it is ready, Section 4). */
+int32_t lora_slots_evict(mlora_site *site, int32_t slot, void *stream);
+
+/* ---- explicit plans: group a batch once, reuse it for every site of every layer ------------ */
+
+/* Device bytes for a plan that can hold up to max_items rows (dense: tokens; MoE: token-expert
+ * pairs) over n_keys groups (dense: n_slots; MoE: n_slots * n_experts). */
+int32_t mlora_plan_bytes(int32_t max_items, int32_t n_keys, size_t *bytes);
+int32_t mlora_plan_create(int32_t max_items, int32_t n_keys, int32_t device, void *plan_dev,
+                          mlora_plan **out);
+void    mlora_plan_destroy(mlora_plan *plan);
+
+/* Groups the T rows of a decode batch by slot (stable: ascending row inside a slot) and cuts
+ * each group into chunks of MLORA_CHUNK rows.  token_slot: DEVICE int32[T].  If ready_from is
+ * non-NULL, rows whose slot is empty at that site are dropped here; the apply re-checks anyway.
+ * Errors: MLORA_E_UNSUPPORTED if T > max_items or n_slots > n_keys. */
+int32_t lora_plan_decode(mlora_plan *plan, const int32_t *token_slot, int32_t T, int32_t n_slots,
+                         const mlora_site *ready_from, void *stream);
+/* y[T, d_out] += per-row LoRA delta using a plan built by lora_plan_decode on the same stream
+ * (or otherwise ordered before this call).  x: [T, d_in] bf16, y: [T, d_out] bf16 in place. */
+int32_t lora_apply_decode_planned(mlora_site *site, const mlora_plan *plan,
+                                  const void *x, int64_t ldx, void *y, int64_t ldy, void *stream);
+
+/* Route index build for packed MoE LoRA (per-expert LoRA tensors are keyed by expert id,
+ * Section 3.4): pair p = t*K + k has key = token_slot[t] * n_experts + topk_ids[t, k]; pairs
+ * with a usable slot are sorted by key with a stable counting sort (ties ascending p).
+ *   topk_ids: DEVICE int32[T, K] with distinct experts per token; token_slot: DEVICE int32[T].
+ *   out_sorted_pair: nullable DEVICE int32[T*K]; entries past the number of usable pairs = -1.
+ *   out_group_off : nullable DEVICE int32[n_slots*n_experts + 1], exclusive prefix of counts.
+ * Both outputs are exactly determined by the inputs (bit-exact against a CPU counting sort). */
+int32_t moe_plan_route(mlora_plan *plan, const int32_t *topk_ids, const int32_t *token_slot,
+                       int32_t T, int32_t K, int32_t n_slots, int32_t n_experts,
+                       const mlora_site *ready_from,
+                       int32_t *out_sorted_pair, int32_t *out_group_off, void *stream);
+/* y[T*K, d_out] (pair-major) += per-pair LoRA delta with the (slot, expert) tables of a packed
+ * MoE site, using a plan from moe_plan_route.  x: [T, d_in]. */
+int32_t moe_lora_apply_planned(mlora_site *site, const mlora_plan *plan,
+                               const void *x, int64_t ldx, void *y, int64_t ldy, void *stream);
+
+/* ---- the four calls of the problem statement ------------------------------------------------ */
+
+/* Decode: one token per row, gather-by-index.  Equivalent to lora_plan_decode on the site's
+ * private scratch followed by lora_apply_decode_planned.  T = 0 is MLORA_OK and launches nothing.
+ * Errors: MLORA_E_UNSUPPORTED on a MoE site, MLORA_E_SHAPE on bad strides. */
+int32_t lora_apply_decode(mlora_site *site, const void *x, int64_t ldx, void *y, int64_t ldy,
+                          const int32_t *token_slot, int32_t T, void *stream);
+
+/* Segmented prefill: rows [seg_off[k], seg_off[k+1]) all use slot seg_slot[k] (a request's
+ * prompt is one contiguous run).  seg_off (int32[S+1]) and seg_slot (int32[S]) are HOST arrays;
+ * they are validated here (MLORA_E_SEGMENTS / MLORA_E_SLOT) and copied to the device.  Sites
+ * with r_pad == 64 and d_in a multiple of 16 run the MFMA kernel; others run the
+ * vector kernel over runs of MLORA_CHUNK rows. */
+int32_t lora_apply_segmented(mlora_site *site, const void *x, int64_t ldx, void *y, int64_t ldy,
+                             const int32_t *seg_off, const int32_t *seg_slot, int32_t S,
+                             int32_t T, void *stream);
+
+/* Packed MoE: moe_plan_route on the site's private scratch followed by moe_lora_apply_planned.
+ * y is [T*K, d_out] pair-major. */
+int32_t moe_lora_apply_packed(mlora_site *site, const void *x, int64_t ldx, void *y, int64_t ldy,
+                              const int32_t *topk_ids, const int32_t *token_slot,
+                              int32_t T, int32_t K,
+                              int32_t *out_sorted_pair, int32_t *out_group_off, void *stream);
+
+/* Tuning knobs read by the launch heuristics (0 = automatic).  Host-side, process-wide. */
+int32_t mlora_set_tuning(const char *name, int32_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLORA_H */

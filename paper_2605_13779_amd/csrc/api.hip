@@ -1,0 +1,538 @@
+// C-ABI entry points: validation, slot bookkeeping and launch configuration.  All arithmetic of
+// the LoRA apply runs in the kernels of rows.hip / seg_mfma.hip / plan.hip.
+#include "internal.h"
+
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace mlora;
+
+struct mlora_plan {
+    int32_t max_items, n_keys, device;
+    PlanView pv;
+    // what the last planning call put in it (host-side knowledge only)
+    int32_t items, top_k, n_experts, n_slots, grid_chunks;
+    bool moe;
+};
+
+struct mlora_site {
+    mlora_site_desc d;
+    int32_t r_pad, E;
+    uint16_t *a_tab, *b_tab;
+    int32_t *rank;
+    float *scale;
+    int64_t *catalog;
+    mlora_plan priv;            // private plan living in the caller-provided scratch
+    int32_t *seg_dev;           // device area for segment tiles / chunks
+    int32_t seg_cap;            // in entries of 3 ints
+    int32_t *stage[2];          // pinned host staging for the segment tables (lazy)
+    hipEvent_t stage_ev[2];
+    bool stage_busy[2];
+    int stage_next;
+};
+
+namespace {
+
+constexpr int32_t kDensePrivItems = 8192;      // rows per private dense plan (one-workgroup planner)
+constexpr int32_t kMoePrivItems = 131072;      // pairs per private MoE plan
+constexpr int32_t kSegCap = 65536;             // segment tiles / chunks per call
+
+std::mutex g_tune_mu;
+std::map<std::string, int> g_tune;
+
+int32_t round_pow2(int32_t r)
+{
+    int32_t p = 1;
+    while (p < r) p <<= 1;
+    return p;
+}
+
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+int32_t check_desc(const mlora_site_desc *d)
+{
+    if (!d) return MLORA_E_INVALID;
+    if (d->d_in <= 0 || d->d_out <= 0 || d->n_slots <= 0 || d->n_experts < 0 || d->device < 0) return MLORA_E_INVALID;
+    if (d->r_max < 1 || d->r_max > MLORA_MAX_RANK) return MLORA_E_SHAPE;
+    if ((d->d_in & 7) || (d->d_out & 7)) return MLORA_E_SHAPE;
+    int64_t keys = (int64_t)d->n_slots * (d->n_experts > 0 ? d->n_experts : 1);
+    if (keys > (1 << 24)) return MLORA_E_UNSUPPORTED;
+    return MLORA_OK;
+}
+
+int32_t priv_items(const mlora_site_desc *d) { return d->n_experts > 0 ? kMoePrivItems : kDensePrivItems; }
+
+__global__ void meta_set_kernel(int32_t *rank, float *scale, int64_t *catalog, int slot, int r, float s, int64_t id)
+{
+    rank[slot] = r; scale[slot] = s; catalog[slot] = id;
+}
+
+__global__ void meta_clear_kernel(int32_t *rank, float *scale, int64_t *catalog, int n)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) { rank[i] = 0; scale[i] = 0.f; catalog[i] = -1; }
+}
+
+// Zero the padding of one slot: A rows r..r_pad-1 and B columns r..r_pad-1, for every expert.
+__global__ void pad_zero_kernel(uint16_t *a_slot, uint16_t *b_slot, int E, int r, int r_pad, int d_in, int d_out)
+{
+    const int64_t na = (int64_t)E * (r_pad - r) * d_in, nb = (int64_t)E * d_out * (r_pad - r);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < na + nb; i += (int64_t)gridDim.x * blockDim.x) {
+        if (i < na) {
+            int64_t e = i / ((int64_t)(r_pad - r) * d_in), rem = i % ((int64_t)(r_pad - r) * d_in);
+            a_slot[e * r_pad * d_in + (int64_t)r * d_in + rem] = 0;
+        } else {
+            int64_t k = i - na;
+            int64_t row = k / (r_pad - r), col = k % (r_pad - r);
+            b_slot[row * r_pad + r + col] = 0;
+        }
+    }
+}
+
+bool ok(hipError_t e) { return e == hipSuccess; }
+
+struct DeviceGuard {
+    int prev = -1;
+    bool good = true;
+    explicit DeviceGuard(int dev)
+    {
+        if (!ok(hipGetDevice(&prev))) { good = false; return; }
+        if (prev != dev && !ok(hipSetDevice(dev))) good = false;
+        cur = dev;
+    }
+    ~DeviceGuard() { if (good && prev != cur) (void)hipSetDevice(prev); }
+    int cur = -1;
+};
+
+int rows_tiles(int d_in, int d_out, int r_pad, int grid_chunks)
+{
+    int t = tuning("rows_tiles");
+    const int opl = r_pad >= 8 ? 1 : 8 / r_pad;
+    const int max_tiles = (d_out + 256 * opl - 1) / (256 * opl);
+    if (t <= 0) {
+        t = (2 * d_out + d_in / 2) / d_in;                     // keep the re-done shrink a minority
+        int want = (1024 + grid_chunks - 1) / grid_chunks;     // enough workgroups for 256 CUs
+        if (t > want) t = want;
+    }
+    if (t > max_tiles) t = max_tiles;
+    if (t < 1) t = 1;
+    return t;
+}
+
+int32_t check_xy(const mlora_site *s, const void *x, int64_t ldx, const void *y, int64_t ldy)
+{
+    if (!s || !x || !y) return MLORA_E_INVALID;
+    if (ldx < s->d.d_in || ldy < s->d.d_out || (ldx & 7) || (ldy & 7)) return MLORA_E_SHAPE;
+    if (!aligned16(x) || !aligned16(y)) return MLORA_E_SHAPE;
+    return MLORA_OK;
+}
+
+RowsArgs rows_args(const mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy)
+{
+    RowsArgs a{};
+    a.x = (const uint16_t *)x; a.ldx = ldx; a.y = (uint16_t *)y; a.ldy = ldy;
+    a.a_tab = s->a_tab; a.b_tab = s->b_tab;
+    a.meta.rank = s->rank; a.meta.scale = s->scale;
+    a.d_in = s->d.d_in; a.d_out = s->d.d_out; a.r_pad = s->r_pad;
+    a.n_experts = s->E; a.top_k = 1;
+    return a;
+}
+
+void init_plan(mlora_plan *p, int32_t max_items, int32_t n_keys, int32_t device, void *base)
+{
+    p->max_items = max_items; p->n_keys = n_keys; p->device = device;
+    p->pv = plan_view(base, max_items, n_keys);
+    p->items = 0; p->top_k = 1; p->n_experts = 1; p->n_slots = 0; p->grid_chunks = 0; p->moe = false;
+}
+
+int32_t plan_decode_impl(mlora_plan *plan, const int32_t *token_slot, int32_t T, int32_t n_slots,
+                         const int32_t *ready_rank, hipStream_t st)
+{
+    if (T > plan->max_items || n_slots > plan->n_keys) return MLORA_E_UNSUPPORTED;
+    plan->items = T; plan->top_k = 1; plan->n_experts = 1; plan->n_slots = n_slots; plan->moe = false;
+    plan->grid_chunks = (int32_t)max_chunks(T, n_slots);
+    hipError_t e;
+    if (T <= kDensePrivItems && !tuning("plan_general"))
+        e = launch_plan_dense_small(plan->pv, token_slot, T, n_slots, ready_rank, st);
+    else
+        e = launch_plan_general(plan->pv, nullptr, token_slot, T, 1, 1, n_slots, ready_rank, nullptr, nullptr, st);
+    return ok(e) ? MLORA_OK : MLORA_E_HIP;
+}
+
+int32_t plan_route_impl(mlora_plan *plan, const int32_t *topk, const int32_t *token_slot, int32_t T, int32_t K,
+                        int32_t n_slots, int32_t E, const int32_t *ready_rank,
+                        int32_t *out_sorted, int32_t *out_off, hipStream_t st)
+{
+    const int64_t P = (int64_t)T * K, NK = (int64_t)n_slots * E;
+    if (P > plan->max_items || NK > plan->n_keys) return MLORA_E_UNSUPPORTED;
+    plan->items = (int32_t)P; plan->top_k = K; plan->n_experts = E; plan->n_slots = n_slots; plan->moe = true;
+    plan->grid_chunks = (int32_t)max_chunks(P, NK);
+    hipError_t e = launch_plan_general(plan->pv, topk, token_slot, T, K, E, n_slots, ready_rank, out_sorted, out_off, st);
+    return ok(e) ? MLORA_OK : MLORA_E_HIP;
+}
+
+int32_t apply_planned_impl(mlora_site *s, const mlora_plan *plan, const void *x, int64_t ldx,
+                           void *y, int64_t ldy, hipStream_t st)
+{
+    if (plan->items == 0) return MLORA_OK;
+    RowsArgs a = rows_args(s, x, ldx, y, ldy);
+    a.hdr = plan->pv.hdr; a.chunks = plan->pv.chunks; a.sorted = plan->pv.sorted;
+    a.top_k = plan->top_k;
+    a.grid_chunks = plan->grid_chunks;
+    a.n_tiles = rows_tiles(a.d_in, a.d_out, a.r_pad, a.grid_chunks);
+    return ok(launch_rows(a, st)) ? MLORA_OK : MLORA_E_HIP;
+}
+
+// Copy a small host table to the site's device area through pinned staging (two buffers in turn).
+int32_t stage_table(mlora_site *s, const std::vector<int32_t> &tab, hipStream_t st)
+{
+    const size_t bytes = tab.size() * sizeof(int32_t);
+    const int k = s->stage_next;
+    if (!s->stage[k]) {
+        if (!ok(hipHostMalloc((void **)&s->stage[k], (size_t)kSegCap * 3 * sizeof(int32_t), hipHostMallocDefault))) return MLORA_E_HIP;
+        if (!ok(hipEventCreateWithFlags(&s->stage_ev[k], hipEventDisableTiming))) return MLORA_E_HIP;
+    }
+    if (s->stage_busy[k] && !ok(hipEventSynchronize(s->stage_ev[k]))) return MLORA_E_HIP;
+    std::memcpy(s->stage[k], tab.data(), bytes);
+    if (!ok(hipMemcpyAsync(s->seg_dev, s->stage[k], bytes, hipMemcpyHostToDevice, st))) return MLORA_E_HIP;
+    if (!ok(hipEventRecord(s->stage_ev[k], st))) return MLORA_E_HIP;
+    s->stage_busy[k] = true;
+    s->stage_next = k ^ 1;
+    return MLORA_OK;
+}
+
+}  // namespace
+
+namespace mlora {
+int tuning(const char *name)
+{
+    std::lock_guard<std::mutex> g(g_tune_mu);
+    auto it = g_tune.find(name);
+    return it == g_tune.end() ? 0 : it->second;
+}
+}  // namespace mlora
+
+extern "C" {
+
+const char *mlora_status_str(int32_t st)
+{
+    switch (st) {
+        case MLORA_OK: return "ok";
+        case MLORA_E_INVALID: return "invalid argument";
+        case MLORA_E_SHAPE: return "shape, rank or alignment not supported";
+        case MLORA_E_SLOT: return "slot index out of range";
+        case MLORA_E_SEGMENTS: return "segment offsets malformed";
+        case MLORA_E_HIP: return "HIP runtime error";
+        case MLORA_E_UNSUPPORTED: return "unsupported call for this site or size";
+    }
+    return "unknown status";
+}
+
+int32_t mlora_set_tuning(const char *name, int32_t value)
+{
+    if (!name) return MLORA_E_INVALID;
+    std::lock_guard<std::mutex> g(g_tune_mu);
+    g_tune[name] = value;
+    return MLORA_OK;
+}
+
+int32_t mlora_site_bytes(const mlora_site_desc *d, size_t *a_tab, size_t *b_tab, size_t *meta, size_t *scratch)
+{
+    int32_t rc = check_desc(d);
+    if (rc) return rc;
+    if (!a_tab || !b_tab || !meta || !scratch) return MLORA_E_INVALID;
+    const int64_t E = d->n_experts > 0 ? d->n_experts : 1, rp = round_pow2(d->r_max);
+    *a_tab = align256((size_t)d->n_slots * E * rp * d->d_in * 2);
+    *b_tab = align256((size_t)d->n_slots * E * d->d_out * rp * 2);
+    *meta = align256((size_t)d->n_slots * 16);
+    *scratch = align256(plan_words(priv_items(d), (int64_t)d->n_slots * E) * 4) + align256((size_t)kSegCap * 3 * 4);
+    return MLORA_OK;
+}
+
+int32_t mlora_site_create(const mlora_site_desc *d, void *a_tab, void *b_tab, void *meta, void *scratch, mlora_site **out)
+{
+    int32_t rc = check_desc(d);
+    if (rc) return rc;
+    if (!a_tab || !b_tab || !meta || !scratch || !out) return MLORA_E_INVALID;
+    if (((uintptr_t)a_tab | (uintptr_t)b_tab | (uintptr_t)meta | (uintptr_t)scratch) & 255) return MLORA_E_SHAPE;
+    mlora_site *s = new (std::nothrow) mlora_site();
+    if (!s) return MLORA_E_INVALID;
+    s->d = *d;
+    s->E = d->n_experts > 0 ? d->n_experts : 1;
+    s->r_pad = round_pow2(d->r_max);
+    s->a_tab = (uint16_t *)a_tab; s->b_tab = (uint16_t *)b_tab;
+    s->rank = (int32_t *)meta;
+    s->scale = (float *)((char *)meta + (size_t)d->n_slots * 4);
+    s->catalog = (int64_t *)((char *)meta + (size_t)d->n_slots * 8);
+    const int64_t NK = (int64_t)d->n_slots * s->E;
+    init_plan(&s->priv, priv_items(d), (int32_t)NK, d->device, scratch);
+    s->seg_dev = (int32_t *)((char *)scratch + align256(plan_words(priv_items(d), NK) * 4));
+    s->seg_cap = kSegCap;
+    s->stage[0] = s->stage[1] = nullptr;
+    s->stage_busy[0] = s->stage_busy[1] = false;
+    s->stage_next = 0;
+    DeviceGuard g(d->device);
+    if (!g.good) { delete s; return MLORA_E_HIP; }
+    meta_clear_kernel<<<dim3((d->n_slots + 255) / 256), dim3(256), 0, 0>>>(s->rank, s->scale, s->catalog, d->n_slots);
+    hipError_t e = launch_fill_i32(s->priv.pv.hdr, 0, 8 + 3 * (NK + 1), 0);
+    if (!ok(e) || !ok(hipGetLastError()) || !ok(hipStreamSynchronize(0))) { delete s; return MLORA_E_HIP; }
+    *out = s;
+    return MLORA_OK;
+}
+
+void mlora_site_destroy(mlora_site *s)
+{
+    if (!s) return;
+    for (int k = 0; k < 2; ++k)
+        if (s->stage[k]) {
+            if (s->stage_busy[k]) (void)hipEventSynchronize(s->stage_ev[k]);
+            (void)hipEventDestroy(s->stage_ev[k]);
+            (void)hipHostFree(s->stage[k]);
+        }
+    delete s;
+}
+
+int32_t lora_slots_upload(mlora_site *s, int32_t slot, int64_t catalog_id, const void *A, const void *B,
+                          int32_t r, float alpha, int32_t src_on_device, void *stream)
+{
+    if (!s || !A || !B) return MLORA_E_INVALID;
+    if (slot < 0 || slot >= s->d.n_slots) return MLORA_E_SLOT;
+    if (r < 1 || r > s->d.r_max) return MLORA_E_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    DeviceGuard g(s->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    const int64_t E = s->E, rp = s->r_pad, d_in = s->d.d_in, d_out = s->d.d_out;
+    uint16_t *a_slot = s->a_tab + (int64_t)slot * E * rp * d_in;
+    uint16_t *b_slot = s->b_tab + (int64_t)slot * E * d_out * rp;
+    const hipMemcpyKind kind = src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    // take the slot out of service while its bytes change
+    meta_set_kernel<<<dim3(1), dim3(1), 0, st>>>(s->rank, s->scale, s->catalog, slot, 0, 0.f, -1);
+    if (r < rp) {
+        int64_t n = E * (rp - r) * (d_in + d_out);
+        unsigned blocks = (unsigned)((n + 255) / 256);
+        if (blocks > 4096) blocks = 4096;
+        pad_zero_kernel<<<dim3(blocks), dim3(256), 0, st>>>(a_slot, b_slot, (int)E, r, (int)rp, (int)d_in, (int)d_out);
+    }
+    hipError_t e;
+    if (r == rp) {
+        e = hipMemcpyAsync(a_slot, A, (size_t)E * r * d_in * 2, kind, st);
+        if (ok(e)) e = hipMemcpyAsync(b_slot, B, (size_t)E * d_out * r * 2, kind, st);
+    } else {
+        e = hipMemcpy2DAsync(a_slot, (size_t)rp * d_in * 2, A, (size_t)r * d_in * 2, (size_t)r * d_in * 2, (size_t)E, kind, st);
+        if (ok(e)) e = hipMemcpy2DAsync(b_slot, (size_t)rp * 2, B, (size_t)r * 2, (size_t)r * 2, (size_t)(E * d_out), kind, st);
+    }
+    if (!ok(e)) return MLORA_E_HIP;
+    meta_set_kernel<<<dim3(1), dim3(1), 0, st>>>(s->rank, s->scale, s->catalog, slot, r, alpha / (float)r, catalog_id);
+    return ok(hipGetLastError()) ? MLORA_OK : MLORA_E_HIP;
+}
+
+int32_t lora_slots_evict(mlora_site *s, int32_t slot, void *stream)
+{
+    if (!s) return MLORA_E_INVALID;
+    if (slot < 0 || slot >= s->d.n_slots) return MLORA_E_SLOT;
+    DeviceGuard g(s->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    meta_set_kernel<<<dim3(1), dim3(1), 0, (hipStream_t)stream>>>(s->rank, s->scale, s->catalog, slot, 0, 0.f, -1);
+    return ok(hipGetLastError()) ? MLORA_OK : MLORA_E_HIP;
+}
+
+int32_t mlora_plan_bytes(int32_t max_items, int32_t n_keys, size_t *bytes)
+{
+    if (!bytes || max_items <= 0 || n_keys <= 0) return MLORA_E_INVALID;
+    *bytes = align256(plan_words(max_items, n_keys) * 4);
+    return MLORA_OK;
+}
+
+int32_t mlora_plan_create(int32_t max_items, int32_t n_keys, int32_t device, void *plan_dev, mlora_plan **out)
+{
+    if (!plan_dev || !out || max_items <= 0 || n_keys <= 0 || device < 0) return MLORA_E_INVALID;
+    if ((uintptr_t)plan_dev & 255) return MLORA_E_SHAPE;
+    mlora_plan *p = new (std::nothrow) mlora_plan();
+    if (!p) return MLORA_E_INVALID;
+    init_plan(p, max_items, n_keys, device, plan_dev);
+    DeviceGuard g(device);
+    if (!g.good) { delete p; return MLORA_E_HIP; }
+    hipError_t e = launch_fill_i32(p->pv.hdr, 0, 8 + 3 * ((int64_t)n_keys + 1), 0);
+    if (!ok(e) || !ok(hipStreamSynchronize(0))) { delete p; return MLORA_E_HIP; }
+    *out = p;
+    return MLORA_OK;
+}
+
+void mlora_plan_destroy(mlora_plan *p) { delete p; }
+
+int32_t lora_plan_decode(mlora_plan *plan, const int32_t *token_slot, int32_t T, int32_t n_slots,
+                         const mlora_site *ready_from, void *stream)
+{
+    if (!plan || T < 0 || n_slots <= 0 || (T > 0 && !token_slot)) return MLORA_E_INVALID;
+    if (ready_from && ready_from->d.n_slots < n_slots) return MLORA_E_SLOT;
+    if (T == 0) { plan->items = 0; plan->grid_chunks = 0; plan->moe = false; return MLORA_OK; }
+    DeviceGuard g(plan->device);
+    if (!g.good) return MLORA_E_HIP;
+    return plan_decode_impl(plan, token_slot, T, n_slots, ready_from ? ready_from->rank : nullptr, (hipStream_t)stream);
+}
+
+int32_t lora_apply_decode_planned(mlora_site *s, const mlora_plan *plan, const void *x, int64_t ldx,
+                                  void *y, int64_t ldy, void *stream)
+{
+    if (!s || !plan) return MLORA_E_INVALID;
+    if (s->d.n_experts > 0 || plan->moe) return MLORA_E_UNSUPPORTED;
+    if (plan->items == 0) return MLORA_OK;
+    int32_t rc = check_xy(s, x, ldx, y, ldy);
+    if (rc) return rc;
+    if (plan->n_slots > s->d.n_slots) return MLORA_E_SLOT;
+    DeviceGuard g(s->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    return apply_planned_impl(s, plan, x, ldx, y, ldy, (hipStream_t)stream);
+}
+
+int32_t moe_plan_route(mlora_plan *plan, const int32_t *topk_ids, const int32_t *token_slot, int32_t T, int32_t K,
+                       int32_t n_slots, int32_t n_experts, const mlora_site *ready_from,
+                       int32_t *out_sorted_pair, int32_t *out_group_off, void *stream)
+{
+    if (!plan || T < 0 || K <= 0 || n_slots <= 0 || n_experts <= 0) return MLORA_E_INVALID;
+    if (T > 0 && (!topk_ids || !token_slot)) return MLORA_E_INVALID;
+    if (ready_from && ready_from->d.n_slots < n_slots) return MLORA_E_SLOT;
+    DeviceGuard g(plan->device);
+    if (!g.good) return MLORA_E_HIP;
+    hipStream_t st = (hipStream_t)stream;
+    if (T == 0) {
+        plan->items = 0; plan->grid_chunks = 0; plan->moe = true;
+        if (out_group_off && !ok(launch_fill_i32(out_group_off, 0, (int64_t)n_slots * n_experts + 1, st))) return MLORA_E_HIP;
+        return MLORA_OK;
+    }
+    return plan_route_impl(plan, topk_ids, token_slot, T, K, n_slots, n_experts,
+                           ready_from ? ready_from->rank : nullptr, out_sorted_pair, out_group_off, st);
+}
+
+int32_t moe_lora_apply_planned(mlora_site *s, const mlora_plan *plan, const void *x, int64_t ldx,
+                               void *y, int64_t ldy, void *stream)
+{
+    if (!s || !plan) return MLORA_E_INVALID;
+    if (s->d.n_experts <= 0 || !plan->moe) return MLORA_E_UNSUPPORTED;
+    if (plan->items == 0) return MLORA_OK;
+    if (plan->n_experts != s->d.n_experts || plan->n_slots > s->d.n_slots) return MLORA_E_SHAPE;
+    int32_t rc = check_xy(s, x, ldx, y, ldy);
+    if (rc) return rc;
+    DeviceGuard g(s->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    return apply_planned_impl(s, plan, x, ldx, y, ldy, (hipStream_t)stream);
+}
+
+int32_t lora_apply_decode(mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy,
+                          const int32_t *token_slot, int32_t T, void *stream)
+{
+    if (!s || T < 0) return MLORA_E_INVALID;
+    if (s->d.n_experts > 0) return MLORA_E_UNSUPPORTED;
+    if (T == 0) return MLORA_OK;
+    if (!token_slot) return MLORA_E_INVALID;
+    int32_t rc = check_xy(s, x, ldx, y, ldy);
+    if (rc) return rc;
+    DeviceGuard g(s->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    hipStream_t st = (hipStream_t)stream;
+    // batches beyond the private plan are processed in slices; rows are independent
+    for (int32_t t0 = 0; t0 < T; t0 += s->priv.max_items) {
+        const int32_t n = T - t0 < s->priv.max_items ? T - t0 : s->priv.max_items;
+        rc = plan_decode_impl(&s->priv, token_slot + t0, n, s->d.n_slots, s->rank, st);
+        if (rc) return rc;
+        rc = apply_planned_impl(s, &s->priv, (const uint16_t *)x + (int64_t)t0 * ldx, ldx,
+                                (uint16_t *)y + (int64_t)t0 * ldy, ldy, st);
+        if (rc) return rc;
+    }
+    return MLORA_OK;
+}
+
+int32_t lora_apply_segmented(mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy,
+                             const int32_t *seg_off, const int32_t *seg_slot, int32_t S, int32_t T, void *stream)
+{
+    if (!s || S < 0 || T < 0) return MLORA_E_INVALID;
+    if (s->d.n_experts > 0) return MLORA_E_UNSUPPORTED;
+    if (S == 0) return T == 0 ? MLORA_OK : MLORA_E_SEGMENTS;
+    if (!seg_off || !seg_slot) return MLORA_E_INVALID;
+    if (seg_off[0] != 0 || seg_off[S] != T) return MLORA_E_SEGMENTS;
+    for (int32_t k = 0; k < S; ++k) {
+        if (seg_off[k + 1] < seg_off[k]) return MLORA_E_SEGMENTS;
+        if (seg_slot[k] < -1 || seg_slot[k] >= s->d.n_slots) return MLORA_E_SLOT;
+    }
+    if (T == 0) return MLORA_OK;
+    int32_t rc = check_xy(s, x, ldx, y, ldy);
+    if (rc) return rc;
+    DeviceGuard g(s->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    hipStream_t st = (hipStream_t)stream;
+
+    const bool mfma = s->r_pad == 64 && (s->d.d_in & 15) == 0 && !tuning("seg_no_mfma");
+    const int rows_per = mfma ? 32 : kChunk;
+    std::vector<int32_t> tab;
+    for (int32_t k = 0; k < S; ++k) {
+        if (seg_slot[k] < 0) continue;
+        for (int32_t r0 = seg_off[k]; r0 < seg_off[k + 1]; r0 += rows_per) {
+            const int32_t n = seg_off[k + 1] - r0 < rows_per ? seg_off[k + 1] - r0 : rows_per;
+            tab.push_back(seg_slot[k]); tab.push_back(r0); tab.push_back(n);
+        }
+    }
+    const int32_t n_units = (int32_t)(tab.size() / 3);
+    if (n_units == 0) return MLORA_OK;
+    if (n_units + 1 > s->seg_cap) return MLORA_E_UNSUPPORTED;
+    if (!mfma) { tab.push_back(n_units); tab.push_back(0); tab.push_back(0); }   // header word after the chunks
+    rc = stage_table(s, tab, st);
+    if (rc) return rc;
+    if (mfma) {
+        SegArgs a{};
+        a.x = (const uint16_t *)x; a.ldx = ldx; a.y = (uint16_t *)y; a.ldy = ldy;
+        a.a_tab = s->a_tab; a.b_tab = s->b_tab; a.meta.rank = s->rank; a.meta.scale = s->scale;
+        a.tiles = s->seg_dev; a.n_tiles = n_units; a.d_in = s->d.d_in; a.d_out = s->d.d_out;
+        return ok(launch_seg_mfma(a, st)) ? MLORA_OK : MLORA_E_HIP;
+    }
+    RowsArgs a = rows_args(s, x, ldx, y, ldy);
+    a.hdr = s->seg_dev + 3 * (int64_t)n_units; a.chunks = s->seg_dev; a.sorted = nullptr;
+    a.grid_chunks = n_units;
+    a.n_tiles = rows_tiles(a.d_in, a.d_out, a.r_pad, n_units);
+    return ok(launch_rows(a, st)) ? MLORA_OK : MLORA_E_HIP;
+}
+
+int32_t moe_lora_apply_packed(mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy,
+                              const int32_t *topk_ids, const int32_t *token_slot, int32_t T, int32_t K,
+                              int32_t *out_sorted_pair, int32_t *out_group_off, void *stream)
+{
+    if (!s || T < 0 || K <= 0) return MLORA_E_INVALID;
+    if (s->d.n_experts <= 0) return MLORA_E_UNSUPPORTED;
+    DeviceGuard g(s->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    hipStream_t st = (hipStream_t)stream;
+    if (T == 0) {
+        if (out_group_off && !ok(launch_fill_i32(out_group_off, 0, (int64_t)s->d.n_slots * s->E + 1, st))) return MLORA_E_HIP;
+        return MLORA_OK;
+    }
+    if (!topk_ids || !token_slot) return MLORA_E_INVALID;
+    int32_t rc = check_xy(s, x, ldx, y, ldy);
+    if (rc) return rc;
+    const int64_t P = (int64_t)T * K;
+    if (P > s->priv.max_items) {
+        if (out_sorted_pair || out_group_off) return MLORA_E_UNSUPPORTED;   // indices are per call, not per slice
+        const int32_t tok_per = s->priv.max_items / K;
+        if (tok_per < 1) return MLORA_E_UNSUPPORTED;
+        for (int32_t t0 = 0; t0 < T; t0 += tok_per) {
+            const int32_t n = T - t0 < tok_per ? T - t0 : tok_per;
+            rc = plan_route_impl(&s->priv, topk_ids + (int64_t)t0 * K, token_slot + t0, n, K, s->d.n_slots, s->E,
+                                 s->rank, nullptr, nullptr, st);
+            if (rc) return rc;
+            rc = apply_planned_impl(s, &s->priv, (const uint16_t *)x + (int64_t)t0 * ldx, ldx,
+                                    (uint16_t *)y + (int64_t)t0 * K * ldy, ldy, st);
+            if (rc) return rc;
+        }
+        return MLORA_OK;
+    }
+    rc = plan_route_impl(&s->priv, topk_ids, token_slot, T, K, s->d.n_slots, s->E, s->rank,
+                         out_sorted_pair, out_group_off, st);
+    if (rc) return rc;
+    return apply_planned_impl(s, &s->priv, x, ldx, y, ldy, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,113 @@
+// Internal declarations shared by the mlora translation units (host launchers + device helpers).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/mlora.h"
+
+namespace mlora {
+
+constexpr int kChunk = MLORA_CHUNK;
+
+// Device view of a site's metadata block: rank | scale | catalog_id.
+struct MetaView {
+    const int32_t *rank;
+    const float   *scale;
+};
+
+// Device view of a plan buffer (all int32).  A chunk is (key, start, count): `count` rows
+// sorted[start .. start+count) all belong to group `key` (dense: slot; MoE: slot*E + expert).
+struct PlanView {
+    int32_t *hdr;         // [8]  hdr[0] = number of chunks, hdr[1] = number of usable rows
+    int32_t *count;       // [n_keys + 1]  zero between calls
+    int32_t *group_off;   // [n_keys + 1]
+    int32_t *chunk_base;  // [n_keys + 1]
+    int32_t *key_of;      // [max_items]
+    int32_t *ticket;      // [max_items]
+    int32_t *tmp;         // [max_items]
+    int32_t *sorted;      // [max_items]
+    int32_t *chunks;      // [3 * max_chunks]
+};
+
+size_t plan_words(int64_t max_items, int64_t n_keys);
+PlanView plan_view(void *base, int64_t max_items, int64_t n_keys);
+inline int64_t max_chunks(int64_t items, int64_t n_keys)
+{
+    int64_t touched = n_keys < items ? n_keys : items;
+    int64_t bound = touched + items / kChunk + 1;
+    return bound < items ? bound : items;
+}
+
+// plan.hip
+hipError_t launch_plan_dense_small(const PlanView &pv, const int32_t *token_slot, int T, int n_slots,
+                                   const int32_t *ready_rank, hipStream_t st);
+hipError_t launch_plan_general(const PlanView &pv, const int32_t *topk, const int32_t *token_slot,
+                               int T, int K, int E, int n_slots, const int32_t *ready_rank,
+                               int32_t *out_sorted, int32_t *out_group_off, hipStream_t st);
+hipError_t launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t st);
+
+// rows.hip: vector-ALU apply over plan chunks (decode, MoE, small-rank segmented)
+struct RowsArgs {
+    const uint16_t *x; int64_t ldx;
+    uint16_t *y;       int64_t ldy;
+    const uint16_t *a_tab; const uint16_t *b_tab;
+    MetaView meta;
+    const int32_t *hdr;      // plan header (hdr[0] = live chunks)
+    const int32_t *chunks;
+    const int32_t *sorted;   // null = identity (row index == sorted position)
+    int32_t d_in, d_out, r_pad;
+    int32_t n_experts;       // >= 1: key / n_experts = slot
+    int32_t top_k;           // x row = item / top_k
+    int32_t grid_chunks;     // upper bound on the number of chunks (launch width)
+    int32_t n_tiles;         // d_out splits
+};
+hipError_t launch_rows(const RowsArgs &a, hipStream_t st);
+
+// seg_mfma.hip: rank-64 segmented apply on the matrix cores
+struct SegArgs {
+    const uint16_t *x; int64_t ldx;
+    uint16_t *y;       int64_t ldy;
+    const uint16_t *a_tab; const uint16_t *b_tab;
+    MetaView meta;
+    const int32_t *tiles;    // [3 * n_tiles]: slot, first row, rows (<= 32)
+    int32_t n_tiles;
+    int32_t d_in, d_out;
+};
+hipError_t launch_seg_mfma(const SegArgs &a, hipStream_t st);
+
+int tuning(const char *name);   // api.hip
+
+}  // namespace mlora
+
+#ifdef __HIPCC__
+namespace mlora {
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+__device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// fp32 -> bf16 bits, round to nearest even; NaN stays NaN.
+__device__ __forceinline__ uint32_t f2bf(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) { return f2bf(lo) | (f2bf(hi) << 16); }
+
+// a.lo*b.lo + a.hi*b.hi + c on packed bf16 pairs, fp32 accumulate (v_dot2c_f32_bf16).
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
+                                           __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+__device__ __forceinline__ float dot8(const uint4 &a, const uint4 &b, float c)
+{
+    c = dot2(a.x, b.x, c); c = dot2(a.y, b.y, c); c = dot2(a.z, b.z, c); c = dot2(a.w, b.w, c);
+    return c;
+}
+
+}  // namespace mlora
+#endif

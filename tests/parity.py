@@ -1,0 +1,59 @@
+"""Comparison rules shared by the GPU parity tests (not a test module itself).
+
+Floating point: |y_gpu - y_ref| <= 2e-2 + 2e-2 * |y_ref| elementwise against the fp64 oracle
+(bf16 in / fp32 accumulate).  Because an N(0, 0.02) adapter can move y by less than that
+tolerance, three guards keep the check from passing vacuously: rows without an adapter must be
+bit-identical, the run is repeated with y0 = 0 where the output is the LoRA delta alone and must
+match to bf16 precision, and the unchanged y0 itself must FAIL the same check.
+"""
+import numpy as np
+import torch
+
+ATOL, RTOL = 2e-2, 2e-2
+
+
+def dev_bf16(bits, device="cuda:0"):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(device)
+
+
+def host_bits(t):
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def widen(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def check_close(got_bits, ref, what=""):
+    got = widen(got_bits)
+    err = np.abs(got - ref)
+    bad = err > ATOL + RTOL * np.abs(ref)
+    assert not bad.any(), (f"{what}: {int(bad.sum())} of {bad.size} elements outside 2e-2 + 2e-2|ref|; "
+                           f"max abs err {err.max():.4g}")
+    return float(err.max()), float((err / np.maximum(np.abs(ref), 1e-30)).max())
+
+
+def check_delta(got_bits, delta_ref, what=""):
+    """y0 = 0 run: the output is the LoRA delta, rounded once to bf16."""
+    got = widen(got_bits)
+    rms = float(np.sqrt(np.mean(delta_ref ** 2))) if delta_ref.size else 0.0
+    err = np.abs(got - delta_ref)
+    bad = err > 2.0 ** -7 * np.abs(delta_ref) + 1e-3 * rms
+    assert not bad.any(), (f"{what}: {int(bad.sum())} of {bad.size} delta elements off; max err {err.max():.4g}, rms {rms:.4g}")
+    return rms
+
+
+def check_untouched(got_bits, y0_bits, rows, what=""):
+    assert np.array_equal(got_bits[rows], y0_bits[rows]), f"{what}: rows without an adapter changed"
+
+
+def noop_must_fail(y0_bits, delta_ref, touched_rows):
+    """The y0 = 0 delta check must reject an implementation that does nothing."""
+    if len(touched_rows) == 0:
+        return
+    z = np.zeros_like(y0_bits)
+    try:
+        check_delta(z[touched_rows], delta_ref[touched_rows])
+    except AssertionError:
+        return
+    raise AssertionError("delta check would accept a no-op kernel")

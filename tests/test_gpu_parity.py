@@ -1,0 +1,337 @@
+"""HIP path vs the fp64 oracle, element by element, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from tests import parity as P
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(300)]
+
+
+@pytest.fixture(scope="module")
+def M():
+    import paper_2605_13779_amd as m
+    m.load_library()
+    return m
+
+
+def upload_all(M, site, c, ranks=None):
+    """Upload every slot in its true (unpadded) PEFT shape."""
+    for s in range(c.n_slots):
+        r = int(c.rank[s])
+        if r == 0:
+            continue
+        A = np.ascontiguousarray(c.A[s][..., :r, :])
+        B = np.ascontiguousarray(c.B[s][..., :, :r])
+        M.lora_slots_upload(site, s, int(c.catalog_id[s]) if getattr(c, "catalog_id", None) is not None else s,
+                            A, B, r, float(c.alpha[s]))
+    torch.cuda.synchronize()
+
+
+def dense_site(M, c):
+    site = M.Site(c.d_in, c.d_out, c.r_max, c.n_slots)
+    upload_all(M, site, c)
+    return site
+
+
+def run_decode(M, site, c, y0_bits, planned=False):
+    x, y = P.dev_bf16(c.x), P.dev_bf16(y0_bits)
+    ts = torch.from_numpy(c.token_slot).cuda()
+    if planned:
+        plan = M.Plan(max(c.T, 1), c.n_slots)
+        M.lora_plan_decode(plan, ts, c.n_slots)
+        M.lora_apply_decode_planned(site, plan, x, y)
+    else:
+        M.lora_apply_decode(site, x, y, ts)
+    torch.cuda.synchronize()
+    return P.host_bits(y)
+
+
+def check_dense(M, oracle, c, runner, rows=None):
+    """Full comparison + the three vacuity guards.  rows: optional subset of rows sent to the oracle."""
+    sel = np.arange(c.T) if rows is None else np.asarray(rows)
+    ref = oracle.apply_decode(c.x[sel], c.y0[sel], c.A, c.B, c.rank, c.alpha, c.token_slot[sel])
+    got = runner(c.y0)
+    P.check_close(got[sel], ref, c.name)
+    eff = np.array([s >= 0 and c.rank[s] > 0 for s in c.token_slot])
+    P.check_untouched(got, c.y0, ~eff, c.name)
+    zero = np.zeros_like(c.y0)
+    dref = oracle.apply_decode(c.x[sel], zero[sel], c.A, c.B, c.rank, c.alpha, c.token_slot[sel])
+    gz = runner(zero)
+    P.check_delta(gz[sel], dref, c.name + " delta")
+    P.noop_must_fail(c.y0[sel], dref, np.nonzero(eff[sel])[0])
+
+
+# ------------------------------------------------------------------ decode
+
+def test_c1_tiny_decode(M, oracle):
+    c = W.c1_tiny_decode()
+    site = dense_site(M, c)
+    check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0))
+    check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0, planned=True))
+
+
+@pytest.mark.parametrize("r", [1, 2, 4, 8, 16, 32, 64])
+def test_decode_all_ranks_ragged(M, oracle, r):
+    """Several d_out tiles, a ragged tail (d_out = 1064 is not a multiple of the pass width),
+    -1 rows, groups larger than one chunk."""
+    c = W.dense_case(f"rag_r{r}", 1000 + r, 77, 328, 1064, 5, r, 2.0 * r, std_a=0.05, std_b=0.05)
+    site = dense_site(M, c)
+    check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0))
+
+
+def test_decode_mixed_ranks_padding_and_empty_slots(M, oracle):
+    ranks = [3, 16, 0, 7, 1, 12]
+    c = W.dense_case("mixed", 2001, 90, 256, 512, 6, 16, 24.0, ranks=ranks, std_a=0.05, std_b=0.05)
+    site = dense_site(M, c)
+    rank, scale, cat = site.meta()
+    assert rank.tolist() == ranks
+    np.testing.assert_allclose(scale[[0, 1, 3]], [24 / 3, 24 / 16, 24 / 7], rtol=1e-6)
+    check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0))
+    # evicting a slot turns its rows into no-ops; re-uploading with a smaller rank must clear the padding
+    M.lora_slots_evict(site, 1)
+    c2 = W.dense_case("mixed", 2001, 90, 256, 512, 6, 16, 24.0, ranks=[3, 0, 0, 7, 1, 12], std_a=0.05, std_b=0.05)
+    check_dense(M, oracle, c2, lambda y0: run_decode(M, site, c2, y0))
+    c3 = W.dense_case("mixed", 2001, 90, 256, 512, 6, 16, 24.0, ranks=[3, 5, 0, 7, 1, 12], std_a=0.05, std_b=0.05)
+    M.lora_slots_upload(site, 1, 77, np.ascontiguousarray(c3.A[1][:5]), np.ascontiguousarray(c3.B[1][:, :5]), 5, 24.0)
+    check_dense(M, oracle, c3, lambda y0: run_decode(M, site, c3, y0))
+    assert site.meta()[2][1] == 77
+
+
+def test_decode_edge_cases(M, oracle):
+    c = W.dense_case("edge", 3001, 40, 64, 64, 4, 8, 16.0, std_a=0.1, std_b=0.1)
+    site = dense_site(M, c)
+    # all rows without an adapter
+    c.token_slot[:] = -1
+    got = run_decode(M, site, c, c.y0)
+    assert np.array_equal(got, c.y0)
+    # every row on one slot (one big group)
+    c.token_slot[:] = 2
+    check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0))
+    # out-of-range indices are treated like -1
+    c.token_slot[::5] = 9
+    c.token_slot[1::5] = -7
+    got = run_decode(M, site, c, c.y0)
+    bad = (c.token_slot < 0) | (c.token_slot >= 4)
+    assert np.array_equal(got[bad], c.y0[bad])
+    # T = 0
+    x0 = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    M.lora_apply_decode(site, x0, x0.clone(), torch.empty(0, dtype=torch.int32, device="cuda"))
+    # single row
+    c1 = W.dense_case("one", 3002, 1, 64, 64, 4, 8, 16.0, std_a=0.1, std_b=0.1, token_slot=[3])
+    upload_all(M, site, c1)
+    check_dense(M, oracle, c1, lambda y0: run_decode(M, site, c1, y0))
+
+
+def test_decode_strided_rows(M, oracle):
+    """x and y as column slices of wider buffers (row stride != width)."""
+    c = W.dense_case("stride", 3003, 33, 128, 256, 3, 8, 16.0, std_a=0.05, std_b=0.05)
+    site = dense_site(M, c)
+    xb = torch.zeros((c.T, 200), dtype=torch.bfloat16, device="cuda")
+    yb = torch.zeros((c.T, 320), dtype=torch.bfloat16, device="cuda")
+    xb[:, 8:136] = P.dev_bf16(c.x)
+    yb[:, 16:272] = P.dev_bf16(c.y0)
+    guard = yb.clone()
+    M.lora_apply_decode(site, xb[:, 8:136], yb[:, 16:272], torch.from_numpy(c.token_slot).cuda())
+    torch.cuda.synchronize()
+    ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+    P.check_close(P.host_bits(yb[:, 16:272]), ref, "strided")
+    assert torch.equal(yb[:, :16], guard[:, :16]) and torch.equal(yb[:, 272:], guard[:, 272:])
+
+
+def test_decode_large_batch_general_planner(M, oracle):
+    """More rows than the one-workgroup planner takes: the histogram/scan/scatter pipeline."""
+    c = W.dense_case("big", 3004, 2500, 64, 96, 37, 4, 8.0, std_a=0.1, std_b=0.1)
+    site = dense_site(M, c)
+    M.set_tuning("plan_general", 1)
+    try:
+        check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0))
+    finally:
+        M.set_tuning("plan_general", 0)
+    check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0))
+
+
+def test_c2_dense_decode_layer(M, oracle):
+    cases = W.c2_dense_decode()
+    ts = torch.from_numpy(cases[0].token_slot).cuda()
+    plan = M.Plan(256, 64)
+    M.lora_plan_decode(plan, ts, 64)
+    sample = W.rng(77).permutation(256)[:48]
+    for c in cases:
+        site = dense_site(M, c)
+
+        def runner(y0, site=site, c=c):
+            x, y = P.dev_bf16(c.x), P.dev_bf16(y0)
+            M.lora_apply_decode_planned(site, plan, x, y)
+            torch.cuda.synchronize()
+            return P.host_bits(y)
+        check_dense(M, oracle, c, runner, rows=sample)
+        site.close()
+
+
+def test_c3_rank1_catalog(M, oracle):
+    c = W.c3_rank1_catalog()
+    site = dense_site(M, c)
+    check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0))
+    assert np.array_equal(site.meta()[2], c.catalog_id)
+
+
+# ------------------------------------------------------------------ segmented
+
+def run_seg(M, site, c, y0_bits, seg_off=None, seg_slot=None):
+    x, y = P.dev_bf16(c.x), P.dev_bf16(y0_bits)
+    M.lora_apply_segmented(site, x, y, c.seg_off if seg_off is None else seg_off,
+                           c.seg_slot if seg_slot is None else seg_slot)
+    torch.cuda.synchronize()
+    return P.host_bits(y)
+
+
+@pytest.mark.parametrize("r,d_in,d_out", [(64, 208, 328), (64, 1024, 520), (16, 200, 264), (4, 64, 72)])
+def test_segmented_small(M, oracle, r, d_in, d_out):
+    """Segments that are shorter than, equal to and longer than a tile, an empty segment, a
+    segment without adapter; d_out with a ragged last block."""
+    seg_off = [0, 1, 33, 33, 100, 132, 140, 205]
+    seg_slot = [0, 1, 2, 1, -1, 3, 0]
+    c = W.seg_case(f"seg_r{r}", 4000 + r + d_in, 205, 7, d_in, d_out, 4, r, 2.0 * r,
+                   seg_off=seg_off, seg_slot=seg_slot, std_a=0.05, std_b=0.05)
+    site = dense_site(M, c)
+    check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0))
+    # the decode path on the same rows must agree with the segmented path to the same bar
+    a = run_seg(M, site, c, c.y0)
+    b = run_decode(M, site, c, c.y0)
+    ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+    P.check_close(a, ref, "seg")
+    P.check_close(b, ref, "dec")
+
+
+def test_segmented_rejects_bad_offsets(M):
+    site = M.Site(64, 64, 64, 2)
+    x = torch.zeros((10, 64), dtype=torch.bfloat16, device="cuda")
+    for off, sl, code in [([0, 6, 4, 10], [0, 1, 0], -4), ([0, 4, 9], [0, 1], -4), ([1, 4, 10], [0, 1], -4),
+                          ([0, 4, 10], [0, 2], -3)]:
+        with pytest.raises(M.MLoraError) as e:
+            M.lora_apply_segmented(site, x, x.clone(), off, sl)
+        assert e.value.status == code
+
+
+def test_c5_segmented_sampled(M, oracle):
+    """Full-size prefill (both widths); the oracle checks a sample of rows that covers every
+    segment's first and last row."""
+    for wide in (False, True):
+        c = W.c5_segmented(wide)
+        site = dense_site(M, c)
+        rows = set(W.rng(5).permutation(c.T)[:40].tolist())
+        for k in range(16):
+            rows.add(int(c.seg_off[k]))
+            rows.add(int(c.seg_off[k + 1] - 1))
+        rows = np.array(sorted(rows))
+        check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0), rows=rows)
+        site.close()
+        del site
+        torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ MoE
+
+def moe_site(M, c):
+    site = M.Site(c.d_in, c.d_out, c.r_max, c.n_slots, n_experts=c.E)
+    upload_all(M, site, c)
+    return site
+
+
+def run_moe(M, site, c, y0_bits, want_idx=True):
+    x, y = P.dev_bf16(c.x), P.dev_bf16(y0_bits)
+    topk, ts = torch.from_numpy(c.topk).cuda(), torch.from_numpy(c.token_slot).cuda()
+    sp = torch.full((c.T * c.K,), -5, dtype=torch.int32, device="cuda") if want_idx else None
+    go = torch.full((c.n_slots * c.E + 1,), -5, dtype=torch.int32, device="cuda") if want_idx else None
+    M.moe_lora_apply_packed(site, x, y, topk, ts, sp, go)
+    torch.cuda.synchronize()
+    return P.host_bits(y), (sp.cpu().numpy() if want_idx else None), (go.cpu().numpy() if want_idx else None)
+
+
+def check_moe(M, oracle, c, site, pairs=None):
+    sel = np.arange(c.T * c.K) if pairs is None else np.asarray(pairs)
+    got, sp, go = run_moe(M, site, c, c.y0)
+    rsp, rgo = oracle.route_sort(c.topk, c.token_slot, c.rank, c.E)
+    assert np.array_equal(go, rgo), "group offsets differ"
+    assert np.array_equal(sp, rsp), "sorted pairs differ"
+    # oracle on the selected pairs: one-token-per-pair view of the same computation
+    tok = sel // c.K
+    sub_topk = c.topk.reshape(-1)[sel].reshape(-1, 1)
+    ref = oracle.apply_moe(c.x[tok], c.y0[sel], c.A, c.B, c.rank, c.alpha, sub_topk, c.token_slot[tok])
+    P.check_close(got[sel], ref, c.name)
+    eff = np.repeat(np.array([s >= 0 and c.rank[s] > 0 for s in c.token_slot]), c.K)
+    P.check_untouched(got, c.y0, ~eff, c.name)
+    zero = np.zeros_like(c.y0)
+    dref = oracle.apply_moe(c.x[tok], zero[sel], c.A, c.B, c.rank, c.alpha, sub_topk, c.token_slot[tok])
+    gz, _, _ = run_moe(M, site, c, zero, want_idx=False)
+    P.check_delta(gz[sel], dref, c.name + " delta")
+    P.noop_must_fail(c.y0[sel], dref, np.nonzero(eff[sel])[0])
+
+
+@pytest.mark.parametrize("T,K,E,S,r", [(37, 2, 4, 3, 8), (200, 4, 16, 5, 4), (64, 8, 8, 2, 16), (9, 1, 1, 2, 2)])
+def test_moe_small(M, oracle, T, K, E, S, r):
+    c = W.moe_case(f"moe_{T}_{K}_{E}", 5000 + T, T, K, E, 136, 200, S, r, 2.0 * r, std_a=0.05, std_b=0.05)
+    c.token_slot[::7] = -1
+    site = moe_site(M, c)
+    check_moe(M, oracle, c, site)
+
+
+def test_moe_empty_slot_and_single_adapter(M, oracle):
+    c = W.moe_case("moe_one", 5100, 300, 4, 8, 64, 96, 3, 4, 8.0, ranks=[4, 0, 2],
+                   token_slot=np.full(300, 0, dtype=np.int32), std_a=0.1, std_b=0.1)
+    site = moe_site(M, c)
+    check_moe(M, oracle, c, site)          # every pair on one adapter: groups of ~150 pairs
+    c.token_slot[::2] = 1                  # half the tokens point at a slot that never became ready
+    c.token_slot[1::4] = 2
+    check_moe(M, oracle, c, site)
+
+
+def test_moe_planned_reuse(M, oracle):
+    """One route plan shared by two sites (gate and up share the routing)."""
+    ca = W.moe_case("gate", 5200, 120, 4, 8, 128, 64, 4, 8, 16.0, std_a=0.05, std_b=0.05)
+    cb = W.moe_case("up", 5201, 120, 4, 8, 128, 64, 4, 8, 16.0, std_a=0.05, std_b=0.05)
+    cb.topk, cb.token_slot = ca.topk, ca.token_slot
+    plan = M.Plan(120 * 4, 4 * 8)
+    topk, ts = torch.from_numpy(ca.topk).cuda(), torch.from_numpy(ca.token_slot).cuda()
+    M.moe_plan_route(plan, topk, ts, 4, 8)
+    for c in (ca, cb):
+        site = moe_site(M, c)
+        x, y = P.dev_bf16(c.x), P.dev_bf16(c.y0)
+        M.moe_lora_apply_planned(site, plan, x, y)
+        torch.cuda.synchronize()
+        ref = oracle.apply_moe(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, c.token_slot)
+        P.check_close(P.host_bits(y), ref, c.name)
+
+
+def test_c4_moe_packed_sampled(M, oracle):
+    c = W.c4_moe_packed("gate")
+    site = moe_site(M, c)
+    pairs = np.sort(W.rng(6).permutation(c.T * c.K)[:512])
+    check_moe(M, oracle, c, site, pairs=pairs)
+
+
+# ------------------------------------------------------------------ ABI errors on the device box
+
+def test_abi_error_codes(M):
+    with pytest.raises(M.MLoraError) as e:
+        M.Site(100, 64, 8, 2)                       # d_in not a multiple of 8
+    assert e.value.status == -2
+    with pytest.raises(M.MLoraError) as e:
+        M.Site(64, 64, 65, 2)
+    assert e.value.status == -2
+    site = M.Site(64, 64, 8, 2)
+    A = np.zeros((9, 64), np.uint16)
+    B = np.zeros((64, 9), np.uint16)
+    with pytest.raises(M.MLoraError) as e:
+        M.lora_slots_upload(site, 0, 0, A, B, 9, 1.0)
+    assert e.value.status == -2
+    with pytest.raises(M.MLoraError) as e:
+        M.lora_slots_upload(site, 2, 0, A[:8], B[:, :8].copy(), 8, 1.0)
+    assert e.value.status == -3
+    moe = M.Site(64, 64, 8, 2, n_experts=2)
+    x = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(M.MLoraError) as e:
+        M.lora_apply_decode(moe, x, x.clone(), torch.zeros(4, dtype=torch.int32, device="cuda"))
+    assert e.value.status == -6
