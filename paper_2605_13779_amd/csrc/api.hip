@@ -141,6 +141,7 @@ RowsArgs rows_args(const mlora_site *s, const void *x, int64_t ldx, void *y, int
     a.meta.rank = s->rank; a.meta.scale = s->scale;
     a.d_in = s->d.d_in; a.d_out = s->d.d_out; a.r_pad = s->r_pad;
     a.n_experts = s->E; a.top_k = 1;
+    a.prof = debug_prof();
     return a;
 }
 
@@ -182,7 +183,7 @@ int32_t apply_planned_impl(mlora_site *s, const mlora_plan *plan, const void *x,
 {
     if (plan->items == 0) return MLORA_OK;
     RowsArgs a = rows_args(s, x, ldx, y, ldy);
-    a.hdr = plan->pv.hdr; a.chunks = plan->pv.chunks; a.sorted = plan->pv.sorted;
+    a.hdr = plan->pv.hdr; a.chunks = plan->pv.chunks;
     a.top_k = plan->top_k;
     a.grid_chunks = plan->grid_chunks;
     a.n_tiles = rows_tiles(a.d_in, a.d_out, a.r_pad, a.grid_chunks);
@@ -209,7 +210,9 @@ int32_t stage_table(mlora_site *s, const std::vector<int32_t> &tab, hipStream_t 
 
 }  // namespace
 
+static uint64_t *g_prof = nullptr;
 namespace mlora {
+uint64_t *debug_prof() { return g_prof; }
 int tuning(const char *name)
 {
     std::lock_guard<std::mutex> g(g_tune_mu);
@@ -219,6 +222,10 @@ int tuning(const char *name)
 }  // namespace mlora
 
 extern "C" {
+
+// Debug hook (not part of the public header): device buffer that receives per-workgroup
+// phase timestamps of the vector kernel, 8 x uint64 per workgroup; null switches it off.
+void mlora_debug_set_prof(void *dev) { g_prof = (uint64_t *)dev; }
 
 const char *mlora_status_str(int32_t st)
 {
@@ -469,18 +476,24 @@ int32_t lora_apply_segmented(mlora_site *s, const void *x, int64_t ldx, void *y,
 
     const bool mfma = s->r_pad == 64 && (s->d.d_in & 15) == 0 && !tuning("seg_no_mfma");
     const int rows_per = mfma ? 32 : kChunk;
+    const int rec = mfma ? 3 : kRec;
     std::vector<int32_t> tab;
     for (int32_t k = 0; k < S; ++k) {
         if (seg_slot[k] < 0) continue;
         for (int32_t r0 = seg_off[k]; r0 < seg_off[k + 1]; r0 += rows_per) {
             const int32_t n = seg_off[k + 1] - r0 < rows_per ? seg_off[k + 1] - r0 : rows_per;
-            tab.push_back(seg_slot[k]); tab.push_back(r0); tab.push_back(n);
+            if (mfma) {
+                tab.push_back(seg_slot[k]); tab.push_back(r0); tab.push_back(n);
+            } else {
+                tab.push_back(seg_slot[k]); tab.push_back(n); tab.push_back(r0); tab.push_back(0);
+                for (int32_t c = 0; c < kChunk; ++c) tab.push_back(r0 + (c < n ? c : n - 1));
+            }
         }
     }
-    const int32_t n_units = (int32_t)(tab.size() / 3);
+    const int32_t n_units = (int32_t)(tab.size() / rec);
     if (n_units == 0) return MLORA_OK;
-    if (n_units + 1 > s->seg_cap) return MLORA_E_UNSUPPORTED;
-    if (!mfma) { tab.push_back(n_units); tab.push_back(0); tab.push_back(0); }   // header word after the chunks
+    if ((int64_t)(n_units + 1) * rec > (int64_t)s->seg_cap * 3) return MLORA_E_UNSUPPORTED;
+    if (!mfma) tab.push_back(n_units);                       // header word after the records
     rc = stage_table(s, tab, st);
     if (rc) return rc;
     if (mfma) {
@@ -491,7 +504,7 @@ int32_t lora_apply_segmented(mlora_site *s, const void *x, int64_t ldx, void *y,
         return ok(launch_seg_mfma(a, st)) ? MLORA_OK : MLORA_E_HIP;
     }
     RowsArgs a = rows_args(s, x, ldx, y, ldy);
-    a.hdr = s->seg_dev + 3 * (int64_t)n_units; a.chunks = s->seg_dev; a.sorted = nullptr;
+    a.hdr = s->seg_dev + (int64_t)kRec * n_units; a.chunks = s->seg_dev;
     a.grid_chunks = n_units;
     a.n_tiles = rows_tiles(a.d_in, a.d_out, a.r_pad, n_units);
     return ok(launch_rows(a, st)) ? MLORA_OK : MLORA_E_HIP;

@@ -7,6 +7,7 @@
 namespace mlora {
 
 constexpr int kChunk = MLORA_CHUNK;
+constexpr int kRec = 4 + kChunk;
 
 // Device view of a site's metadata block: rank | scale | catalog_id.
 struct MetaView {
@@ -14,8 +15,10 @@ struct MetaView {
     const float   *scale;
 };
 
-// Device view of a plan buffer (all int32).  A chunk is (key, start, count): `count` rows
-// sorted[start .. start+count) all belong to group `key` (dense: slot; MoE: slot*E + expert).
+// Device view of a plan buffer (all int32).  A chunk record is kRec ints:
+//   [0] key (dense: slot; MoE: slot*E + expert)  [1] count (1..kChunk)  [2] start in `sorted`
+//   [3] unused  [4 .. 4+kChunk) the row ids of the chunk, ascending
+// so that a workgroup learns everything about its chunk from one 48-byte read.
 struct PlanView {
     int32_t *hdr;         // [8]  hdr[0] = number of chunks, hdr[1] = number of usable rows
     int32_t *count;       // [n_keys + 1]  zero between calls
@@ -25,7 +28,7 @@ struct PlanView {
     int32_t *ticket;      // [max_items]
     int32_t *tmp;         // [max_items]
     int32_t *sorted;      // [max_items]
-    int32_t *chunks;      // [3 * max_chunks]
+    int32_t *chunks;      // [kRec * max_chunks]
 };
 
 size_t plan_words(int64_t max_items, int64_t n_keys);
@@ -52,13 +55,13 @@ struct RowsArgs {
     const uint16_t *a_tab; const uint16_t *b_tab;
     MetaView meta;
     const int32_t *hdr;      // plan header (hdr[0] = live chunks)
-    const int32_t *chunks;
-    const int32_t *sorted;   // null = identity (row index == sorted position)
+    const int32_t *chunks;   // kRec ints per chunk
     int32_t d_in, d_out, r_pad;
     int32_t n_experts;       // >= 1: key / n_experts = slot
     int32_t top_k;           // x row = item / top_k
     int32_t grid_chunks;     // upper bound on the number of chunks (launch width)
     int32_t n_tiles;         // d_out splits
+    uint64_t *prof;          // debug: per-workgroup phase timestamps (null in normal use)
 };
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st);
 
@@ -75,6 +78,7 @@ struct SegArgs {
 hipError_t launch_seg_mfma(const SegArgs &a, hipStream_t st);
 
 int tuning(const char *name);   // api.hip
+uint64_t *debug_prof();         // api.hip
 
 }  // namespace mlora
 

@@ -9,7 +9,7 @@ namespace mlora {
 
 size_t plan_words(int64_t M, int64_t NK)
 {
-    return 8 + 3 * (NK + 1) + 4 * M + 3 * max_chunks(M, NK) + 64;
+    return 8 + 3 * (NK + 1) + 4 * M + kRec * max_chunks(M, NK) + 64;
 }
 
 PlanView plan_view(void *base, int64_t M, int64_t NK)
@@ -49,47 +49,62 @@ __global__ __launch_bounds__(1024)
 void plan_dense_small_kernel(PlanView pv, const int32_t *__restrict__ token_slot, int T, int n_slots,
                              const int32_t *__restrict__ ready_rank)
 {
-    extern __shared__ int32_t sm[];
-    int32_t *ss = sm;          // usable slot or -1
-    int32_t *rk = sm + T;      // rank of the row inside its slot group
+    extern __shared__ int4 sm4[];
+    const int Tp = (T + 3) & ~3;
+    int32_t *ss = (int32_t *)sm4;      // usable slot or -1 (padded to a multiple of 4 with -1)
+    int32_t *rk = ss + Tp;             // rank of the row inside its slot group
+    const int4 *ss4 = (const int4 *)ss, *rk4 = (const int4 *)rk;
     __shared__ int32_t n_chunks, n_rows;
     const int tid = threadIdx.x, nt = blockDim.x;
     if (tid == 0) { n_chunks = 0; n_rows = 0; }
-    for (int t = tid; t < T; t += nt) {
-        int s = token_slot[t];
-        if (s < 0 || s >= n_slots || (ready_rank && ready_rank[s] <= 0)) s = -1;
+    for (int t = tid; t < Tp; t += nt) {
+        int s = -1;
+        if (t < T) {
+            s = token_slot[t];
+            if (s < 0 || s >= n_slots || (ready_rank && ready_rank[s] <= 0)) s = -1;
+        }
         ss[t] = s;
     }
     __syncthreads();
-    for (int t = tid; t < T; t += nt) {
-        int s = ss[t], r = -1;
+    for (int t = tid; t < Tp; t += nt) {
+        const int s = ss[t];
+        int r = -1;
         if (s >= 0) {
             r = 0;
-            for (int u = 0; u < t; ++u) r += (ss[u] == s);
+#pragma unroll 4
+            for (int q = 0; q * 4 < t; ++q) {
+                const int4 v = ss4[q];
+                const int u = q * 4;
+                r += (v.x == s) + ((v.y == s) & (u + 1 < t)) + ((v.z == s) & (u + 2 < t)) + ((v.w == s) & (u + 3 < t));
+            }
         }
         rk[t] = r;
     }
     __syncthreads();
     int my_chunks = 0, my_rows = 0;
     for (int t = tid; t < T; t += nt) {
-        int s = ss[t];
+        const int s = ss[t];
         if (s < 0) continue;
         int less = 0, n = 0, cb = 0;
-        for (int u = 0; u < T; ++u) {
-            int su = ss[u];
-            bool lt = (su >= 0) & (su < s);
-            less += lt;
-            n += (su == s);
-            cb += lt & ((rk[u] % kChunk) == 0);
+#pragma unroll 4
+        for (int q = 0; q * 4 < Tp; ++q) {
+            const int4 v = ss4[q], k = rk4[q];
+            // padding and unusable rows carry slot -1 and never compare below a usable slot here
+            const bool l0 = (unsigned)v.x < (unsigned)s, l1 = (unsigned)v.y < (unsigned)s;
+            const bool l2 = (unsigned)v.z < (unsigned)s, l3 = (unsigned)v.w < (unsigned)s;
+            less += l0 + l1 + l2 + l3;
+            n += (v.x == s) + (v.y == s) + (v.z == s) + (v.w == s);
+            cb += (l0 & ((k.x % kChunk) == 0)) + (l1 & ((k.y % kChunk) == 0))
+                + (l2 & ((k.z % kChunk) == 0)) + (l3 & ((k.w % kChunk) == 0));
         }
-        int r = rk[t], pos = less + r;
+        const int r = rk[t], pos = less + r;
         pv.sorted[pos] = t;
         my_rows += 1;
+        const int c = cb + r / kChunk;
+        int32_t *rec = pv.chunks + (int64_t)c * kRec;
+        rec[4 + (r % kChunk)] = t;
         if (r % kChunk == 0) {
-            int c = cb + r / kChunk;
-            pv.chunks[3 * c + 0] = s;
-            pv.chunks[3 * c + 1] = pos;
-            pv.chunks[3 * c + 2] = min(kChunk, n - r);
+            rec[0] = s; rec[1] = min(kChunk, n - r); rec[2] = pos; rec[3] = 0;
             my_chunks += 1;
         }
     }
@@ -103,7 +118,7 @@ hipError_t launch_plan_dense_small(const PlanView &pv, const int32_t *token_slot
                                    const int32_t *ready_rank, hipStream_t st)
 {
     int nt = T <= 256 ? 256 : (T <= 512 ? 512 : 1024);
-    size_t lds = (size_t)2 * T * sizeof(int32_t);
+    size_t lds = (size_t)2 * ((T + 3) & ~3) * sizeof(int32_t);
     plan_dense_small_kernel<<<dim3(1), dim3(nt), lds, st>>>(pv, token_slot, T, n_slots, ready_rank);
     return hipGetLastError();
 }
@@ -196,12 +211,9 @@ void plan_fix_kernel(PlanView pv, int P, int32_t *__restrict__ out_sorted)
     for (int m = 0; m < n; ++m) r += (pv.tmp[off + m] < p);
     pv.sorted[off + r] = p;
     if (out_sorted) out_sorted[off + r] = p;
-    if (r % kChunk == 0) {
-        int c = pv.chunk_base[key] + r / kChunk;
-        pv.chunks[3 * c + 0] = key;
-        pv.chunks[3 * c + 1] = off + r;
-        pv.chunks[3 * c + 2] = min(kChunk, n - r);
-    }
+    int32_t *rec = pv.chunks + (int64_t)(pv.chunk_base[key] + r / kChunk) * kRec;
+    rec[4 + (r % kChunk)] = p;
+    if (r % kChunk == 0) { rec[0] = key; rec[1] = min(kChunk, n - r); rec[2] = off + r; rec[3] = 0; }
 }
 
 hipError_t launch_plan_general(const PlanView &pv, const int32_t *topk, const int32_t *token_slot,
