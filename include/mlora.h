@@ -45,7 +45,7 @@ enum {
 };
 
 #define MLORA_MAX_RANK 64       /* r_max is rounded up to a power of two <= 64 in the tables */
-#define MLORA_CHUNK     8       /* rows of one adapter handled together by one workgroup   */
+#define MLORA_CHUNK     4       /* rows of one adapter handled together by one workgroup   */
 
 /* One LoRA-targeted projection (a "site"): its slot tables and their shape limits
  * (Section 3.2: a worker advertises adapter-shape limits and allocates slots at them). */
@@ -78,6 +78,10 @@ int32_t mlora_site_bytes(const mlora_site_desc *desc, size_t *a_tab, size_t *b_t
 int32_t mlora_site_create(const mlora_site_desc *desc, void *a_tab_dev, void *b_tab_dev,
                           void *meta_dev, void *scratch_dev, mlora_site **out);
 void    mlora_site_destroy(mlora_site *site);   /* frees host state only */
+/* Synchronises `stream`, then returns MLORA_E_HIP if a launch on this site gave up waiting for
+ * an intermediate result of its own launch (bounded wait; not expected to happen) and clears
+ * that flag; MLORA_OK otherwise. */
+int32_t mlora_site_check(mlora_site *site, void *stream);
 
 /* Copies one adapter into slot `slot` (the last hop of an adapter load, Sections 3.4 and 4:
  * an exported revision becomes an engine-local adapter in a GPU slot).

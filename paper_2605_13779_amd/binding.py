@@ -32,6 +32,7 @@ SIGNATURES = {
     "mlora_site_bytes": (_i32, [C.POINTER(SiteDesc)] + [C.POINTER(_sz)] * 4),
     "mlora_site_create": (_i32, [C.POINTER(SiteDesc), _vp, _vp, _vp, _vp, C.POINTER(_vp)]),
     "mlora_site_destroy": (None, [_vp]),
+    "mlora_site_check": (_i32, [_vp, _vp]),
     "lora_slots_upload": (_i32, [_vp, _i32, _i64, _vp, _vp, _i32, C.c_float, _i32, _vp]),
     "lora_slots_evict": (_i32, [_vp, _i32, _vp]),
     "mlora_plan_bytes": (_i32, [_i32, _i32, C.POINTER(_sz)]),
@@ -114,6 +115,9 @@ class Site:
         n = self.n_slots
         return (raw[:4 * n].view(np.int32).copy(), raw[4 * n:8 * n].view(np.float32).copy(),
                 raw[8 * n:16 * n].view(np.int64).copy())
+
+    def check(self, stream=None):
+        _check("mlora_site_check", load_library().mlora_site_check(self.handle, _stream(stream)))
 
     def close(self):
         if self.handle is not None:

@@ -27,6 +27,8 @@ struct mlora_site {
     float *scale;
     int64_t *catalog;
     mlora_plan priv;            // private plan living in the caller-provided scratch
+    uint32_t *ctrl;             // dense sites: launch tag / sign-in counters of split launches
+    uint64_t *xch;              // dense sites: partial shrink results in flight between workgroups
     int32_t *seg_dev;           // device area for segment tiles / chunks
     int32_t seg_cap;            // in entries of 3 ints
     int32_t *stage[2];          // pinned host staging for the segment tables (lazy)
@@ -40,6 +42,9 @@ namespace {
 constexpr int32_t kDensePrivItems = 8192;      // rows per private dense plan (one-workgroup planner)
 constexpr int32_t kMoePrivItems = 131072;      // pairs per private MoE plan
 constexpr int32_t kSegCap = 65536;             // segment tiles / chunks per call
+constexpr int32_t kXchChunks = 256;            // chunks per launch that may use the split shape
+constexpr size_t kCtrlBytes = 1024;
+constexpr size_t kXchBytes = (size_t)kXchChunks * 128 * kChunk * 8;   // <= 128 values per row of a chunk
 
 std::mutex g_tune_mu;
 std::map<std::string, int> g_tune;
@@ -110,21 +115,6 @@ struct DeviceGuard {
     int cur = -1;
 };
 
-int rows_tiles(int d_in, int d_out, int r_pad, int grid_chunks)
-{
-    int t = tuning("rows_tiles");
-    const int opl = r_pad >= 8 ? 1 : 8 / r_pad;
-    const int max_tiles = (d_out + 256 * opl - 1) / (256 * opl);
-    if (t <= 0) {
-        t = (2 * d_out + d_in / 2) / d_in;                     // keep the re-done shrink a minority
-        int want = (1024 + grid_chunks - 1) / grid_chunks;     // enough workgroups for 256 CUs
-        if (t > want) t = want;
-    }
-    if (t > max_tiles) t = max_tiles;
-    if (t < 1) t = 1;
-    return t;
-}
-
 int32_t check_xy(const mlora_site *s, const void *x, int64_t ldx, const void *y, int64_t ldy)
 {
     if (!s || !x || !y) return MLORA_E_INVALID;
@@ -141,6 +131,7 @@ RowsArgs rows_args(const mlora_site *s, const void *x, int64_t ldx, void *y, int
     a.meta.rank = s->rank; a.meta.scale = s->scale;
     a.d_in = s->d.d_in; a.d_out = s->d.d_out; a.r_pad = s->r_pad;
     a.n_experts = s->E; a.top_k = 1;
+    a.xch = s->xch; a.ctrl = s->ctrl; a.xch_chunks = s->xch ? kXchChunks : 0;
     a.prof = debug_prof();
     return a;
 }
@@ -183,10 +174,9 @@ int32_t apply_planned_impl(mlora_site *s, const mlora_plan *plan, const void *x,
 {
     if (plan->items == 0) return MLORA_OK;
     RowsArgs a = rows_args(s, x, ldx, y, ldy);
-    a.hdr = plan->pv.hdr; a.chunks = plan->pv.chunks;
+    a.chunks = plan->pv.chunks;
     a.top_k = plan->top_k;
     a.grid_chunks = plan->grid_chunks;
-    a.n_tiles = rows_tiles(a.d_in, a.d_out, a.r_pad, a.grid_chunks);
     return ok(launch_rows(a, st)) ? MLORA_OK : MLORA_E_HIP;
 }
 
@@ -258,7 +248,8 @@ int32_t mlora_site_bytes(const mlora_site_desc *d, size_t *a_tab, size_t *b_tab,
     *a_tab = align256((size_t)d->n_slots * E * rp * d->d_in * 2);
     *b_tab = align256((size_t)d->n_slots * E * d->d_out * rp * 2);
     *meta = align256((size_t)d->n_slots * 16);
-    *scratch = align256(plan_words(priv_items(d), (int64_t)d->n_slots * E) * 4) + align256((size_t)kSegCap * 3 * 4);
+    *scratch = align256(plan_words(priv_items(d), (int64_t)d->n_slots * E) * 4) + align256((size_t)kSegCap * 3 * 4)
+             + (d->n_experts > 0 ? 0 : kCtrlBytes + kXchBytes);
     return MLORA_OK;
 }
 
@@ -281,6 +272,11 @@ int32_t mlora_site_create(const mlora_site_desc *d, void *a_tab, void *b_tab, vo
     init_plan(&s->priv, priv_items(d), (int32_t)NK, d->device, scratch);
     s->seg_dev = (int32_t *)((char *)scratch + align256(plan_words(priv_items(d), NK) * 4));
     s->seg_cap = kSegCap;
+    s->ctrl = nullptr; s->xch = nullptr;
+    if (d->n_experts == 0) {
+        s->ctrl = (uint32_t *)((char *)s->seg_dev + align256((size_t)kSegCap * 3 * 4));
+        s->xch = (uint64_t *)((char *)s->ctrl + kCtrlBytes);
+    }
     s->stage[0] = s->stage[1] = nullptr;
     s->stage_busy[0] = s->stage_busy[1] = false;
     s->stage_next = 0;
@@ -288,6 +284,10 @@ int32_t mlora_site_create(const mlora_site_desc *d, void *a_tab, void *b_tab, vo
     if (!g.good) { delete s; return MLORA_E_HIP; }
     meta_clear_kernel<<<dim3((d->n_slots + 255) / 256), dim3(256), 0, 0>>>(s->rank, s->scale, s->catalog, d->n_slots);
     hipError_t e = launch_fill_i32(s->priv.pv.hdr, 0, 8 + 3 * (NK + 1), 0);
+    if (ok(e) && s->ctrl) {
+        e = launch_fill_i32((int32_t *)s->ctrl, 0, (int64_t)((kCtrlBytes + kXchBytes) / 4), 0);   // tag 0 = never written
+        if (ok(e)) e = launch_fill_i32((int32_t *)s->ctrl, 1, 1, 0);                               // first launch tag
+    }
     if (!ok(e) || !ok(hipGetLastError()) || !ok(hipStreamSynchronize(0))) { delete s; return MLORA_E_HIP; }
     *out = s;
     return MLORA_OK;
@@ -337,6 +337,22 @@ int32_t lora_slots_upload(mlora_site *s, int32_t slot, int64_t catalog_id, const
     if (!ok(e)) return MLORA_E_HIP;
     meta_set_kernel<<<dim3(1), dim3(1), 0, st>>>(s->rank, s->scale, s->catalog, slot, r, alpha / (float)r, catalog_id);
     return ok(hipGetLastError()) ? MLORA_OK : MLORA_E_HIP;
+}
+
+int32_t mlora_site_check(mlora_site *s, void *stream)
+{
+    if (!s) return MLORA_E_INVALID;
+    DeviceGuard g(s->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    if (!ok(hipStreamSynchronize((hipStream_t)stream))) return MLORA_E_HIP;
+    if (!s->ctrl) return MLORA_OK;
+    uint32_t flag = 0;
+    if (!ok(hipMemcpy(&flag, s->ctrl + 1, sizeof flag, hipMemcpyDeviceToHost))) return MLORA_E_HIP;
+    if (flag) {
+        (void)launch_fill_i32((int32_t *)s->ctrl + 1, 0, 1, (hipStream_t)stream);
+        return MLORA_E_HIP;
+    }
+    return MLORA_OK;
 }
 
 int32_t lora_slots_evict(mlora_site *s, int32_t slot, void *stream)
@@ -493,7 +509,6 @@ int32_t lora_apply_segmented(mlora_site *s, const void *x, int64_t ldx, void *y,
     const int32_t n_units = (int32_t)(tab.size() / rec);
     if (n_units == 0) return MLORA_OK;
     if ((int64_t)(n_units + 1) * rec > (int64_t)s->seg_cap * 3) return MLORA_E_UNSUPPORTED;
-    if (!mfma) tab.push_back(n_units);                       // header word after the records
     rc = stage_table(s, tab, st);
     if (rc) return rc;
     if (mfma) {
@@ -504,9 +519,8 @@ int32_t lora_apply_segmented(mlora_site *s, const void *x, int64_t ldx, void *y,
         return ok(launch_seg_mfma(a, st)) ? MLORA_OK : MLORA_E_HIP;
     }
     RowsArgs a = rows_args(s, x, ldx, y, ldy);
-    a.hdr = s->seg_dev + (int64_t)kRec * n_units; a.chunks = s->seg_dev;
+    a.chunks = s->seg_dev;
     a.grid_chunks = n_units;
-    a.n_tiles = rows_tiles(a.d_in, a.d_out, a.r_pad, n_units);
     return ok(launch_rows(a, st)) ? MLORA_OK : MLORA_E_HIP;
 }
 

@@ -18,6 +18,7 @@ struct MetaView {
 // Device view of a plan buffer (all int32).  A chunk record is kRec ints:
 //   [0] key (dense: slot; MoE: slot*E + expert)  [1] count (1..kChunk)  [2] start in `sorted`
 //   [3] unused  [4 .. 4+kChunk) the row ids of the chunk, ascending
+// Records past the live chunks of a batch have count 0.
 // so that a workgroup learns everything about its chunk from one 48-byte read.
 struct PlanView {
     int32_t *hdr;         // [8]  hdr[0] = number of chunks, hdr[1] = number of usable rows
@@ -54,13 +55,18 @@ struct RowsArgs {
     uint16_t *y;       int64_t ldy;
     const uint16_t *a_tab; const uint16_t *b_tab;
     MetaView meta;
-    const int32_t *hdr;      // plan header (hdr[0] = live chunks)
     const int32_t *chunks;   // kRec ints per chunk
     int32_t d_in, d_out, r_pad;
     int32_t n_experts;       // >= 1: key / n_experts = slot
     int32_t top_k;           // x row = item / top_k
-    int32_t grid_chunks;     // upper bound on the number of chunks (launch width)
-    int32_t n_tiles;         // d_out splits
+    int32_t grid_chunks;     // upper bound on the number of chunks
+    // exchange area of the site (null on sites that only run fused launches)
+    uint64_t *xch;           // [xch_chunks][<= 128 values][kChunk] words
+    uint32_t *ctrl;          // [0] launch tag, [1] error flag, [2] top sign-in, [8..72) group sign-ins
+    int32_t xch_chunks;
+    // filled in by the launcher
+    int32_t mode;            // 0 fused, 1 split
+    int32_t ksplit, kslice_units, ntiles;
     uint64_t *prof;          // debug: per-workgroup phase timestamps (null in normal use)
 };
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st);

@@ -47,7 +47,7 @@ hipError_t launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t st)
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024)
 void plan_dense_small_kernel(PlanView pv, const int32_t *__restrict__ token_slot, int T, int n_slots,
-                             const int32_t *__restrict__ ready_rank)
+                             const int32_t *__restrict__ ready_rank, int rec_bound)
 {
     extern __shared__ int4 sm4[];
     const int Tp = (T + 3) & ~3;
@@ -112,6 +112,8 @@ void plan_dense_small_kernel(PlanView pv, const int32_t *__restrict__ token_slot
     if (my_rows) atomicAdd(&n_rows, my_rows);
     __syncthreads();
     if (tid == 0) { pv.hdr[0] = n_chunks; pv.hdr[1] = n_rows; }
+    // records past the live chunks are marked empty (count 0): the apply kernels read only records
+    for (int c = n_chunks + tid; c < rec_bound; c += nt) pv.chunks[(int64_t)c * kRec + 1] = 0;
 }
 
 hipError_t launch_plan_dense_small(const PlanView &pv, const int32_t *token_slot, int T, int n_slots,
@@ -119,7 +121,8 @@ hipError_t launch_plan_dense_small(const PlanView &pv, const int32_t *token_slot
 {
     int nt = T <= 256 ? 256 : (T <= 512 ? 512 : 1024);
     size_t lds = (size_t)2 * ((T + 3) & ~3) * sizeof(int32_t);
-    plan_dense_small_kernel<<<dim3(1), dim3(nt), lds, st>>>(pv, token_slot, T, n_slots, ready_rank);
+    plan_dense_small_kernel<<<dim3(1), dim3(nt), lds, st>>>(pv, token_slot, T, n_slots, ready_rank,
+                                                            (int)max_chunks(T, n_slots));
     return hipGetLastError();
 }
 
@@ -194,11 +197,12 @@ void plan_scatter_kernel(PlanView pv, int P)
 }
 
 __global__ __launch_bounds__(256)
-void plan_fix_kernel(PlanView pv, int P, int32_t *__restrict__ out_sorted)
+void plan_fix_kernel(PlanView pv, int P, int32_t *__restrict__ out_sorted, int rec_bound)
 {
     int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= P) return;
     const int n_rows = pv.hdr[1];
+    if (j >= pv.hdr[0] && j < rec_bound) pv.chunks[(int64_t)j * kRec + 1] = 0;   // empty record past the live chunks
     if (j >= n_rows) {
         pv.sorted[j] = -1;
         if (out_sorted) out_sorted[j] = -1;
@@ -225,7 +229,7 @@ hipError_t launch_plan_general(const PlanView &pv, const int32_t *topk, const in
     plan_hist_kernel<<<dim3(nb), dim3(256), 0, st>>>(pv, topk, token_slot, P, K, E, n_slots, ready_rank);
     plan_scan_kernel<<<dim3(1), dim3(1024), 0, st>>>(pv, NK, out_group_off);
     plan_scatter_kernel<<<dim3(nb), dim3(256), 0, st>>>(pv, P);
-    plan_fix_kernel<<<dim3(nb), dim3(256), 0, st>>>(pv, P, out_sorted);
+    plan_fix_kernel<<<dim3(nb), dim3(256), 0, st>>>(pv, P, out_sorted, (int)max_chunks(P, NK));
     return hipGetLastError();
 }
 
