@@ -39,7 +39,7 @@ struct mlora_site {
 
 namespace {
 
-constexpr int32_t kDensePrivItems = 8192;      // rows per private dense plan (one-workgroup planner)
+constexpr int32_t kDensePrivItems = 1024;      // rows per private dense plan (one-workgroup planner)
 constexpr int32_t kMoePrivItems = 131072;      // pairs per private MoE plan
 constexpr int32_t kSegCap = 65536;             // segment tiles / chunks per call
 constexpr int32_t kXchChunks = 256;            // chunks per launch that may use the split shape

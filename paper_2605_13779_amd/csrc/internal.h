@@ -67,6 +67,7 @@ struct RowsArgs {
     // filled in by the launcher
     int32_t mode;            // 0 fused, 1 split
     int32_t ksplit, kslice_units, ntiles;
+    int32_t tile_par;        // fused launches: 1 = an item expands every tile, ntiles = one tile per item
     uint64_t *prof;          // debug: per-workgroup phase timestamps (null in normal use)
 };
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st);

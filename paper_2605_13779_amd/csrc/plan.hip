@@ -42,87 +42,142 @@ hipError_t launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t st)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Small dense batches: one workgroup, comparison counting in LDS.  Row t lands at position
-// #{t' usable : (slot', t') < (slot, t)}, which is the stable sort by slot.
+// Small dense batches (up to kSortMax rows): one workgroup, one key (slot, row) per thread, sorted
+// with a bitonic network -- keys are distinct, so the result is the stable sort by slot.  Exchanges
+// at distance < 64 stay inside a wave (DPP / swizzle), only the few longer ones go through LDS.
+// Group starts and chunk numbers then come from two scans, and the chunk records are written.
 // ---------------------------------------------------------------------------------------------
+constexpr int kSortMax = 1024;
+
+template <int D>
+__device__ __forceinline__ uint32_t lane_xor_u32(uint32_t x)
+{
+    int r;
+    if constexpr (D == 1) r = __builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xf, 0xf, true);
+    else if constexpr (D == 2) r = __builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xf, 0xf, true);
+    else if constexpr (D == 4) {
+        r = __builtin_amdgcn_update_dpp(0, (int)x, 0x104, 0xf, 0x5, false);
+        r = __builtin_amdgcn_update_dpp(r, (int)x, 0x114, 0xf, 0xa, false);
+    } else if constexpr (D == 8) r = __builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xf, 0xf, true);
+    else if constexpr (D == 16) r = __builtin_amdgcn_ds_swizzle((int)x, 0x401F);
+    else r = __shfl_xor((int)x, 32, 64);
+    return (uint32_t)r;
+}
+
+// One compare-exchange step of the network for the key held by thread i (partner i ^ J, merge size K).
+template <int K, int J>
+__device__ __forceinline__ void bitonic_step(uint32_t &ks, uint32_t &kt, int i, uint2 *xch)
+{
+    uint32_t ps, pt;
+    if constexpr (J < 64) {
+        ps = lane_xor_u32<J>(ks);
+        pt = lane_xor_u32<J>(kt);
+    } else {
+        xch[i] = make_uint2(ks, kt);
+        __syncthreads();
+        const uint2 p = xch[i ^ J];
+        __syncthreads();
+        ps = p.x; pt = p.y;
+    }
+    const bool self_less = ks < ps || (ks == ps && kt < pt);
+    const bool up = (i & K) == 0, lower = (i & J) == 0;
+    const bool keep_self = (lower == up) == self_less;      // lower lane of an ascending pair keeps the smaller key
+    if (!keep_self) { ks = ps; kt = pt; }
+}
+
+template <int K, int J>
+struct BitonicMerge {
+    static __device__ __forceinline__ void run(uint32_t &ks, uint32_t &kt, int i, uint2 *xch)
+    {
+        bitonic_step<K, J>(ks, kt, i, xch);
+        if constexpr (J > 1) BitonicMerge<K, J / 2>::run(ks, kt, i, xch);
+    }
+};
+
+template <int K>
+struct BitonicSort {
+    static __device__ __forceinline__ void run(uint32_t &ks, uint32_t &kt, int i, int N, uint2 *xch)
+    {
+        if constexpr (K > 2) BitonicSort<K / 2>::run(ks, kt, i, N, xch);
+        if (K <= N) BitonicMerge<K, K / 2>::run(ks, kt, i, xch);      // N is uniform over the workgroup
+    }
+};
+
+// Inclusive scan over the workgroup (one value per thread); IS_MAX selects max instead of plus.
+template <bool IS_MAX>
+__device__ __forceinline__ int block_scan(int v, int tid, int nw, int32_t *wave_tot)
+{
+    const int lane = tid & 63, w = tid >> 6;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(v, d, 64);
+        if (lane >= d) v = IS_MAX ? max(v, o) : v + o;
+    }
+    if (lane == 63) wave_tot[w] = v;
+    __syncthreads();
+    int base = 0;
+    for (int k = 0; k < w; ++k) base = IS_MAX ? max(base, wave_tot[k]) : base + wave_tot[k];
+    __syncthreads();
+    (void)nw;
+    return IS_MAX ? max(v, base) : v + base;
+}
+
 __global__ __launch_bounds__(1024)
 void plan_dense_small_kernel(PlanView pv, const int32_t *__restrict__ token_slot, int T, int n_slots,
-                             const int32_t *__restrict__ ready_rank, int rec_bound)
+                             const int32_t *__restrict__ ready_rank, int rec_bound, int N)
 {
-    extern __shared__ int4 sm4[];
-    const int Tp = (T + 3) & ~3;
-    int32_t *ss = (int32_t *)sm4;      // usable slot or -1 (padded to a multiple of 4 with -1)
-    int32_t *rk = ss + Tp;             // rank of the row inside its slot group
-    const int4 *ss4 = (const int4 *)ss, *rk4 = (const int4 *)rk;
-    __shared__ int32_t n_chunks, n_rows;
-    const int tid = threadIdx.x, nt = blockDim.x;
-    if (tid == 0) { n_chunks = 0; n_rows = 0; }
-    for (int t = tid; t < Tp; t += nt) {
-        int s = -1;
-        if (t < T) {
-            s = token_slot[t];
-            if (s < 0 || s >= n_slots || (ready_rank && ready_rank[s] <= 0)) s = -1;
-        }
-        ss[t] = s;
+    __shared__ uint2 xch[kSortMax];              // long-distance exchanges, then sorted slots / chunk starts
+    __shared__ int32_t wave_tot[16];
+    __shared__ int32_t s_rows, s_chunks;
+    const int i = threadIdx.x;                   // blockDim.x == N, a power of two in [64, 1024]
+    const uint32_t kNone = 0xffffffffu;
+    if (i == 0) { s_rows = 0; s_chunks = 0; }
+    uint32_t ks = kNone, kt = (uint32_t)i;
+    if (i < T) {
+        const int s = token_slot[i];
+        if (s >= 0 && s < n_slots && !(ready_rank && ready_rank[s] <= 0)) ks = (uint32_t)s;
     }
+    BitonicSort<kSortMax>::run(ks, kt, i, N, xch);
+
+    // neighbours' slots through LDS: group starts, number of usable rows
+    int32_t *ss = (int32_t *)xch;
+    ss[i] = (int32_t)ks;
     __syncthreads();
-    for (int t = tid; t < Tp; t += nt) {
-        const int s = ss[t];
-        int r = -1;
-        if (s >= 0) {
-            r = 0;
-#pragma unroll 4
-            for (int q = 0; q * 4 < t; ++q) {
-                const int4 v = ss4[q];
-                const int u = q * 4;
-                r += (v.x == s) + ((v.y == s) & (u + 1 < t)) + ((v.z == s) & (u + 2 < t)) + ((v.w == s) & (u + 3 < t));
-            }
-        }
-        rk[t] = r;
-    }
+    const bool live = ks != kNone;
+    const bool start = live && (i == 0 || (uint32_t)ss[i - 1] != ks);
+    if (live && (i == N - 1 || (uint32_t)ss[i + 1] == kNone)) s_rows = i + 1;
     __syncthreads();
-    int my_chunks = 0, my_rows = 0;
-    for (int t = tid; t < T; t += nt) {
-        const int s = ss[t];
-        if (s < 0) continue;
-        int less = 0, n = 0, cb = 0;
-#pragma unroll 4
-        for (int q = 0; q * 4 < Tp; ++q) {
-            const int4 v = ss4[q], k = rk4[q];
-            // padding and unusable rows carry slot -1 and never compare below a usable slot here
-            const bool l0 = (unsigned)v.x < (unsigned)s, l1 = (unsigned)v.y < (unsigned)s;
-            const bool l2 = (unsigned)v.z < (unsigned)s, l3 = (unsigned)v.w < (unsigned)s;
-            less += l0 + l1 + l2 + l3;
-            n += (v.x == s) + (v.y == s) + (v.z == s) + (v.w == s);
-            cb += (l0 & ((k.x % kChunk) == 0)) + (l1 & ((k.y % kChunk) == 0))
-                + (l2 & ((k.z % kChunk) == 0)) + (l3 & ((k.w % kChunk) == 0));
-        }
-        const int r = rk[t], pos = less + r;
-        pv.sorted[pos] = t;
-        my_rows += 1;
-        const int c = cb + r / kChunk;
+    const int n_rows = s_rows;
+    const int gs = block_scan<true>(start ? i : 0, i, N >> 6, wave_tot);
+    const int r = i - gs;
+    const bool cstart = live && (r % kChunk) == 0;
+    const int c = block_scan<false>(cstart ? 1 : 0, i, N >> 6, wave_tot) - 1;     // chunk of this row
+    if (live && i == n_rows - 1) s_chunks = c + 1;
+    int32_t *cs = (int32_t *)xch;                // chunk c starts at sorted position cs[c]
+    __syncthreads();
+    const int n_chunks = s_chunks;
+    if (cstart) cs[c] = i;
+    if (i == 0) cs[n_chunks] = n_rows;
+    __syncthreads();
+    if (live) {
+        pv.sorted[i] = (int32_t)kt;
         int32_t *rec = pv.chunks + (int64_t)c * kRec;
-        rec[4 + (r % kChunk)] = t;
-        if (r % kChunk == 0) {
-            rec[0] = s; rec[1] = min(kChunk, n - r); rec[2] = pos; rec[3] = 0;
-            my_chunks += 1;
-        }
+        rec[4 + (r % kChunk)] = (int32_t)kt;
+        if (cstart) { rec[0] = (int32_t)ks; rec[1] = cs[c + 1] - cs[c]; rec[2] = i; rec[3] = 0; }
     }
-    if (my_chunks) atomicAdd(&n_chunks, my_chunks);
-    if (my_rows) atomicAdd(&n_rows, my_rows);
-    __syncthreads();
-    if (tid == 0) { pv.hdr[0] = n_chunks; pv.hdr[1] = n_rows; }
+    if (i == 0) { pv.hdr[0] = n_chunks; pv.hdr[1] = n_rows; }
     // records past the live chunks are marked empty (count 0): the apply kernels read only records
-    for (int c = n_chunks + tid; c < rec_bound; c += nt) pv.chunks[(int64_t)c * kRec + 1] = 0;
+    for (int d = n_chunks + i; d < rec_bound; d += N) pv.chunks[(int64_t)d * kRec + 1] = 0;
 }
 
 hipError_t launch_plan_dense_small(const PlanView &pv, const int32_t *token_slot, int T, int n_slots,
                                    const int32_t *ready_rank, hipStream_t st)
 {
-    int nt = T <= 256 ? 256 : (T <= 512 ? 512 : 1024);
-    size_t lds = (size_t)2 * ((T + 3) & ~3) * sizeof(int32_t);
-    plan_dense_small_kernel<<<dim3(1), dim3(nt), lds, st>>>(pv, token_slot, T, n_slots, ready_rank,
-                                                            (int)max_chunks(T, n_slots));
+    int N = 64;
+    while (N < T) N <<= 1;
+    if (N > kSortMax) return hipErrorInvalidValue;
+    plan_dense_small_kernel<<<dim3(1), dim3(N), 0, st>>>(pv, token_slot, T, n_slots, ready_rank,
+                                                         (int)max_chunks(T, n_slots), N);
     return hipGetLastError();
 }
 

@@ -33,7 +33,7 @@ struct RowsCfg {
     static constexpr int NV  = CS * JPW;                 // values per lane per pass (8)
     static constexpr int OPL = RP >= 8 ? 1 : 8 / RP;     // outputs per lane in the expand
     static constexpr int BV  = RP >= 8 ? RP / 8 : 1;     // 16-byte loads of B per lane
-    static constexpr int TILE = RP <= 4 ? NT * OPL : (RP <= 16 ? 1024 : 512);   // outputs per expand flight
+    static constexpr int TILE = RP <= 4 ? NT * OPL : (RP <= 16 ? (NW == 16 ? 2048 : 1024) : (NW == 16 ? 1024 : 512));   // outputs per expand flight
     static constexpr int EU  = TILE / (NT * OPL);        // outputs groups per lane per flight
     static_assert(JG * KS == NW && EU >= 1, "wave layout");
 };
@@ -141,7 +141,7 @@ __device__ __forceinline__ uint64_t xch_get(const uint64_t *p)
 constexpr int kSpinLimit = 1 << 18;     // polls before an expand item gives up and raises the error flag
 
 template <int RP, int NW, bool SPLIT>
-__global__ __launch_bounds__(NW * 64, (NW == 8 && RP <= 16) ? 4 : 1)
+__global__ __launch_bounds__(NW * 64, (NW >= 8 && RP <= 16) ? 4 : 1)
 void rows_kernel(const RowsArgs a)
 {
     using C = RowsCfg<RP, NW>;
@@ -160,7 +160,7 @@ void rows_kernel(const RowsArgs a)
     // Items are numbered over the upper bound of chunks, so an item's chunk record can be fetched
     // together with the live chunk count (and the launch tag) in one round trip.
     const int n_shr = SPLIT ? a.grid_chunks * a.ksplit : 0;
-    const int n_items = SPLIT ? n_shr + a.grid_chunks * a.ntiles : a.grid_chunks;
+    const int n_items = SPLIT ? n_shr + a.grid_chunks * a.ntiles : a.grid_chunks * a.tile_par;
 
     // Split launches carry a tag that must differ from launch to launch, also when a captured
     // graph replays the same kernel arguments, so it lives in device memory: every workgroup
@@ -182,6 +182,8 @@ void rows_kernel(const RowsArgs a)
         if (SPLIT) {
             if (item < n_shr) { chunk = item / a.ksplit; kslice = item - chunk * a.ksplit; do_expand = false; }
             else { const int e = item - n_shr; chunk = e / a.ntiles; tile0 = e - chunk * a.ntiles; tile1 = tile0 + 1; do_shrink = false; }
+        } else if (a.tile_par > 1) {
+            chunk = item / a.tile_par; tile0 = item - chunk * a.tile_par; tile1 = tile0 + 1;
         } else {
             chunk = item;
         }
@@ -436,9 +438,9 @@ static hipError_t launch_rp(RowsArgs a, hipStream_t st)
     const int ksplit = (U + C::FLU - 1) / C::FLU;
     a.ntiles = ntiles;
     const bool can_split = a.xch && a.ctrl && a.grid_chunks <= a.xch_chunks && ksplit <= 8 && ksplit * RP <= 128;
-    const int mode = tuning("rows_mode");                 // 0 auto, 1 fused, 2 split
-    bool split = can_split && (ksplit > 1 || ntiles > 1);
-    if (mode == 1) split = false;
+    const int mode = tuning("rows_mode");                 // 0 auto, 1 fused, 2 split, 3 fused with one tile per item
+    bool split = can_split && ksplit > 1;                 // d_in needs several flights: cut it across workgroups
+    if (mode == 1 || mode == 3) split = false;
     if (mode == 2) split = can_split;
     if (split) {
         const int cap = rows_capacity<RP, NW, true>();
@@ -451,7 +453,8 @@ static hipError_t launch_rp(RowsArgs a, hipStream_t st)
         rows_kernel<RP, NW, true><<<dim3((unsigned)items), dim3(NW * 64), 0, st>>>(a);
     } else {
         a.mode = 0; a.ksplit = 1; a.kslice_units = U;
-        rows_kernel<RP, NW, false><<<dim3((unsigned)a.grid_chunks), dim3(NW * 64), 0, st>>>(a);
+        a.tile_par = (mode == 3 || (mode == 0 && ksplit == 1 && a.n_experts == 1)) ? ntiles : 1;
+        rows_kernel<RP, NW, false><<<dim3((unsigned)(a.grid_chunks * a.tile_par)), dim3(NW * 64), 0, st>>>(a);
     }
     return hipGetLastError();
 }
@@ -459,11 +462,19 @@ static hipError_t launch_rp(RowsArgs a, hipStream_t st)
 template <int RP>
 static hipError_t launch_nw(const RowsArgs &a, hipStream_t st)
 {
-    // wide workgroups when a flight of 8 waves is not mostly idle lanes
+    const int U = a.d_in >> 3;
     int nw = tuning("rows_waves");
-    if (nw != 4 && nw != 8) nw = (a.d_in >> 3) >= RowsCfg<RP, 8>::FLU * 3 / 4 ? 8 : 4;
+    if (nw != 4 && nw != 8 && nw != 16) {
+        // 16 waves when one flight of them covers all of d_in (then every item is shrink + one tile,
+        // nothing crosses workgroups); else 8, or 4 when 8 would be mostly idle lanes
+        nw = U >= RowsCfg<RP, 8>::FLU * 3 / 4 ? 8 : 4;
+        if constexpr (RP >= 8 && RP <= 16) {
+            if (a.n_experts == 1 && U > RowsCfg<RP, 8>::FLU && U <= RowsCfg<RP, 16>::FLU) nw = 16;
+        }
+    }
     if constexpr (RP >= 64) nw = 8;
-    if (nw == 8) return launch_rp<RP, 8>(a, st);
+    if constexpr (RP >= 8 && RP <= 16) { if (nw == 16) return launch_rp<RP, 16>(a, st); }
+    if (nw >= 8) return launch_rp<RP, 8>(a, st);
     if constexpr (RP < 64) return launch_rp<RP, 4>(a, st);
     return hipErrorInvalidValue;
 }
