@@ -77,23 +77,22 @@ void seg_mfma_kernel(const SegArgs a)
         }
         f32x16_t acc0 = {0}, acc1 = {0};
         const int n_kt = (a.d_in + KT - 1) / KT;
-        uint4 stage[6];
-        auto fetch = [&](int t) {
+        auto fetch = [&](int t, uint4 (&stage)[6]) {
             const int k0 = t * KT;
-            const bool in = k0 + sseg * 8 < a.d_in;           // d_in is a multiple of 16: a segment is in or out as a whole
+            const bool in = t < n_kt && k0 + sseg * 8 < a.d_in;   // d_in is a multiple of 16: a segment is in or out as a whole
 #pragma unroll
             for (int q = 0; q < 6; ++q) {
                 stage[q] = make_uint4(0, 0, 0, 0);
-                if (in) stage[q] = *(const uint4 *)(gp[q] + k0);
+                if (in) stage[q] = q < 2 ? ld_stream(gp[q] + k0) : *(const uint4 *)(gp[q] + k0);
             }
         };
-        fetch(0);
-        for (int t = 0; t < n_kt; ++t) {
-            __syncthreads();                                  // the previous tile has been consumed
+        auto consume = [&](const uint4 (&stage)[6]) {
+            __syncthreads();                                  // the previous tile has been read by every wave
 #pragma unroll
             for (int q = 0; q < 6; ++q) *(uint4 *)(buf + (srow + 16 * q) * TROW + sseg * 16) = stage[q];
             __syncthreads();
-            if (t + 1 < n_kt) fetch(t + 1);
+        };
+        auto mma_tile = [&]() {
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
                 const int kb = (2 * w + s2) * 32 + kh * 16;   // byte offset of this lane's 8 k values
@@ -102,6 +101,20 @@ void seg_mfma_kernel(const SegArgs a)
                 const uint4 v1 = *(const uint4 *)(buf + (64 + m) * TROW + kb);
                 acc0 = mfma32(xv, v0, acc0);
                 acc1 = mfma32(xv, v1, acc1);
+            }
+        };
+        // two k tiles are in flight while a third is being multiplied
+        uint4 sa[6], sb[6];
+        fetch(0, sa);
+        fetch(1, sb);
+        for (int t = 0; t < n_kt; t += 2) {
+            consume(sa);
+            fetch(t + 2, sa);
+            mma_tile();
+            if (t + 1 < n_kt) {
+                consume(sb);
+                fetch(t + 3, sb);
+                mma_tile();
             }
         }
         __syncthreads();
@@ -153,7 +166,7 @@ void seg_mfma_kernel(const SegArgs a)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int tok = tr + 8 * q;
-            if (tok < nrows && oc < a.d_out) yv[q] = *(const uint4 *)(a.y + (int64_t)(row0 + tok) * a.ldy + oc);
+            if (tok < nrows && oc < a.d_out) yv[q] = ld_stream(a.y + (int64_t)(row0 + tok) * a.ldy + oc);
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) *(uint4 *)(wt + (8 * i + tr) * BROW + og * 16) = braw[i];
@@ -188,7 +201,7 @@ void seg_mfma_kernel(const SegArgs a)
                 o.y = pack_bf2(bf_lo(yv[q].y) + d0.z, bf_hi(yv[q].y) + d0.w);
                 o.z = pack_bf2(bf_lo(yv[q].z) + d1.x, bf_hi(yv[q].z) + d1.y);
                 o.w = pack_bf2(bf_lo(yv[q].w) + d1.z, bf_hi(yv[q].w) + d1.w);
-                *(uint4 *)(a.y + (int64_t)(row0 + tok) * a.ldy + oc) = o;
+                st_stream(a.y + (int64_t)(row0 + tok) * a.ldy + oc, o);
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
