@@ -99,12 +99,21 @@ def bench_c2(M, W, steps, warmup, n_layers=8, eager=True):
         layers.append((M.Plan(T, 64), sites))
     torch.cuda.synchronize()
 
+    # launches of one layer: q/k/v are independent of each other and share a launch, so do gate/up;
+    # o and down depend on what runs between them in a real layer and stay on their own
+    groups = [(0, 1, 2), (3,), (4, 5), (6,)]
+
     def layer_step(i, with_plan=True):
         plan, sites = layers[i % n_layers]
         if with_plan:
             M.lora_plan_decode(plan, ts, 64)
-        for site, x, y in sites:
-            M.lora_apply_decode_planned(site, plan, x, y)
+        for grp in groups:
+            if len(grp) == 1:
+                site, x, y = sites[grp[0]]
+                M.lora_apply_decode_planned(site, plan, x, y)
+            else:
+                M.lora_apply_decode_multi([sites[k][0] for k in grp], plan,
+                                          [sites[k][1] for k in grp], [sites[k][2] for k in grp])
 
     def all_layers(with_plan=True):
         for i in range(n_layers):
@@ -116,7 +125,7 @@ def bench_c2(M, W, steps, warmup, n_layers=8, eager=True):
     ms_full = time_region(g_full.replay, reps, wreps) / n_layers
     ms_apply = time_region(g_apply.replay, reps, wreps) / n_layers
     out = {"ms_per_step": ms_full, "steps_timed": reps * n_layers, "tokens": T,
-           "ms_apply_only": ms_apply, "launches_per_step": 7}
+           "ms_apply_only": ms_apply, "launches_per_step": len(groups)}
     if eager:
         k = [0]
 
@@ -205,6 +214,22 @@ def bench_c5(M, W, steps, warmup, wide=False, n_sets=3):
             "bytes_per_step": dense_bytes(c), "flops_per_step": flops}
 
 
+def bench_copy(steps, warmup, mib=256):
+    """A plain device-to-device copy of known size: the calibration kernel for the HBM byte counters."""
+    import torch
+    n = mib << 20
+    bufs = [(torch.zeros(n, dtype=torch.uint8, device="cuda"), torch.empty(n, dtype=torch.uint8, device="cuda"))
+            for _ in range(3)]
+    k = [0]
+
+    def one():
+        src, dst = bufs[k[0] % 3]
+        k[0] += 1
+        dst.copy_(src)
+    ms = time_region(one, steps, warmup)
+    return {"ms_per_step": ms, "ms_apply_only": ms, "tokens": 0, "launches_per_step": 1, "bytes_per_step": 2 * n}
+
+
 def summarize(r):
     t = r["ms_apply_only"] * 1e-3
     gbs = r["bytes_per_step"] / t / 1e9
@@ -244,7 +269,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="all", choices=["all", "c2", "c3", "c4", "c5", "c5w"])
+    ap.add_argument("--workload", default="all", choices=["all", "c2", "c3", "c4", "c5", "c5w", "copy"])
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--tune", action="append", default=[], help="name=value for mlora_set_tuning")
     args = ap.parse_args()
@@ -286,6 +311,8 @@ def main():
         per["c5_seg_wide"] = summarize(bench_c5(M, W, max(10, args.steps // 40), max(3, args.warmup // 40), wide=True))
         torch.cuda.empty_cache()
 
+    if args.workload == "copy":
+        per["copy_256MiB"] = summarize(bench_copy(max(10, args.steps // 40), max(3, args.warmup // 40)))
     if head is None:      # single non-headline workload: still one JSON line, clearly labelled
         name, s = next(iter(per.items()))
         print(json.dumps({"metric": "LoRA-applied tokens/s", "value": s["tokens_per_s"], "unit": "tokens/s",

@@ -118,6 +118,15 @@ int32_t lora_plan_decode(mlora_plan *plan, const int32_t *token_slot, int32_t T,
 int32_t lora_apply_decode_planned(mlora_site *site, const mlora_plan *plan,
                                   const void *x, int64_t ldx, void *y, int64_t ldy, void *stream);
 
+/* Several dense sites that take the same batch plan, applied with as few launches as possible
+ * (q/k/v of one layer, or gate/up, are independent of each other and can share one launch; sites
+ * whose shape needs the split launch get one of their own).  sites, xs, ldxs, ys, ldys are HOST
+ * arrays of length n_sites; each (site, x, y) triple follows the rules of
+ * lora_apply_decode_planned.  The result equals n_sites separate calls. */
+int32_t lora_apply_decode_multi(mlora_site *const *sites, int32_t n_sites, const mlora_plan *plan,
+                                const void *const *xs, const int64_t *ldxs,
+                                void *const *ys, const int64_t *ldys, void *stream);
+
 /* Route index build for packed MoE LoRA (per-expert LoRA tensors are keyed by expert id,
  * Section 3.4): pair p = t*K + k has key = token_slot[t] * n_experts + topk_ids[t, k]; pairs
  * with a usable slot are sorted by key with a stable counting sort (ties ascending p).

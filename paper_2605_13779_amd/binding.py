@@ -40,6 +40,7 @@ SIGNATURES = {
     "mlora_plan_destroy": (None, [_vp]),
     "lora_plan_decode": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
     "lora_apply_decode_planned": (_i32, [_vp, _vp, _vp, _i64, _vp, _i64, _vp]),
+    "lora_apply_decode_multi": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_plan_route": (_i32, [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]),
     "moe_lora_apply_planned": (_i32, [_vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "lora_apply_decode": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _i32, _vp]),
@@ -224,6 +225,19 @@ def lora_apply_decode_planned(site, plan, x, y, stream=None):
     py, ldy = _rows(y)
     _check("lora_apply_decode_planned", load_library().lora_apply_decode_planned(
         site.handle, plan.handle, px, ldx, py, ldy, _stream(stream)))
+
+
+def lora_apply_decode_multi(sites, plan, xs, ys, stream=None):
+    n = len(sites)
+    assert len(xs) == n and len(ys) == n
+    rows = [(_rows(x), _rows(y)) for x, y in zip(xs, ys)]
+    hs = (_vp * n)(*[s.handle for s in sites])
+    px = (_vp * n)(*[r[0][0] for r in rows])
+    lx = (_i64 * n)(*[r[0][1] for r in rows])
+    py = (_vp * n)(*[r[1][0] for r in rows])
+    ly = (_i64 * n)(*[r[1][1] for r in rows])
+    _check("lora_apply_decode_multi", load_library().lora_apply_decode_multi(
+        hs, n, plan.handle, px, lx, py, ly, _stream(stream)))
 
 
 def moe_plan_route(plan, topk_ids, token_slot, n_slots, n_experts, ready_from=None,

@@ -414,6 +414,47 @@ int32_t lora_apply_decode_planned(mlora_site *s, const mlora_plan *plan, const v
     return apply_planned_impl(s, plan, x, ldx, y, ldy, (hipStream_t)stream);
 }
 
+int32_t lora_apply_decode_multi(mlora_site *const *sites, int32_t n_sites, const mlora_plan *plan,
+                                const void *const *xs, const int64_t *ldxs, void *const *ys, const int64_t *ldys,
+                                void *stream)
+{
+    if (!sites || !plan || !xs || !ldxs || !ys || !ldys || n_sites < 1) return MLORA_E_INVALID;
+    if (plan->moe) return MLORA_E_UNSUPPORTED;
+    for (int32_t k = 0; k < n_sites; ++k) {
+        if (!sites[k]) return MLORA_E_INVALID;
+        if (sites[k]->d.n_experts > 0) return MLORA_E_UNSUPPORTED;
+        if (sites[k]->d.device != sites[0]->d.device) return MLORA_E_INVALID;
+        if (plan->n_slots > sites[k]->d.n_slots) return MLORA_E_SLOT;
+        int32_t rc = check_xy(sites[k], xs[k], ldxs[k], ys[k], ldys[k]);
+        if (rc) return rc;
+    }
+    if (plan->items == 0) return MLORA_OK;
+    DeviceGuard g(sites[0]->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    hipStream_t st = (hipStream_t)stream;
+    // group neighbouring sites that can share a launch; the others get a launch of their own
+    int32_t k = 0;
+    while (k < n_sites) {
+        RowsArgs grp[kMaxMulti];
+        int32_t n = 0;
+        while (k + n < n_sites && n < kMaxMulti) {
+            RowsArgs a = rows_args(sites[k + n], xs[k + n], ldxs[k + n], ys[k + n], ldys[k + n]);
+            a.chunks = plan->pv.chunks; a.top_k = plan->top_k; a.grid_chunks = plan->grid_chunks;
+            if (!rows_can_group(a) || (n > 0 && a.r_pad != grp[0].r_pad)) break;
+            grp[n++] = a;
+        }
+        if (n >= 2) {
+            if (!ok(launch_rows_multi(grp, n, st))) return MLORA_E_HIP;
+            k += n;
+        } else {
+            int32_t rc = apply_planned_impl(sites[k], plan, xs[k], ldxs[k], ys[k], ldys[k], st);
+            if (rc) return rc;
+            k += 1;
+        }
+    }
+    return MLORA_OK;
+}
+
 int32_t moe_plan_route(mlora_plan *plan, const int32_t *topk_ids, const int32_t *token_slot, int32_t T, int32_t K,
                        int32_t n_slots, int32_t n_experts, const mlora_site *ready_from,
                        int32_t *out_sorted_pair, int32_t *out_group_off, void *stream)

@@ -71,6 +71,9 @@ struct RowsArgs {
     uint64_t *prof;          // debug: per-workgroup phase timestamps (null in normal use)
 };
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st);
+constexpr int kMaxMulti = 4;     // sites per grouped launch
+bool rows_can_group(const RowsArgs &a);
+hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st);
 
 // seg_mfma.hip: rank-64 segmented apply on the matrix cores
 struct SegArgs {

@@ -140,9 +140,9 @@ __device__ __forceinline__ uint64_t xch_get(const uint64_t *p)
 
 constexpr int kSpinLimit = 1 << 18;     // polls before an expand item gives up and raises the error flag
 
+// Work of workgroup `wg` out of `n_wg` on one site (one launch may cover several sites).
 template <int RP, int NW, bool SPLIT>
-__global__ __launch_bounds__(NW * 64, (NW >= 8 && RP <= 16) ? 4 : 1)
-void rows_kernel(const RowsArgs a)
+__device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const int n_wg)
 {
     using C = RowsCfg<RP, NW>;
     typedef typename YVec<C::OPL>::T yvec_t;
@@ -154,13 +154,14 @@ void rows_kernel(const RowsArgs a)
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int jg = w % C::JG, ks = w / C::JG;
     const int U = a.d_in >> 3;                               // 16-byte units per row of x / A
-    uint64_t *prof = a.prof ? a.prof + (int64_t)blockIdx.x * 8 : nullptr;
+    uint64_t *prof = a.prof ? a.prof + (int64_t)wg * 8 : nullptr;
     if (prof && tid == 0) { prof[0] = wall_clock64(); prof[7] = 0; }
 
     // Items are numbered over the upper bound of chunks, so an item's chunk record can be fetched
     // together with the live chunk count (and the launch tag) in one round trip.
     const int n_shr = SPLIT ? a.grid_chunks * a.ksplit : 0;
-    const int n_items = SPLIT ? n_shr + a.grid_chunks * a.ntiles : a.grid_chunks * a.tile_par;
+    const int n_items = SPLIT ? n_shr + a.grid_chunks * a.ntiles
+                              : (a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : a.grid_chunks);
 
     // Split launches carry a tag that must differ from launch to launch, also when a captured
     // graph replays the same kernel arguments, so it lives in device memory: every workgroup
@@ -168,14 +169,14 @@ void rows_kernel(const RowsArgs a)
     // the grid, when its own items are done, sees all sign-ins and advances the tag for the
     // next launch.  Nobody waits for an atomic's return value on the way in.
     uint32_t tag = 0;
-    const int grp = blockIdx.x & 63;
+    const int grp = wg & 63;
     if (SPLIT && tid == 0) {
         s_fail = 0;
         tag = __hip_atomic_load(a.ctrl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     bool first_item = true;
 
-    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    for (int item = wg; item < n_items; item += n_wg) {
         // ---- which chunk, which part of it ----
         int chunk, kslice = 0, tile0 = 0, tile1 = a.ntiles;
         bool do_shrink = true, do_expand = true;
@@ -183,7 +184,11 @@ void rows_kernel(const RowsArgs a)
             if (item < n_shr) { chunk = item / a.ksplit; kslice = item - chunk * a.ksplit; do_expand = false; }
             else { const int e = item - n_shr; chunk = e / a.ntiles; tile0 = e - chunk * a.ntiles; tile1 = tile0 + 1; do_shrink = false; }
         } else if (a.tile_par > 1) {
-            chunk = item / a.tile_par; tile0 = item - chunk * a.tile_par; tile1 = tile0 + 1;
+            // workgroups are dealt round-robin to the 8 XCDs: keep the tiles of one chunk (they all
+            // read the chunk's A rows) on one XCD and its L2, and deal the chunks over the XCDs
+            const int idx = item >> 3, grp8 = idx / a.tile_par;
+            chunk = grp8 * 8 + (item & 7); tile0 = idx - grp8 * a.tile_par; tile1 = tile0 + 1;
+            if (chunk >= a.grid_chunks) continue;
         } else {
             chunk = item;
         }
@@ -389,7 +394,7 @@ void rows_kernel(const RowsArgs a)
     if (SPLIT) {
         if (first_item && tid == 0 && tag != 0xffffffffu)       // a workgroup without items still signs in
             (void)__hip_atomic_fetch_add(a.ctrl + 8 + grp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (blockIdx.x == gridDim.x - 1 && w == 0) {
+        if (wg == n_wg - 1 && w == 0) {
             if (!first_item) tag = s_tag;
             else tag = __shfl(tag, 0, 64);
             uint32_t total = 0;
@@ -398,10 +403,10 @@ void rows_kernel(const RowsArgs a)
                 c += lane_xor<1>(c); c += lane_xor<2>(c); c += lane_xor<4>(c);
                 c += lane_xor<8>(c); c += lane_xor<16>(c); c += lane_xor<32>(c);
                 total = (uint32_t)c;                              // counts are far below 2^24: exact in fp32
-                if (total >= gridDim.x) break;
+                if (total >= (uint32_t)n_wg) break;
                 __builtin_amdgcn_s_sleep(2);
             }
-            if (total >= gridDim.x) {
+            if (total >= (uint32_t)n_wg) {
                 __hip_atomic_store(a.ctrl + 8 + lane, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (lane == 0) {
                     uint32_t nt = tag + 1;
@@ -413,6 +418,32 @@ void rows_kernel(const RowsArgs a)
             }
         }
     }
+}
+
+template <int RP, int NW, bool SPLIT>
+__global__ __launch_bounds__(NW * 64, (NW >= 8 && RP <= 16) ? 4 : 1)
+void rows_kernel(const RowsArgs a)
+{
+    rows_body<RP, NW, SPLIT>(a, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// Several sites that share a batch plan in one launch (q/k/v of one layer, or gate/up): site s owns
+// workgroups [first[s], first[s + 1]).  Only fused launches are grouped; nothing crosses workgroups.
+struct MultiArgs {
+    int32_t n;
+    int32_t first[kMaxMulti + 1];
+    RowsArgs site[kMaxMulti];
+};
+
+template <int RP, int NW>
+__global__ __launch_bounds__(NW * 64, (NW >= 8 && RP <= 16) ? 4 : 1)
+void rows_multi_kernel(const MultiArgs m)
+{
+    const int b = (int)blockIdx.x;
+    int s = 0;
+#pragma unroll
+    for (int k = 1; k < kMaxMulti; ++k) s += (k < m.n && b >= m.first[k]) ? 1 : 0;
+    rows_body<RP, NW, false>(m.site[s], b - m.first[s], m.first[s + 1] - m.first[s]);
 }
 
 template <int RP, int NW, bool SPLIT>
@@ -454,7 +485,8 @@ static hipError_t launch_rp(RowsArgs a, hipStream_t st)
     } else {
         a.mode = 0; a.ksplit = 1; a.kslice_units = U;
         a.tile_par = (mode == 3 || (mode == 0 && ksplit == 1 && a.n_experts == 1)) ? ntiles : 1;
-        rows_kernel<RP, NW, false><<<dim3((unsigned)(a.grid_chunks * a.tile_par)), dim3(NW * 64), 0, st>>>(a);
+        const unsigned grid = a.tile_par > 1 ? (unsigned)(((a.grid_chunks + 7) & ~7) * a.tile_par) : (unsigned)a.grid_chunks;
+        rows_kernel<RP, NW, false><<<dim3(grid), dim3(NW * 64), 0, st>>>(a);
     }
     return hipGetLastError();
 }
@@ -477,6 +509,52 @@ static hipError_t launch_nw(const RowsArgs &a, hipStream_t st)
     if (nw >= 8) return launch_rp<RP, 8>(a, st);
     if constexpr (RP < 64) return launch_rp<RP, 4>(a, st);
     return hipErrorInvalidValue;
+}
+
+// Fill in the fused-launch fields of one site; returns its number of workgroups.
+template <int RP, int NW>
+static int prepare_fused(RowsArgs &a)
+{
+    using C = RowsCfg<RP, NW>;
+    const int U = a.d_in >> 3;
+    a.ntiles = (a.d_out + C::TILE - 1) / C::TILE;
+    a.mode = 0; a.ksplit = 1; a.kslice_units = U;
+    a.tile_par = a.n_experts == 1 ? a.ntiles : 1;
+    return a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : a.grid_chunks;
+}
+
+template <int RP>
+static hipError_t launch_multi_rp(const RowsArgs *sites, int n, hipStream_t st)
+{
+    MultiArgs m;
+    m.n = n;
+    m.first[0] = 0;
+    for (int k = 0; k < n; ++k) {
+        m.site[k] = sites[k];
+        m.first[k + 1] = m.first[k] + prepare_fused<RP, 16>(m.site[k]);
+    }
+    for (int k = n; k < kMaxMulti; ++k) { m.site[k] = sites[0]; m.first[k + 1] = m.first[n]; }
+    rows_multi_kernel<RP, 16><<<dim3((unsigned)m.first[n]), dim3(16 * 64), 0, st>>>(m);
+    return hipGetLastError();
+}
+
+// Sites can share a launch when each of them alone would run the 16-wave fused shape.
+bool rows_can_group(const RowsArgs &a)
+{
+    if (a.r_pad != 8 && a.r_pad != 16) return false;
+    const int U = a.d_in >> 3;
+    const int flu8 = a.r_pad == 8 ? RowsCfg<8, 8>::FLU : RowsCfg<16, 8>::FLU;
+    const int flu16 = a.r_pad == 8 ? RowsCfg<8, 16>::FLU : RowsCfg<16, 16>::FLU;
+    return a.n_experts == 1 && U > flu8 && U <= flu16 && !tuning("rows_mode") && !tuning("rows_waves");
+}
+
+hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st)
+{
+    if (n < 1 || n > kMaxMulti) return hipErrorInvalidValue;
+    for (int k = 0; k < n; ++k)
+        if (sites[k].r_pad != sites[0].r_pad || !rows_can_group(sites[k])) return hipErrorInvalidValue;
+    if (sites[0].grid_chunks <= 0) return hipSuccess;
+    return sites[0].r_pad == 8 ? launch_multi_rp<8>(sites, n, st) : launch_multi_rp<16>(sites, n, st);
 }
 
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st)

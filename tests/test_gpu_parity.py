@@ -152,6 +152,68 @@ def test_decode_large_batch_general_planner(M, oracle):
     check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0))
 
 
+def test_decode_multi_site_launch(M, oracle):
+    """Sites that share a plan in one launch (the q/k/v pattern): identical to separate calls and
+    right against the oracle; a site that cannot be grouped (small d_in) still gets its own launch."""
+    shapes = [(2304, 264, 16), (2304, 1032, 16), (2304, 2056, 16), (128, 72, 16), (2304, 520, 16), (2304, 264, 16)]
+    slots = W.rng(31).integers(-1, 5, size=61).astype(np.int32)
+    cases = [W.dense_case(f"multi{i}", 3100 + i, 61, di, do, 5, r, 32.0, token_slot=slots, std_a=0.05, std_b=0.05)
+             for i, (di, do, r) in enumerate(shapes)]
+    sites = [dense_site(M, c) for c in cases]
+    plan = M.Plan(61, 5)
+    M.lora_plan_decode(plan, torch.from_numpy(slots).cuda(), 5)
+    xs = [P.dev_bf16(c.x) for c in cases]
+    ys = [P.dev_bf16(c.y0) for c in cases]
+    M.lora_apply_decode_multi(sites, plan, xs, ys)
+    torch.cuda.synchronize()
+    for c, site, x, y in zip(cases, sites, xs, ys):
+        ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+        got = P.host_bits(y)
+        P.check_close(got, ref, c.name)
+        P.check_untouched(got, c.y0, c.token_slot < 0, c.name)
+        y1 = P.dev_bf16(c.y0)
+        M.lora_apply_decode_planned(site, plan, x, y1)
+        torch.cuda.synchronize()
+        assert np.array_equal(P.host_bits(y1), got), c.name
+        dref = oracle.apply_decode(c.x, np.zeros_like(c.y0), c.A, c.B, c.rank, c.alpha, c.token_slot)
+        P.noop_must_fail(c.y0, dref, np.nonzero(c.token_slot >= 0)[0])
+
+
+def test_graph_replay_keeps_results_right(M, oracle):
+    """A captured graph replays the same kernel arguments; the launches that exchange partial
+    results between workgroups must still tell one replay from the next.  Inputs change between
+    replays, every replay is compared with the eager result."""
+    c = W.dense_case("graph", 3200, 40, 4608, 264, 4, 16, 32.0, std_a=0.05, std_b=0.05)     # d_in needs the split launch
+    site = dense_site(M, c)
+    plan = M.Plan(40, 4)
+    ts = torch.from_numpy(c.token_slot).cuda()
+    x, y = P.dev_bf16(c.x), P.dev_bf16(c.y0)
+
+    def step():
+        M.lora_plan_decode(plan, ts, 4)
+        M.lora_apply_decode_planned(site, plan, x, y)
+    step()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(4):
+        xr = W.normal_bf16(W.rng(3300 + rep), c.x.shape, 1.0)
+        x.copy_(P.dev_bf16(xr))
+        y.copy_(P.dev_bf16(c.y0))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = P.host_bits(y)
+        y2 = P.dev_bf16(c.y0)
+        M.lora_apply_decode_planned(site, plan, x, y2)          # eager, same inputs
+        torch.cuda.synchronize()
+        assert np.array_equal(got, P.host_bits(y2)), f"replay {rep} differs from the eager launch"
+        ref = oracle.apply_decode(xr, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+        P.check_close(got, ref, f"replay {rep}")
+    site.check()
+
+
 def test_c2_dense_decode_layer(M, oracle):
     cases = W.c2_dense_decode()
     ts = torch.from_numpy(cases[0].token_slot).cuda()
