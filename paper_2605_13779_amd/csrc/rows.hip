@@ -161,7 +161,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
     // together with the live chunk count (and the launch tag) in one round trip.
     const int n_shr = SPLIT ? a.grid_chunks * a.ksplit : 0;
     const int n_items = SPLIT ? n_shr + a.grid_chunks * a.ntiles
-                              : (a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : a.grid_chunks);
+                              : (a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : ((a.grid_chunks + 63) & ~63));
 
     // Split launches carry a tag that must differ from launch to launch, also when a captured
     // graph replays the same kernel arguments, so it lives in device memory: every workgroup
@@ -190,7 +190,12 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
             chunk = grp8 * 8 + (item & 7); tile0 = idx - grp8 * a.tile_par; tile1 = tile0 + 1;
             if (chunk >= a.grid_chunks) continue;
         } else {
-            chunk = item;
+            // neighbouring chunks can belong to one adapter (and expert): keep them on one XCD, where
+            // the second chunk finds the adapter rows in L2 (workgroups are dealt round-robin to 8 XCDs)
+            // (runs of 8 chunks per XCD, dealt cyclically, so the unused tail of the records spreads evenly)
+            const int idx = item >> 3;
+            chunk = ((idx >> 3) * 8 + (item & 7)) * 8 + (idx & 7);
+            if (chunk >= a.grid_chunks) continue;
         }
         // The whole record is fetched before its count is looked at (one round trip, not two).
         const int4 *rec = (const int4 *)(a.chunks + (int64_t)chunk * kRec);
@@ -485,7 +490,7 @@ static hipError_t launch_rp(RowsArgs a, hipStream_t st)
     } else {
         a.mode = 0; a.ksplit = 1; a.kslice_units = U;
         a.tile_par = (mode == 3 || (mode == 0 && ksplit == 1 && a.n_experts == 1)) ? ntiles : 1;
-        const unsigned grid = a.tile_par > 1 ? (unsigned)(((a.grid_chunks + 7) & ~7) * a.tile_par) : (unsigned)a.grid_chunks;
+        const unsigned grid = a.tile_par > 1 ? (unsigned)(((a.grid_chunks + 7) & ~7) * a.tile_par) : (unsigned)((a.grid_chunks + 63) & ~63);
         rows_kernel<RP, NW, false><<<dim3(grid), dim3(NW * 64), 0, st>>>(a);
     }
     return hipGetLastError();
@@ -520,7 +525,7 @@ static int prepare_fused(RowsArgs &a)
     a.ntiles = (a.d_out + C::TILE - 1) / C::TILE;
     a.mode = 0; a.ksplit = 1; a.kslice_units = U;
     a.tile_par = a.n_experts == 1 ? a.ntiles : 1;
-    return a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : a.grid_chunks;
+    return a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : ((a.grid_chunks + 63) & ~63);
 }
 
 template <int RP>
