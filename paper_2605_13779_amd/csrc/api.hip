@@ -45,6 +45,8 @@ constexpr int32_t kSegCap = 65536;             // segment tiles / chunks per cal
 constexpr int32_t kXchChunks = 256;            // chunks per launch that may use the split shape
 constexpr size_t kCtrlBytes = 1024;
 constexpr size_t kXchBytes = (size_t)kXchChunks * 128 * kChunk * 8;   // <= 128 values per row of a chunk
+constexpr int32_t kSegXchBlocks = 1024;        // rank-64 sites: tile partials of 32 x 64 words shared inside a cluster
+constexpr size_t kSegXchBytes = (size_t)kSegXchBlocks * 32 * 64 * 8;
 
 std::mutex g_tune_mu;
 std::map<std::string, int> g_tune;
@@ -131,7 +133,7 @@ RowsArgs rows_args(const mlora_site *s, const void *x, int64_t ldx, void *y, int
     a.meta.rank = s->rank; a.meta.scale = s->scale;
     a.d_in = s->d.d_in; a.d_out = s->d.d_out; a.r_pad = s->r_pad;
     a.n_experts = s->E; a.top_k = 1;
-    a.xch = s->xch; a.ctrl = s->ctrl; a.xch_chunks = s->xch ? kXchChunks : 0;
+    a.xch = s->xch; a.ctrl = s->ctrl; a.xch_chunks = s->xch ? kXchChunks : 0;   // a rank-64 site's larger area holds these too
     a.prof = debug_prof();
     return a;
 }
@@ -249,7 +251,7 @@ int32_t mlora_site_bytes(const mlora_site_desc *d, size_t *a_tab, size_t *b_tab,
     *b_tab = align256((size_t)d->n_slots * E * d->d_out * rp * 2);
     *meta = align256((size_t)d->n_slots * 16);
     *scratch = align256(plan_words(priv_items(d), (int64_t)d->n_slots * E) * 4) + align256((size_t)kSegCap * 3 * 4)
-             + (d->n_experts > 0 ? 0 : kCtrlBytes + kXchBytes);
+             + (d->n_experts > 0 ? 0 : kCtrlBytes + (round_pow2(d->r_max) == 64 ? kSegXchBytes : kXchBytes));
     return MLORA_OK;
 }
 
@@ -285,7 +287,7 @@ int32_t mlora_site_create(const mlora_site_desc *d, void *a_tab, void *b_tab, vo
     meta_clear_kernel<<<dim3((d->n_slots + 255) / 256), dim3(256), 0, 0>>>(s->rank, s->scale, s->catalog, d->n_slots);
     hipError_t e = launch_fill_i32(s->priv.pv.hdr, 0, 8 + 3 * (NK + 1), 0);
     if (ok(e) && s->ctrl) {
-        e = launch_fill_i32((int32_t *)s->ctrl, 0, (int64_t)((kCtrlBytes + kXchBytes) / 4), 0);   // tag 0 = never written
+        e = launch_fill_i32((int32_t *)s->ctrl, 0, (int64_t)((kCtrlBytes + (s->r_pad == 64 ? kSegXchBytes : kXchBytes)) / 4), 0);   // tag 0 = never written
         if (ok(e)) e = launch_fill_i32((int32_t *)s->ctrl, 1, 1, 0);                               // first launch tag
     }
     if (!ok(e) || !ok(hipGetLastError()) || !ok(hipStreamSynchronize(0))) { delete s; return MLORA_E_HIP; }
@@ -557,6 +559,7 @@ int32_t lora_apply_segmented(mlora_site *s, const void *x, int64_t ldx, void *y,
         a.x = (const uint16_t *)x; a.ldx = ldx; a.y = (uint16_t *)y; a.ldy = ldy;
         a.a_tab = s->a_tab; a.b_tab = s->b_tab; a.meta.rank = s->rank; a.meta.scale = s->scale;
         a.tiles = s->seg_dev; a.n_tiles = n_units; a.d_in = s->d.d_in; a.d_out = s->d.d_out;
+        a.xch = s->xch; a.ctrl = s->ctrl; a.xch_blocks = s->xch ? kSegXchBlocks : 0; a.cluster = 1;
         return ok(launch_seg_mfma(a, st)) ? MLORA_OK : MLORA_E_HIP;
     }
     RowsArgs a = rows_args(s, x, ldx, y, ldy);

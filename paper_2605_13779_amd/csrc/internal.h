@@ -84,6 +84,11 @@ struct SegArgs {
     const int32_t *tiles;    // [3 * n_tiles]: slot, first row, rows (<= 32)
     int32_t n_tiles;
     int32_t d_in, d_out;
+    // exchange area of the site, used when a tile is shared by a cluster of workgroups
+    uint64_t *xch;           // [n_tiles * cluster][32 * 64] words
+    uint32_t *ctrl;          // launch tag / error flag / sign-in counters (same block as the vector kernel's)
+    int32_t xch_blocks;      // capacity of xch in blocks of 32 * 64 words
+    int32_t cluster;         // filled in by the launcher: workgroups per tile (1, 2 or 4)
 };
 hipError_t launch_seg_mfma(const SegArgs &a, hipStream_t st);
 
@@ -98,6 +103,58 @@ namespace mlora {
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+// ---- exchange of partial results between workgroups of ONE launch ----------------------------
+// A word is (launch tag << 32) | fp32 bits, written and read with single relaxed device-scope
+// 64-bit accesses, so a reader that sees the tag also sees the value and no fences are needed.
+// The tag must differ from launch to launch, also when a captured graph replays the same kernel
+// arguments, so it lives in device memory (ctrl[0]): every workgroup reads it, then signs in with a
+// fire-and-forget add on one of 64 counters (ctrl[8..72)); the last workgroup of the grid, once its
+// own work is done, sees all sign-ins, clears the counters and advances the tag.  ctrl[1] is an
+// error flag raised when a bounded wait gives up.
+constexpr int kSpinLimit = 1 << 18;
+
+__device__ __forceinline__ void xch_put(uint64_t *p, float v, uint32_t tag)
+{
+    __hip_atomic_store(p, ((uint64_t)tag << 32) | __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t xch_get(const uint64_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t tag_read(const uint32_t *ctrl)
+{
+    return __hip_atomic_load(ctrl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// One thread per workgroup, after its tag_read has returned (the branch makes the add depend on it).
+__device__ __forceinline__ void tag_sign_in(uint32_t *ctrl, int wg, uint32_t tag)
+{
+    if (tag != 0xffffffffu)
+        (void)__hip_atomic_fetch_add(ctrl + 8 + (wg & 63), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Called by one full wave of the last workgroup of the grid when its work is done.
+__device__ __forceinline__ void tag_advance(uint32_t *ctrl, int n_wg, uint32_t tag, int lane)
+{
+    uint32_t total = 0;
+    for (int spins = 0; spins < kSpinLimit; ++spins) {
+        int c = (int)__hip_atomic_load(ctrl + 8 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) c += __shfl_xor(c, d, 64);
+        total = (uint32_t)c;
+        if (total >= (uint32_t)n_wg) break;
+        __builtin_amdgcn_s_sleep(2);
+    }
+    if (total >= (uint32_t)n_wg) {
+        __hip_atomic_store(ctrl + 8 + lane, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (lane == 0) {
+            uint32_t nt = tag + 1;
+            if (nt == 0 || nt == 0xffffffffu) nt = 1;
+            __hip_atomic_store(ctrl, nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    } else if (lane == 0) {
+        __hip_atomic_store(ctrl + 1, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // never expected
+    }
+}
 
 // Streaming accesses (touched once per launch): the non-temporal hint keeps them from pushing
 // the adapter tables, which are re-read by many workgroups, out of L2.

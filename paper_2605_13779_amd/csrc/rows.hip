@@ -126,20 +126,6 @@ __device__ __forceinline__ void y_pack(const float *f, uint4 &r)
     r.z = pack_bf2(f[4], f[5]); r.w = pack_bf2(f[6], f[7]);
 }
 
-// ---- exchange of partial shrink results between workgroups of one launch --------------------
-// One 64-bit word = (launch tag << 32) | fp32 bits, written and read with single relaxed
-// device-scope accesses: a reader that sees the tag also sees the value.
-__device__ __forceinline__ void xch_put(uint64_t *p, float v, uint32_t tag)
-{
-    __hip_atomic_store(p, ((uint64_t)tag << 32) | __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint64_t xch_get(const uint64_t *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-constexpr int kSpinLimit = 1 << 18;     // polls before an expand item gives up and raises the error flag
-
 // Work of workgroup `wg` out of `n_wg` on one site (one launch may cover several sites).
 template <int RP, int NW, bool SPLIT>
 __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const int n_wg)
@@ -169,10 +155,9 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
     // the grid, when its own items are done, sees all sign-ins and advances the tag for the
     // next launch.  Nobody waits for an atomic's return value on the way in.
     uint32_t tag = 0;
-    const int grp = wg & 63;
     if (SPLIT && tid == 0) {
         s_fail = 0;
-        tag = __hip_atomic_load(a.ctrl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        tag = tag_read(a.ctrl);
     }
     bool first_item = true;
 
@@ -208,8 +193,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         if (SPLIT && first_item) {
             if (tid == 0) {
                 s_tag = tag;
-                if (tag != 0xffffffffu)      // always true; the sign-in is issued after the tag has arrived
-                    (void)__hip_atomic_fetch_add(a.ctrl + 8 + grp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                tag_sign_in(a.ctrl, wg, tag);
             }
             __syncthreads();
             tag = s_tag;
@@ -397,30 +381,11 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
 
     // ---- tag bookkeeping ----
     if (SPLIT) {
-        if (first_item && tid == 0 && tag != 0xffffffffu)       // a workgroup without items still signs in
-            (void)__hip_atomic_fetch_add(a.ctrl + 8 + grp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (first_item && tid == 0) tag_sign_in(a.ctrl, wg, tag);   // a workgroup without items still signs in
         if (wg == n_wg - 1 && w == 0) {
             if (!first_item) tag = s_tag;
             else tag = __shfl(tag, 0, 64);
-            uint32_t total = 0;
-            for (int spins = 0; spins < kSpinLimit; ++spins) {
-                float c = (float)__hip_atomic_load(a.ctrl + 8 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                c += lane_xor<1>(c); c += lane_xor<2>(c); c += lane_xor<4>(c);
-                c += lane_xor<8>(c); c += lane_xor<16>(c); c += lane_xor<32>(c);
-                total = (uint32_t)c;                              // counts are far below 2^24: exact in fp32
-                if (total >= (uint32_t)n_wg) break;
-                __builtin_amdgcn_s_sleep(2);
-            }
-            if (total >= (uint32_t)n_wg) {
-                __hip_atomic_store(a.ctrl + 8 + lane, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (lane == 0) {
-                    uint32_t nt = tag + 1;
-                    if (nt == 0 || nt == 0xffffffffu) nt = 1;
-                    __hip_atomic_store(a.ctrl, nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            } else if (lane == 0) {
-                __hip_atomic_store(a.ctrl + 1, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // never expected
-            }
+            tag_advance(a.ctrl, n_wg, tag, lane);
         }
     }
 }

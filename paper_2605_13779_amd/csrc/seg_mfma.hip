@@ -55,14 +55,32 @@ void seg_mfma_kernel(const SegArgs a)
     uint16_t *hh = (uint16_t *)(buf + RED_BYTES);
     uint16_t *hl = hh + TM * H_LD;
 
-    const int per_xcd = gridDim.x >> 3;
-    const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (v >= a.n_tiles) return;
-    const int slot = a.tiles[3 * v], row0 = a.tiles[3 * v + 1], nrows = a.tiles[3 * v + 2];
-    if (slot < 0 || a.meta.rank[slot] <= 0) return;
-    const float scale = a.meta.scale[slot];
-
+    __shared__ uint32_t s_tag;
+    __shared__ int s_fail;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, kh = lane >> 5;
+    const int G = a.cluster;                  // workgroups that share one tile: k-slices of the shrink, output slices of the expand
+    const int n_wg = (int)gridDim.x;
+    const bool last_wg = (int)blockIdx.x == n_wg - 1;
+    uint32_t tag = 0;
+    if (G > 1) {
+        if (tid == 0) { tag = tag_read(a.ctrl); s_tag = tag; s_fail = 0; tag_sign_in(a.ctrl, (int)blockIdx.x, tag); }
+        __syncthreads();
+        tag = s_tag;
+    }
+    // neighbouring work ids share an XCD (workgroups are dealt round-robin to 8 XCDs): the tiles of one
+    // segment reuse its adapter in L2, and the members of a cluster sit next to each other in dispatch order
+    const int per_xcd = n_wg >> 3;
+    const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const int tile = v / G, g = v - tile * G;
+    bool live = tile < a.n_tiles;
+    int slot = -1, row0 = 0, nrows = 1;
+    if (live) { slot = a.tiles[3 * tile]; row0 = a.tiles[3 * tile + 1]; nrows = a.tiles[3 * tile + 2]; }
+    live = live && slot >= 0 && a.meta.rank[slot] > 0;
+    if (!live) {
+        if (G > 1 && last_wg && w == 0) tag_advance(a.ctrl, n_wg, tag, lane);
+        return;
+    }
+    const float scale = a.meta.scale[slot];
 
     // ---------------- shrink: k tiles of [32 x rows + 64 A rows] x 256 staged through LDS ----------------
     {
@@ -76,9 +94,12 @@ void seg_mfma_kernel(const SegArgs a)
                             : a.a_tab + ((int64_t)slot * 64 + (r - 32)) * a.d_in + sseg * 8;
         }
         f32x16_t acc0 = {0}, acc1 = {0};
-        const int n_kt = (a.d_in + KT - 1) / KT;
+        const int n_kt_all = (a.d_in + KT - 1) / KT;
+        const int kt_per = (n_kt_all + G - 1) / G;
+        const int kt0 = g * kt_per;                            // this member's k tiles: [kt0, kt0 + n_kt)
+        const int n_kt = max(0, min(n_kt_all, kt0 + kt_per) - kt0);
         auto fetch = [&](int t, uint4 (&stage)[6]) {
-            const int k0 = t * KT;
+            const int k0 = (kt0 + t) * KT;
             const bool in = t < n_kt && k0 + sseg * 8 < a.d_in;   // d_in is a multiple of 16: a segment is in or out as a whole
 #pragma unroll
             for (int q = 0; q < 6; ++q) {
@@ -126,18 +147,66 @@ void seg_mfma_kernel(const SegArgs a)
         }
     }
     __syncthreads();
-    for (int e = tid; e < TM * 64; e += NT) {
-        float s = 0.f;
+    {
+        float part[4];                                           // TM * 64 / NT elements per thread
 #pragma unroll
-        for (int k = 0; k < NW; ++k) s += ((const float *)buf)[e + k * TM * 64];
-        s *= scale;
-        const uint32_t hi = f2bf(s);
-        const uint32_t lo = f2bf(s - __uint_as_float(hi << 16));
-        const int tok = e >> 6, j = e & 63;
-        hh[tok * H_LD + j] = (uint16_t)hi;
-        hl[tok * H_LD + j] = (uint16_t)lo;
+        for (int q = 0; q < 4; ++q) {
+            const int e = tid + q * NT;
+            float s = 0.f;
+#pragma unroll
+            for (int k = 0; k < NW; ++k) s += ((const float *)buf)[e + k * TM * 64];
+            part[q] = s;
+        }
+        bool ok = true;
+        if (G > 1) {
+            // publish this member's partial, then add the members' partials in member order, so that
+            // every member of the cluster ends up with bit-identical h
+            uint64_t *mine = a.xch + ((int64_t)tile * G + g) * (TM * 64);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) xch_put(mine + tid + q * NT, part[q], tag);
+            float tot[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int gg = 0; gg < G; ++gg) {
+                if (gg == g) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) tot[q] += part[q];
+                    continue;
+                }
+                const uint64_t *src = a.xch + ((int64_t)tile * G + gg) * (TM * 64);
+                uint64_t wv[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) wv[q] = xch_get(src + tid + q * NT);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    int spins = 0;
+                    while ((uint32_t)(wv[q] >> 32) != tag) {
+                        if (++spins > kSpinLimit) { ok = false; break; }
+                        __builtin_amdgcn_s_sleep(1);
+                        wv[q] = xch_get(src + tid + q * NT);
+                    }
+                    tot[q] += __uint_as_float((uint32_t)wv[q]);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) part[q] = tot[q];
+        }
+        if (!ok) s_fail = 1;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = tid + q * NT;
+            const float s = part[q] * scale;
+            const uint32_t hi = f2bf(s);
+            const uint32_t lo = f2bf(s - __uint_as_float(hi << 16));
+            const int tok = e >> 6, j = e & 63;
+            hh[tok * H_LD + j] = (uint16_t)hi;
+            hl[tok * H_LD + j] = (uint16_t)lo;
+        }
     }
     __syncthreads();
+    if (G > 1 && s_fail) {                       // a member never showed up (not expected): leave y alone, raise the flag
+        if (tid == 0) __hip_atomic_store(a.ctrl + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (last_wg && w == 0) tag_advance(a.ctrl, n_wg, tag, lane);
+        return;
+    }
     uint4 hA[4], lA[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -155,7 +224,9 @@ void seg_mfma_kernel(const SegArgs a)
     unsigned char *wt = buf + w * WAVE_BYTES;
     float *stg = (float *)wt;
     const int og = lane & 7, tr = lane >> 3;          // 8 lanes cover 128 bytes of one row
-    for (int n0 = w * WB; n0 < a.d_out; n0 += NW * WB) {
+    const int out_per = ((a.d_out + WB * G - 1) / (WB * G)) * WB;      // outputs per member, a multiple of a pass
+    const int out_lo = g * out_per, out_hi = min(a.d_out, out_lo + out_per);
+    for (int n0 = out_lo + w * WB; n0 < out_hi; n0 += NW * WB) {
         const int oc = n0 + og * 8;
         uint4 yv[4], braw[8];
 #pragma unroll
@@ -206,12 +277,30 @@ void seg_mfma_kernel(const SegArgs a)
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     }
+    if (G > 1 && last_wg && w == 0) tag_advance(a.ctrl, n_wg, tag, lane);
 }
 
-hipError_t launch_seg_mfma(const SegArgs &a, hipStream_t st)
+hipError_t launch_seg_mfma(const SegArgs &a_in, hipStream_t st)
 {
-    if (a.n_tiles <= 0) return hipSuccess;
-    const unsigned grid = (unsigned)((a.n_tiles + 7) / 8 * 8);
+    if (a_in.n_tiles <= 0) return hipSuccess;
+    SegArgs a = a_in;
+    // Cluster size: more workgroups than CUs evens out the load (tiles are cut per segment, so their
+    // number is rarely a multiple of the CU count) and halves each workgroup's chain of dependent
+    // passes.  Members of a cluster are neighbours in dispatch order, so a member that is not resident
+    // yet gets its slot as soon as any complete cluster retires; waits are bounded anyway.
+    static int cap = 0;
+    if (cap == 0) {
+        int per_cu = 0, cus = 0, dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return hipErrorUnknown;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, seg_mfma_kernel, NT, 0) != hipSuccess) return hipErrorUnknown;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return hipErrorUnknown;
+        cap = per_cu * cus;
+    }
+    int g = tuning("seg_cluster");                        // 0 auto, 1 / 2 / 4 forced
+    if (g != 1 && g != 2 && g != 4) g = a.n_tiles * 2 <= cap + cap / 8 ? 2 : 1;
+    while (g > 1 && (!a.xch || !a.ctrl || (int64_t)a.n_tiles * g > a.xch_blocks || (int64_t)a.n_tiles * g > 2 * (int64_t)cap)) g >>= 1;
+    a.cluster = g;
+    const unsigned grid = (unsigned)(((int64_t)a.n_tiles * g + 7) / 8 * 8);
     seg_mfma_kernel<<<dim3(grid), dim3(NT), 0, st>>>(a);
     return hipGetLastError();
 }
