@@ -122,7 +122,8 @@ int32_t lora_apply_decode_planned(mlora_site *site, const mlora_plan *plan,
  * (q/k/v of one layer, or gate/up, are independent of each other and can share one launch; sites
  * whose shape needs the split launch get one of their own).  sites, xs, ldxs, ys, ldys are HOST
  * arrays of length n_sites; each (site, x, y) triple follows the rules of
- * lora_apply_decode_planned.  The result equals n_sites separate calls. */
+ * lora_apply_decode_planned.  The result is that of n_sites separate calls up to the order in which
+ * the fp32 partial sums of the shrink are added (a launch may cut d_in into more or fewer slices). */
 int32_t lora_apply_decode_multi(mlora_site *const *sites, int32_t n_sites, const mlora_plan *plan,
                                 const void *const *xs, const int64_t *ldxs,
                                 void *const *ys, const int64_t *ldys, void *stream);

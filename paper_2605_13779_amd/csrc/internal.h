@@ -36,9 +36,9 @@ size_t plan_words(int64_t max_items, int64_t n_keys);
 PlanView plan_view(void *base, int64_t max_items, int64_t n_keys);
 inline int64_t max_chunks(int64_t items, int64_t n_keys)
 {
+    // sum over groups of ceil(n_g / kChunk) <= (items + (kChunk - 1) * groups) / kChunk
     int64_t touched = n_keys < items ? n_keys : items;
-    int64_t bound = touched + items / kChunk + 1;
-    return bound < items ? bound : items;
+    return (items + (kChunk - 1) * touched) / kChunk;
 }
 
 // plan.hip
@@ -65,9 +65,10 @@ struct RowsArgs {
     uint32_t *ctrl;          // [0] launch tag, [1] error flag, [2] top sign-in, [8..72) group sign-ins
     int32_t xch_chunks;
     // filled in by the launcher
-    int32_t mode;            // 0 fused, 1 split
+    int32_t mode;            // 0 nothing crosses workgroups; 1 shrink items + expand items; 2 parts that trade k-slices
     int32_t ksplit, kslice_units, ntiles;
-    int32_t tile_par;        // fused launches: 1 = an item expands every tile, ntiles = one tile per item
+    int32_t tile_par;        // parts a chunk is cut into (one item each; 1 = one item per chunk): part p expands
+    int32_t out_per_part;    // outputs [p * out_per_part, ...) and, in mode 2, shrinks k-slice p
     uint64_t *prof;          // debug: per-workgroup phase timestamps (null in normal use)
 };
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st);
@@ -103,6 +104,8 @@ namespace mlora {
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 
 // ---- exchange of partial results between workgroups of ONE launch ----------------------------
 // A word is (launch tag << 32) | fp32 bits, written and read with single relaxed device-scope
@@ -113,6 +116,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 // own work is done, sees all sign-ins, clears the counters and advances the tag.  ctrl[1] is an
 // error flag raised when a bounded wait gives up.
 constexpr int kSpinLimit = 1 << 18;
+constexpr int kPollLimit = 512;   // polls of an exchange word before a reader computes the value itself
 
 __device__ __forceinline__ void xch_put(uint64_t *p, float v, uint32_t tag)
 {

@@ -33,8 +33,15 @@ struct RowsCfg {
     static constexpr int NV  = CS * JPW;                 // values per lane per pass (8)
     static constexpr int OPL = RP >= 8 ? 1 : 8 / RP;     // outputs per lane in the expand
     static constexpr int BV  = RP >= 8 ? RP / 8 : 1;     // 16-byte loads of B per lane
-    static constexpr int TILE = RP <= 4 ? NT * OPL : (RP <= 16 ? (NW == 16 ? 2048 : 1024) : (NW == 16 ? 1024 : 512));   // outputs per expand flight
+    static constexpr int TILE = RP <= 4 ? NT * OPL : (RP <= 16 ? 1024 : 512);   // outputs per expand tile
+    static constexpr int DEPTH = NW == 16 ? 2 : 1;       // expand tiles kept in flight by an item that walks several
     static constexpr int EU  = TILE / (NT * OPL);        // outputs groups per lane per flight
+    // The expand of a 4-row chunk is a small dense contraction (4 x RP times RP x 64 per wave and
+    // output group); on the vector ALU it costs 4 * RP multiply-adds per lane and was what bounded
+    // these kernels.  For RP = 8 and 16 it runs on the matrix cores instead: the 4x4x4 bf16 MFMA
+    // works on 16 independent 4x4 blocks, lane l = (block l/4, column l%4), so lane l's result
+    // column is its own output and its four accumulator registers are the chunk's four rows.
+    static constexpr bool MX = (RP == 8 || RP == 16) && kChunk == 4;
     static_assert(JG * KS == NW && EU >= 1, "wave layout");
 };
 
@@ -89,6 +96,18 @@ __device__ __forceinline__ void wave_sum_transpose(float (&v)[N], int lane)
     TransposeStep<N, N / 2, 1>::run(v, lane);
 }
 
+// Calls f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N - 1>): a loop whose
+// index is a compile-time constant inside the body (register arrays stay in registers).
+template <int I> struct IntC { static constexpr int value = I; };
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(IntC<I>{});
+        static_for<N, I + 1>(f);
+    }
+}
+
 template <int BITS>
 __device__ __forceinline__ int bitrev(int x)
 {
@@ -127,15 +146,16 @@ __device__ __forceinline__ void y_pack(const float *f, uint4 &r)
 }
 
 // Work of workgroup `wg` out of `n_wg` on one site (one launch may cover several sites).
-template <int RP, int NW, bool SPLIT>
+// XCH: the kernel can pass partial shrink results between workgroups (a.mode 1 or 2).
+template <int RP, int NW, bool XCH>
 __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const int n_wg)
 {
     using C = RowsCfg<RP, NW>;
     typedef typename YVec<C::OPL>::T yvec_t;
-    __shared__ float hs[kChunk][RP];
+    __shared__ __attribute__((aligned(16))) float hs[kChunk][RP];
     __shared__ float part[C::KS][kChunk][RP];
     __shared__ uint32_t s_tag;
-    __shared__ int s_fail;
+    __shared__ uint32_t s_missing;
 
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int jg = w % C::JG, ks = w / C::JG;
@@ -143,36 +163,53 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
     uint64_t *prof = a.prof ? a.prof + (int64_t)wg * 8 : nullptr;
     if (prof && tid == 0) { prof[0] = wall_clock64(); prof[7] = 0; }
 
+    const bool use_x = XCH && a.mode != 0;                   // this site's items exchange partial results
+    const bool two_kinds = XCH && a.mode == 1;               // shrink items and expand items
     // Items are numbered over the upper bound of chunks, so an item's chunk record can be fetched
     // together with the live chunk count (and the launch tag) in one round trip.
-    const int n_shr = SPLIT ? a.grid_chunks * a.ksplit : 0;
-    const int n_items = SPLIT ? n_shr + a.grid_chunks * a.ntiles
-                              : (a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : ((a.grid_chunks + 63) & ~63));
+    const int n_shr = two_kinds ? a.grid_chunks * a.ksplit : 0;
+    const int n_items = two_kinds ? n_shr + a.grid_chunks * a.ntiles
+                                  : (a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : ((a.grid_chunks + 63) & ~63));
 
-    // Split launches carry a tag that must differ from launch to launch, also when a captured
-    // graph replays the same kernel arguments, so it lives in device memory: every workgroup
-    // reads it, then signs in (fire-and-forget add on one of 64 counters); the last workgroup of
-    // the grid, when its own items are done, sees all sign-ins and advances the tag for the
-    // next launch.  Nobody waits for an atomic's return value on the way in.
+    // Launches that exchange carry a tag that must differ from launch to launch, also when a
+    // captured graph replays the same kernel arguments, so it lives in device memory: every
+    // workgroup reads it, then signs in (fire-and-forget add on one of 64 counters); the last
+    // workgroup of the grid, when its own items are done, sees all sign-ins and advances the tag
+    // for the next launch.  Nobody waits for an atomic's return value on the way in.
     uint32_t tag = 0;
-    if (SPLIT && tid == 0) {
-        s_fail = 0;
-        tag = tag_read(a.ctrl);
+    if (XCH && tid == 0) {
+        s_missing = 0;
+        if (use_x) tag = tag_read(a.ctrl);
     }
     bool first_item = true;
+    // An item is taken a second time only after a bounded wait for another workgroup's partial sums
+    // has given up: it then runs on its own, with the whole shrink.
+    bool solo_next = false;
 
     for (int item = wg; item < n_items; item += n_wg) {
         // ---- which chunk, which part of it ----
-        int chunk, kslice = 0, tile0 = 0, tile1 = a.ntiles;
+        int chunk, kslice = 0, out0 = 0, out1 = a.d_out;
         bool do_shrink = true, do_expand = true;
-        if (SPLIT) {
+        const bool solo = solo_next;
+        solo_next = false;
+        if (two_kinds) {
             if (item < n_shr) { chunk = item / a.ksplit; kslice = item - chunk * a.ksplit; do_expand = false; }
-            else { const int e = item - n_shr; chunk = e / a.ntiles; tile0 = e - chunk * a.ntiles; tile1 = tile0 + 1; do_shrink = false; }
+            else {
+                const int e = item - n_shr;
+                chunk = e / a.ntiles;
+                out0 = (e - chunk * a.ntiles) * C::TILE; out1 = min(a.d_out, out0 + C::TILE);
+                do_shrink = solo;
+            }
         } else if (a.tile_par > 1) {
-            // workgroups are dealt round-robin to the 8 XCDs: keep the tiles of one chunk (they all
-            // read the chunk's A rows) on one XCD and its L2, and deal the chunks over the XCDs
+            // workgroups are dealt round-robin to the 8 XCDs: keep the parts of one chunk (they share
+            // the chunk's rows of x and its exchange words) on one XCD and its L2, and deal the chunks
+            // over the XCDs
             const int idx = item >> 3, grp8 = idx / a.tile_par;
-            chunk = grp8 * 8 + (item & 7); tile0 = idx - grp8 * a.tile_par; tile1 = tile0 + 1;
+            const int part_i = idx - grp8 * a.tile_par;
+            chunk = grp8 * 8 + (item & 7);
+            out0 = part_i * a.out_per_part; out1 = min(a.d_out, out0 + a.out_per_part);
+            do_expand = out0 < out1;
+            if (use_x && !solo) { kslice = part_i; do_shrink = part_i < a.ksplit; }   // else every part does the whole shrink
             if (chunk >= a.grid_chunks) continue;
         } else {
             // neighbouring chunks can belong to one adapter (and expert): keep them on one XCD, where
@@ -190,10 +227,10 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         int row[kChunk];
         row[0] = __builtin_amdgcn_readfirstlane(r1.x); row[1] = __builtin_amdgcn_readfirstlane(r1.y);
         row[2] = __builtin_amdgcn_readfirstlane(r1.z); row[3] = __builtin_amdgcn_readfirstlane(r1.w);
-        if (SPLIT && first_item) {
+        if (XCH && first_item) {
             if (tid == 0) {
                 s_tag = tag;
-                tag_sign_in(a.ctrl, wg, tag);
+                if (use_x) tag_sign_in(a.ctrl, wg, tag);
             }
             __syncthreads();
             tag = s_tag;
@@ -213,52 +250,57 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         const int rank = a.meta.rank[slot + lane_zero];
         const float scale = a.meta.scale[slot + lane_zero];
 
+        const bool xitem = use_x && !solo;
         // ---- one flight: every load of this item is issued here ----
         const uint16_t *Bg = a.b_tab + (int64_t)key * a.d_out * RP;
         uint16_t *yrow[kChunk];
 #pragma unroll
         for (int c = 0; c < kChunk; ++c) yrow[c] = a.y + (int64_t)row[c] * a.ldy;
-        uint4 braw[C::EU][C::BV];
-        yvec_t yraw[C::EU][kChunk];
-        auto load_tile = [&](int t) {
-            const int lo = t * C::TILE;
+        uint4 braw[C::DEPTH][C::EU][C::BV];
+        yvec_t yraw[C::DEPTH][C::EU][kChunk];
+        auto load_tile = [&](int lo, auto dconst) {
+            constexpr int d = decltype(dconst)::value;
 #pragma unroll
             for (int e = 0; e < C::EU; ++e) {
                 const int o = lo + (e * C::NT + tid) * C::OPL;
-                const int oc = o < a.d_out ? o : 0;               // clamped address, result unused
+                const uint32_t oc = o < out1 ? (uint32_t)o : 0u;  // clamped address, result unused
+                // uniform 64-bit base + 32-bit per-lane byte offset: no 64-bit address registers per lane
 #pragma unroll
-                for (int q = 0; q < C::BV; ++q) braw[e][q] = ((const uint4 *)(Bg + (int64_t)oc * RP))[q];
+                for (int q = 0; q < C::BV; ++q) braw[d][e][q] = *(const uint4 *)((const char *)Bg + (oc * (uint32_t)(RP * 2) + (uint32_t)(q * 16)));
 #pragma unroll
                 for (int c = 0; c < kChunk; ++c)
-                    if (c < cnt) yraw[e][c] = *(const yvec_t *)(yrow[c] + oc);
+                    if (c < cnt) yraw[d][e][c] = *(const yvec_t *)((const char *)yrow[c] + oc * 2u);
             }
         };
-        const int u_lo = SPLIT ? kslice * a.kslice_units : 0;
-        const int u_hi = SPLIT ? min(U, u_lo + a.kslice_units) : U;
-        const uint4 *Ag = (const uint4 *)(a.a_tab + (int64_t)key * RP * a.d_in + (int64_t)(jg * C::JPW) * a.d_in);
+        const char *Ag = (const char *)(a.a_tab + (int64_t)key * RP * a.d_in + (int64_t)(jg * C::JPW) * a.d_in);
+        const uint32_t a_row_bytes = (uint32_t)a.d_in * 2u;
         const uint4 *xp[kChunk];
 #pragma unroll
         for (int c = 0; c < kChunk; ++c) xp[c] = (const uint4 *)(a.x + (int64_t)(row[c] / a.top_k) * a.ldx);
         uint4 av[C::JPW], xv[kChunk];
-        auto load_flight = [&](int f) {
+        auto load_flight = [&](int f, int ul, int uh) {
             const int u = f + ks * 64 + lane;
-            const int uc = u < u_hi ? u : u_lo;
+            const uint32_t ub = (uint32_t)(u < uh ? u : ul) * 16u;
 #pragma unroll
-            for (int jj = 0; jj < C::JPW; ++jj) av[jj] = Ag[(int64_t)jj * U + uc];
+            for (int jj = 0; jj < C::JPW; ++jj) av[jj] = *(const uint4 *)(Ag + (size_t)((uint32_t)jj * a_row_bytes) + ub);
 #pragma unroll
             for (int c = 0; c < kChunk; ++c)
-                if (c < cnt) xv[c] = xp[c][uc];
+                if (c < cnt) xv[c] = *(const uint4 *)((const char *)xp[c] + ub);
         };
-        if (do_shrink) load_flight(u_lo);
-        if (do_expand) load_tile(tile0);
-        if (prof && tid == 0 && first_item) { prof[1] = wall_clock64(); prof[7] = cnt + 100 * (do_shrink ? 1 : 0) + 1000 * (do_expand ? 1 : 0); }
-
-        // ---- shrink over this item's range of d_in ----
-        if (do_shrink) {
+        // Tiles 1 .. DEPTH-1 of the expand are requested once the shrink's operands have been consumed
+        // (their registers are free then) and travel while the partial sums are reduced and traded.
+        auto load_more_tiles = [&]() {
+            static_for<C::DEPTH>([&](auto dc) {
+                if constexpr (decltype(dc)::value >= 1) { if (out0 + dc.value * C::TILE < out1) load_tile(out0 + dc.value * C::TILE, dc); }
+            });
+        };
+        // Shrink over the units [ul, uh) of d_in.  Returns, in thread c * RP + j, the sum for row c
+        // of the chunk and adapter row j (other threads: 0).
+        auto shrink_units = [&](int ul, int uh, bool then_tiles) -> float {
             bool first = true;
-            for (int f = u_lo; f < u_hi; f += C::FLU) {
-                if (f > u_lo) load_flight(f);
-                const bool in = f + ks * 64 + lane < u_hi;
+            for (int f = ul; f < uh; f += C::FLU) {
+                if (f > ul) load_flight(f, ul, uh);
+                const bool in = f + ks * 64 + lane < uh;
 #pragma unroll
                 for (int c0 = 0; c0 < kChunk; c0 += C::CS) {
                     if (c0 >= cnt) break;
@@ -282,96 +324,167 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                 }
                 first = false;
             }
-            if (prof && tid == 0 && first_item) prof[2] = wall_clock64();
+            if (then_tiles) load_more_tiles();
             __syncthreads();
-            if (tid < kChunk * RP) {
-                const int c = tid / RP, j = tid % RP;
-                float s = 0.f;
+            float s = 0.f;
+            if (tid < kChunk * RP && tid / RP < cnt) {
 #pragma unroll
-                for (int k = 0; k < C::KS; ++k) s += part[k][c][j];
-                if (SPLIT) {
-                    if (c < cnt) xch_put(a.xch + ((int64_t)(chunk * a.ksplit + kslice) * kChunk + c) * RP + j, s, tag);
-                } else {
-                    hs[c][j] = s * scale;
-                }
+                for (int k = 0; k < C::KS; ++k) s += part[k][tid / RP][tid % RP];
             }
+            __syncthreads();                                      // part may be written again
+            return s;
+        };
+        const int u_lo = solo ? 0 : kslice * a.kslice_units, u_hi = solo ? U : min(U, u_lo + a.kslice_units);
+        if (do_shrink) load_flight(u_lo, u_lo, u_hi);
+        if (do_expand) {                          // the first tile travels with the shrink operands
+            load_tile(out0, IntC<0>{});
+            if (!do_shrink) load_more_tiles();
+        }
+        if (prof && tid == 0 && first_item) { prof[1] = wall_clock64(); prof[7] = cnt + 100 * (do_shrink ? 1 : 0) + 1000 * (do_expand ? 1 : 0); }
+
+        // ---- shrink over this item's range of d_in ----
+        float own = 0.f;
+        if (do_shrink) own = shrink_units(u_lo, u_hi, do_expand);
+        if (prof && tid == 0 && first_item) prof[2] = wall_clock64();
+        const int hc = tid / RP, hj = tid % RP;                   // this thread's element of h (tid < kChunk * RP)
+        const bool h_thread = tid < kChunk * RP && hc < cnt;
+        if (!xitem) {
+            if (tid < kChunk * RP) hs[hc][hj] = own * scale;
             __syncthreads();
         } else {
-            // ---- pick up the partial shrink results of every k-slice, summed in slice order ----
-            bool ok = true;
-            if (tid < kChunk * RP) {
-                const int c = tid / RP, j = tid % RP;
+            uint64_t *xw = a.xch + ((int64_t)(chunk * a.ksplit) * kChunk + hc) * RP + hj;   // + k * kChunk * RP: slice k
+            if (do_shrink && h_thread) xch_put(xw + (int64_t)kslice * kChunk * RP, own, tag);
+            if (do_expand) {
+                // ---- the partial sums of every k-slice, added in slice order ----
+                // The workgroups that produce them belong to this launch and publish before they wait
+                // for anything, so they arrive within microseconds when those workgroups are running.
+                // Should one not be running yet (more live items than the GPU holds at once), the
+                // bounded wait ends and this workgroup starts the item again on its own.
                 float s = 0.f;
-                if (c < cnt) {
-                    const uint64_t *src = a.xch + ((int64_t)(chunk * a.ksplit) * kChunk + c) * RP + j;
-                    for (int k0 = 0; k0 < a.ksplit; k0 += 4) {        // four words in flight at a time
+                bool gave_up = false;
+                if (h_thread) {
+                    for (int k0 = 0; k0 < a.ksplit; k0 += 4) {    // four words in flight at a time
                         uint64_t wv[4];
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
-                            if (k0 + k < a.ksplit) wv[k] = xch_get(src + (int64_t)(k0 + k) * kChunk * RP);
+                            if (k0 + k < a.ksplit) wv[k] = xch_get(xw + (int64_t)(k0 + k) * kChunk * RP);
 #pragma unroll
                         for (int k = 0; k < 4; ++k) {
                             if (k0 + k < a.ksplit) {
+                                if (do_shrink && k0 + k == kslice) { s += own; continue; }
                                 int spins = 0;
                                 while ((uint32_t)(wv[k] >> 32) != tag) {
-                                    if (++spins > kSpinLimit) { ok = false; break; }
+                                    if (++spins > kPollLimit) { gave_up = true; break; }
                                     __builtin_amdgcn_s_sleep(1);
-                                    wv[k] = xch_get(src + (int64_t)(k0 + k) * kChunk * RP);
+                                    wv[k] = xch_get(xw + (int64_t)(k0 + k) * kChunk * RP);
                                 }
                                 s += __uint_as_float((uint32_t)wv[k]);
                             }
                         }
                     }
+                    if (gave_up) atomicOr(&s_missing, 1u);
                 }
-                hs[c][j] = s * scale;
-            }
-            if (!ok) s_fail = 1;
-            __syncthreads();
-            if (s_fail) {                                         // never seen in a healthy launch
-                if (tid == 0) __hip_atomic_store(a.ctrl + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;
+                __syncthreads();
+                if (s_missing) {                                  // rare
+                    __syncthreads();
+                    if (tid == 0) s_missing = 0;                  // next use is behind the shrink's barriers
+                    solo_next = true; first_item = false;
+                    item -= n_wg;
+                    continue;
+                }
+                if (tid < kChunk * RP) hs[hc][hj] = s * scale;
+                __syncthreads();
             }
         }
         if (prof && tid == 0 && first_item) prof[3] = wall_clock64();
 
         // ---- expand + in-place add ----
         if (do_expand) {
-            for (int t = tile0; t < tile1; ++t) {
-                if (t > tile0) load_tile(t);
-                const int lo = t * C::TILE;
+            // Matrix-core operands of h: lane l supplies row l%4 of the chunk, four ranks per step.
+            // h is fp32; it goes in as a bf16 head (truncated) plus a bf16 tail (rounded), which
+            // together carry 16 bits of h, far inside the output's own bf16 rounding.
+            s16x4_t ahi[C::MX ? RP / 4 : 1], alo[C::MX ? RP / 4 : 1];
+            if constexpr (C::MX) {
+                const float *hrow = hs[lane & 3];
 #pragma unroll
-                for (int e = 0; e < C::EU; ++e) {
-                    // hs is re-read for every output group: keeping all of it in registers across
-                    // groups costs more registers than the LDS reads cost time
-                    asm volatile("" ::: "memory");
-                    const int o = lo + (e * C::NT + tid) * C::OPL;
-                    // bf[q*RP + j]: B value of output q of this lane; for RP >= 8 there is one output
-                    float bf[C::BV * 8];
+                for (int s4 = 0; s4 < RP / 4; ++s4) {
+                    const float4 v = *(const float4 *)(hrow + 4 * s4);
+                    const float f[4] = {v.x, v.y, v.z, v.w};
+                    uint32_t hi[4], lo[4];
 #pragma unroll
-                    for (int q = 0; q < C::BV; ++q) {
-                        bf[q * 8 + 0] = bf_lo(braw[e][q].x); bf[q * 8 + 1] = bf_hi(braw[e][q].x);
-                        bf[q * 8 + 2] = bf_lo(braw[e][q].y); bf[q * 8 + 3] = bf_hi(braw[e][q].y);
-                        bf[q * 8 + 4] = bf_lo(braw[e][q].z); bf[q * 8 + 5] = bf_hi(braw[e][q].z);
-                        bf[q * 8 + 6] = bf_lo(braw[e][q].w); bf[q * 8 + 7] = bf_hi(braw[e][q].w);
+                    for (int k = 0; k < 4; ++k) {
+                        hi[k] = __float_as_uint(f[k]) & 0xffff0000u;
+                        lo[k] = f2bf(f[k] - __uint_as_float(hi[k]));
                     }
-#pragma unroll
-                    for (int c = 0; c < kChunk; ++c) {
-                        if (c < cnt && o < a.d_out && rank > 0) {     // empty slot: rows stay untouched
-                            float yf[C::OPL];
-                            y_unpack(yraw[e][c], yf);
-#pragma unroll
-                            for (int q = 0; q < C::OPL; ++q) {
-                                float d = 0.f;
-#pragma unroll
-                                for (int j = 0; j < RP; ++j) d = fmaf(hs[c][j], bf[q * RP + j], d);
-                                yf[q] += d;
-                            }
-                            yvec_t out;
-                            y_pack(yf, out);
-                            *(yvec_t *)(yrow[c] + o) = out;
-                        }
-                    }
+                    ahi[s4] = __builtin_bit_cast(s16x4_t, make_uint2((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]));
+                    alo[s4] = __builtin_bit_cast(s16x4_t, make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)));
                 }
+            }
+            // an item that walks several tiles keeps DEPTH of them in flight: tile t + DEPTH is requested
+            // as soon as tile t has been written back
+            for (int l0 = out0; l0 < out1; l0 += C::DEPTH * C::TILE) {
+                static_for<C::DEPTH>([&](auto dc) {
+                    constexpr int d = decltype(dc)::value;
+                    const int lo = l0 + d * C::TILE;
+                    if (lo < out1) {
+#pragma unroll
+                        for (int e = 0; e < C::EU; ++e) {
+                            const int o = lo + (e * C::NT + tid) * C::OPL;
+                            if constexpr (C::MX) {
+                                f32x4_t d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                                for (int s4 = 0; s4 < RP / 4; ++s4) {
+                                    const uint4 bq = braw[d][e][s4 / 2];
+                                    const s16x4_t bop = __builtin_bit_cast(s16x4_t, (s4 & 1) ? make_uint2(bq.z, bq.w) : make_uint2(bq.x, bq.y));
+                                    d0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ahi[s4], bop, d0, 0, 0, 0);
+                                    d1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(alo[s4], bop, d1, 0, 0, 0);
+                                }
+#pragma unroll
+                                for (int c = 0; c < kChunk; ++c) {
+                                    if (c < cnt && o < out1 && rank > 0) {        // empty slot: rows stay untouched
+                                        float yf[1];
+                                        y_unpack(yraw[d][e][c], yf);
+                                        yf[0] += d0[c] + d1[c];
+                                        yvec_t out;
+                                        y_pack(yf, out);
+                                        *(yvec_t *)((char *)yrow[c] + (uint32_t)o * 2u) = out;
+                                    }
+                                }
+                            } else {
+                                // hs is re-read for every output group: keeping all of it in registers across
+                                // groups costs more registers than the LDS reads cost time
+                                asm volatile("" ::: "memory");
+                                // bf[q*RP + j]: B value of output q of this lane; for RP >= 8 there is one output
+                                float bf[C::BV * 8];
+#pragma unroll
+                                for (int q = 0; q < C::BV; ++q) {
+                                    bf[q * 8 + 0] = bf_lo(braw[d][e][q].x); bf[q * 8 + 1] = bf_hi(braw[d][e][q].x);
+                                    bf[q * 8 + 2] = bf_lo(braw[d][e][q].y); bf[q * 8 + 3] = bf_hi(braw[d][e][q].y);
+                                    bf[q * 8 + 4] = bf_lo(braw[d][e][q].z); bf[q * 8 + 5] = bf_hi(braw[d][e][q].z);
+                                    bf[q * 8 + 6] = bf_lo(braw[d][e][q].w); bf[q * 8 + 7] = bf_hi(braw[d][e][q].w);
+                                }
+#pragma unroll
+                                for (int c = 0; c < kChunk; ++c) {
+                                    if (c < cnt && o < out1 && rank > 0) {        // empty slot: rows stay untouched
+                                        float yf[C::OPL];
+                                        y_unpack(yraw[d][e][c], yf);
+#pragma unroll
+                                        for (int q = 0; q < C::OPL; ++q) {
+                                            float dlt = 0.f;
+#pragma unroll
+                                            for (int j = 0; j < RP; ++j) dlt = fmaf(hs[c][j], bf[q * RP + j], dlt);
+                                            yf[q] += dlt;
+                                        }
+                                        yvec_t out;
+                                        y_pack(yf, out);
+                                        *(yvec_t *)(yrow[c] + o) = out;
+                                    }
+                                }
+                            }
+                        }
+                        if (lo + C::DEPTH * C::TILE < out1) load_tile(lo + C::DEPTH * C::TILE, dc);
+                    }
+                });
             }
             __syncthreads();                                      // hs is rewritten by the next item
         }
@@ -380,7 +493,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
     }
 
     // ---- tag bookkeeping ----
-    if (SPLIT) {
+    if (use_x) {
         if (first_item && tid == 0) tag_sign_in(a.ctrl, wg, tag);   // a workgroup without items still signs in
         if (wg == n_wg - 1 && w == 0) {
             if (!first_item) tag = s_tag;
@@ -390,22 +503,22 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
     }
 }
 
-template <int RP, int NW, bool SPLIT>
+template <int RP, int NW, bool XCH>
 __global__ __launch_bounds__(NW * 64, (NW >= 8 && RP <= 16) ? 4 : 1)
 void rows_kernel(const RowsArgs a)
 {
-    rows_body<RP, NW, SPLIT>(a, (int)blockIdx.x, (int)gridDim.x);
+    rows_body<RP, NW, XCH>(a, (int)blockIdx.x, (int)gridDim.x);
 }
 
 // Several sites that share a batch plan in one launch (q/k/v of one layer, or gate/up): site s owns
-// workgroups [first[s], first[s + 1]).  Only fused launches are grouped; nothing crosses workgroups.
+// workgroups [first[s], first[s + 1]).  Workgroups of different sites never talk to each other.
 struct MultiArgs {
     int32_t n;
     int32_t first[kMaxMulti + 1];
     RowsArgs site[kMaxMulti];
 };
 
-template <int RP, int NW>
+template <int RP, int NW, bool XCH>
 __global__ __launch_bounds__(NW * 64, (NW >= 8 && RP <= 16) ? 4 : 1)
 void rows_multi_kernel(const MultiArgs m)
 {
@@ -413,21 +526,72 @@ void rows_multi_kernel(const MultiArgs m)
     int s = 0;
 #pragma unroll
     for (int k = 1; k < kMaxMulti; ++k) s += (k < m.n && b >= m.first[k]) ? 1 : 0;
-    rows_body<RP, NW, false>(m.site[s], b - m.first[s], m.first[s + 1] - m.first[s]);
+    rows_body<RP, NW, XCH>(m.site[s], b - m.first[s], m.first[s + 1] - m.first[s]);
 }
 
-template <int RP, int NW, bool SPLIT>
+template <int RP, int NW, bool XCH>
 static int rows_capacity()
 {
     static int cap = 0;
     if (cap == 0) {
         int per_cu = 0, cus = 0, dev = 0;
         if (hipGetDevice(&dev) != hipSuccess) return 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, rows_kernel<RP, NW, SPLIT>, NW * 64, 0) != hipSuccess) return 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, rows_kernel<RP, NW, XCH>, NW * 64, 0) != hipSuccess) return 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
         cap = per_cu * cus;
     }
     return cap;
+}
+
+// Bytes one chunk of a site moves: adapter rows and x for the shrink, B rows and y (read + write)
+// for the expand.
+static double chunk_bytes(const RowsArgs &a)
+{
+    return 2.0 * a.d_in * (a.r_pad + kChunk) + (double)a.d_out * (2.0 * a.r_pad + 4.0 * kChunk);
+}
+
+static bool can_exchange(const RowsArgs &a)
+{
+    return a.xch && a.ctrl && a.n_experts == 1 && a.grid_chunks <= a.xch_chunks;
+}
+
+// Cuts a chunk of a dense site into `parts` items.  A CU pulls only so many bytes per microsecond,
+// so a launch with fewer chunks than the GPU has CUs spreads each chunk over several workgroups:
+// part p expands outputs [p * out_per_part, ...) and, where the site has an exchange area, shrinks
+// k-slice p of d_in and trades the partial sums with the other parts of its chunk (no adapter byte
+// is read twice); without an exchange area every part redoes the whole shrink.
+static void set_parts(RowsArgs &a, int parts, bool exchange)
+{
+    const int U = a.d_in >> 3;
+    const int groups = (a.d_out + 63) / 64;
+    if (exchange) {
+        if (parts > 8) parts = 8;
+        if (parts * a.r_pad > 128) parts = 128 / a.r_pad;
+    }
+    if (parts > groups) parts = groups;
+    if (parts < 1 || a.n_experts != 1) parts = 1;
+    const int gpp = (groups + parts - 1) / parts;
+    a.out_per_part = gpp * 64;
+    a.tile_par = (groups + gpp - 1) / gpp;
+    a.mode = 0; a.ksplit = 1; a.kslice_units = U;
+    if (exchange && a.tile_par > 1) {
+        int ku = (U + a.tile_par - 1) / a.tile_par;
+        ku = (ku + 63) & ~63;
+        a.mode = 2;
+        a.kslice_units = ku;
+        a.ksplit = (U + ku - 1) / ku;
+    }
+}
+
+static int fused_grid(const RowsArgs &a)
+{
+    return a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : ((a.grid_chunks + 63) & ~63);
+}
+
+static int items_target(int cap)
+{
+    const int t = tuning("rows_items_target");
+    return t > 0 ? t : cap;
 }
 
 template <int RP, int NW>
@@ -438,26 +602,23 @@ static hipError_t launch_rp(RowsArgs a, hipStream_t st)
     const int ntiles = (a.d_out + C::TILE - 1) / C::TILE;
     const int ksplit = (U + C::FLU - 1) / C::FLU;
     a.ntiles = ntiles;
-    const bool can_split = a.xch && a.ctrl && a.grid_chunks <= a.xch_chunks && ksplit <= 8 && ksplit * RP <= 128;
-    const int mode = tuning("rows_mode");                 // 0 auto, 1 fused, 2 split, 3 fused with one tile per item
-    bool split = can_split && ksplit > 1;                 // d_in needs several flights: cut it across workgroups
-    if (mode == 1 || mode == 3) split = false;
-    if (mode == 2) split = can_split;
-    if (split) {
-        const int cap = rows_capacity<RP, NW, true>();
-        if (cap <= 0) return hipErrorUnknown;
+    const int mode = tuning("rows_mode");     // 0 auto, 1 parts that redo the shrink, 2 shrink items + expand items, 3 one item per chunk
+    const int cap = rows_capacity<RP, NW, true>();
+    if (cap <= 0) return hipErrorUnknown;
+    if (mode == 2 && can_exchange(a) && ksplit <= 8 && ksplit * RP <= 128) {
         a.mode = 1;
         a.ksplit = ksplit;
         a.kslice_units = (U + ksplit - 1) / ksplit;
+        a.tile_par = 1; a.out_per_part = a.d_out;
         int64_t items = (int64_t)a.grid_chunks * (ksplit + ntiles);
-        if (items > cap) items = cap;                     // every workgroup resident: waits always end
+        if (items > cap) items = cap;
         rows_kernel<RP, NW, true><<<dim3((unsigned)items), dim3(NW * 64), 0, st>>>(a);
-    } else {
-        a.mode = 0; a.ksplit = 1; a.kslice_units = U;
-        a.tile_par = (mode == 3 || (mode == 0 && ksplit == 1 && a.n_experts == 1)) ? ntiles : 1;
-        const unsigned grid = a.tile_par > 1 ? (unsigned)(((a.grid_chunks + 7) & ~7) * a.tile_par) : (unsigned)((a.grid_chunks + 63) & ~63);
-        rows_kernel<RP, NW, false><<<dim3(grid), dim3(NW * 64), 0, st>>>(a);
+        return hipGetLastError();
     }
+    const bool exchange = can_exchange(a) && mode == 0;
+    set_parts(a, mode == 3 ? 1 : items_target(cap) / a.grid_chunks, exchange);
+    if (a.mode == 2) rows_kernel<RP, NW, true><<<dim3((unsigned)fused_grid(a)), dim3(NW * 64), 0, st>>>(a);
+    else rows_kernel<RP, NW, false><<<dim3((unsigned)fused_grid(a)), dim3(NW * 64), 0, st>>>(a);
     return hipGetLastError();
 }
 
@@ -471,7 +632,7 @@ static hipError_t launch_nw(const RowsArgs &a, hipStream_t st)
         // nothing crosses workgroups); else 8, or 4 when 8 would be mostly idle lanes
         nw = U >= RowsCfg<RP, 8>::FLU * 3 / 4 ? 8 : 4;
         if constexpr (RP >= 8 && RP <= 16) {
-            if (a.n_experts == 1 && U > RowsCfg<RP, 8>::FLU && U <= RowsCfg<RP, 16>::FLU) nw = 16;
+            if (a.n_experts == 1 && U > RowsCfg<RP, 8>::FLU && U <= RowsCfg<RP, 16>::FLU && tuning("rows_single_waves") == 16) nw = 16;
         }
     }
     if constexpr (RP >= 64) nw = 8;
@@ -481,41 +642,45 @@ static hipError_t launch_nw(const RowsArgs &a, hipStream_t st)
     return hipErrorInvalidValue;
 }
 
-// Fill in the fused-launch fields of one site; returns its number of workgroups.
 template <int RP, int NW>
-static int prepare_fused(RowsArgs &a)
-{
-    using C = RowsCfg<RP, NW>;
-    const int U = a.d_in >> 3;
-    a.ntiles = (a.d_out + C::TILE - 1) / C::TILE;
-    a.mode = 0; a.ksplit = 1; a.kslice_units = U;
-    a.tile_par = a.n_experts == 1 ? a.ntiles : 1;
-    return a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : ((a.grid_chunks + 63) & ~63);
-}
-
-template <int RP>
 static hipError_t launch_multi_rp(const RowsArgs *sites, int n, hipStream_t st)
 {
+    const int cap = rows_capacity<RP, NW, true>();
+    if (cap <= 0) return hipErrorUnknown;
     MultiArgs m;
     m.n = n;
     m.first[0] = 0;
+    // every item of the launch should move about the same number of bytes
+    double total = 0.0;
+    bool exchange = tuning("rows_mode") == 0;
+    for (int k = 0; k < n; ++k) { total += chunk_bytes(sites[k]); exchange = exchange && can_exchange(sites[k]); }
+    const double per_item = total * sites[0].grid_chunks / items_target(cap);
+    bool any_x = false;
     for (int k = 0; k < n; ++k) {
         m.site[k] = sites[k];
-        m.first[k + 1] = m.first[k] + prepare_fused<RP, 16>(m.site[k]);
+        set_parts(m.site[k], (int)(chunk_bytes(sites[k]) / per_item + 0.5), exchange);
+        any_x = any_x || m.site[k].mode == 2;
+        m.first[k + 1] = m.first[k] + fused_grid(m.site[k]);
     }
-    for (int k = n; k < kMaxMulti; ++k) { m.site[k] = sites[0]; m.first[k + 1] = m.first[n]; }
-    rows_multi_kernel<RP, 16><<<dim3((unsigned)m.first[n]), dim3(16 * 64), 0, st>>>(m);
+    for (int k = n; k < kMaxMulti; ++k) { m.site[k] = m.site[0]; m.first[k + 1] = m.first[n]; }
+    if (any_x) rows_multi_kernel<RP, NW, true><<<dim3((unsigned)m.first[n]), dim3(NW * 64), 0, st>>>(m);
+    else rows_multi_kernel<RP, NW, false><<<dim3((unsigned)m.first[n]), dim3(NW * 64), 0, st>>>(m);
     return hipGetLastError();
 }
 
-// Sites can share a launch when each of them alone would run the 16-wave fused shape.
+static int group_waves()
+{
+    const int nw = tuning("rows_group_waves");
+    return nw == 16 ? 16 : 8;
+}
+
+// Dense sites of rank 8 or 16 whose d_in keeps most lanes of the shrink busy can share a launch.
 bool rows_can_group(const RowsArgs &a)
 {
     if (a.r_pad != 8 && a.r_pad != 16) return false;
     const int U = a.d_in >> 3;
     const int flu8 = a.r_pad == 8 ? RowsCfg<8, 8>::FLU : RowsCfg<16, 8>::FLU;
-    const int flu16 = a.r_pad == 8 ? RowsCfg<8, 16>::FLU : RowsCfg<16, 16>::FLU;
-    return a.n_experts == 1 && U > flu8 && U <= flu16 && !tuning("rows_mode") && !tuning("rows_waves");
+    return a.n_experts == 1 && U >= flu8 * 3 / 4 && tuning("rows_mode") != 2 && !tuning("rows_waves");
 }
 
 hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st)
@@ -524,7 +689,9 @@ hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st)
     for (int k = 0; k < n; ++k)
         if (sites[k].r_pad != sites[0].r_pad || !rows_can_group(sites[k])) return hipErrorInvalidValue;
     if (sites[0].grid_chunks <= 0) return hipSuccess;
-    return sites[0].r_pad == 8 ? launch_multi_rp<8>(sites, n, st) : launch_multi_rp<16>(sites, n, st);
+    if (group_waves() == 16)
+        return sites[0].r_pad == 8 ? launch_multi_rp<8, 16>(sites, n, st) : launch_multi_rp<16, 16>(sites, n, st);
+    return sites[0].r_pad == 8 ? launch_multi_rp<8, 8>(sites, n, st) : launch_multi_rp<16, 8>(sites, n, st);
 }
 
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st)

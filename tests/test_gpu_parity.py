@@ -153,8 +153,10 @@ def test_decode_large_batch_general_planner(M, oracle):
 
 
 def test_decode_multi_site_launch(M, oracle):
-    """Sites that share a plan in one launch (the q/k/v pattern): identical to separate calls and
-    right against the oracle; a site that cannot be grouped (small d_in) still gets its own launch."""
+    """Sites that share a plan in one launch (the q/k/v pattern): right against the oracle and, up to
+    the order of the fp32 partial sums (a grouped launch may cut d_in into a different number of
+    slices), equal to separate calls; a site that cannot be grouped (small d_in) still gets its own
+    launch."""
     shapes = [(2304, 264, 16), (2304, 1032, 16), (2304, 2056, 16), (128, 72, 16), (2304, 520, 16), (2304, 264, 16)]
     slots = W.rng(31).integers(-1, 5, size=61).astype(np.int32)
     cases = [W.dense_case(f"multi{i}", 3100 + i, 61, di, do, 5, r, 32.0, token_slot=slots, std_a=0.05, std_b=0.05)
@@ -174,7 +176,11 @@ def test_decode_multi_site_launch(M, oracle):
         y1 = P.dev_bf16(c.y0)
         M.lora_apply_decode_planned(site, plan, x, y1)
         torch.cuda.synchronize()
-        assert np.array_equal(P.host_bits(y1), got), c.name
+        single = P.host_bits(y1)
+        P.check_close(single, ref, c.name + " (own launch)")
+        wa, wb = P.widen(single), P.widen(got)
+        assert np.all(np.abs(wa - wb) <= 2.0 ** -7 * np.maximum(np.abs(wa), np.abs(wb))), c.name   # one bf16 step at most
+        assert np.mean(single != got) < 0.02, c.name
         dref = oracle.apply_decode(c.x, np.zeros_like(c.y0), c.A, c.B, c.rank, c.alpha, c.token_slot)
         P.noop_must_fail(c.y0, dref, np.nonzero(c.token_slot >= 0)[0])
 
