@@ -45,8 +45,12 @@ constexpr int32_t kSegCap = 65536;             // segment tiles / chunks per cal
 constexpr int32_t kXchChunks = 256;            // chunks per launch that may use the split shape
 constexpr size_t kCtrlBytes = 1024;
 constexpr size_t kXchBytes = (size_t)kXchChunks * 128 * kChunk * 8;   // <= 128 values per row of a chunk
-constexpr int32_t kSegXchBlocks = 1024;        // rank-64 sites: tile partials of 32 x 64 words shared inside a cluster
-constexpr size_t kSegXchBytes = (size_t)kSegXchBlocks * 32 * 64 * 8;
+constexpr size_t kSegXchBytes = (size_t)16 << 20;   // rank-64 sites: exchange words, then the prefill's partial shrink results
+// behind the exchange words: tile counters (16 KB), then per tile 16 KB of h (bf16 head + tail), then the
+// fp32 partials of the k-slices
+constexpr int32_t kSegMaxTiles = 256;              // tiles of 64 rows per batch of launches
+constexpr size_t kSegCountBytes = 16384;
+constexpr int32_t kSegHpBlocks = (int32_t)((kSegXchBytes - kXchBytes - kSegCountBytes - (size_t)kSegMaxTiles * 16384) / 16384);
 
 std::mutex g_tune_mu;
 std::map<std::string, int> g_tune;
@@ -197,6 +201,74 @@ int32_t stage_table(mlora_site *s, const std::vector<int32_t> &tab, hipStream_t 
     if (!ok(hipEventRecord(s->stage_ev[k], st))) return MLORA_E_HIP;
     s->stage_busy[k] = true;
     s->stage_next = k ^ 1;
+    return MLORA_OK;
+}
+
+// Rank-64 prefill: cut the segments into tiles of 64 rows (shrink items) and runs of whole tiles
+// (expand items), in batches that fit the partial-result buffer, and launch shrink + expand per batch.
+int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy,
+                       const int32_t *seg_off, const int32_t *seg_slot, int32_t S, hipStream_t st)
+{
+    struct Tile { int32_t slot, row0, rows, seg; };
+    std::vector<Tile> tiles;
+    for (int32_t k = 0; k < S; ++k) {
+        if (seg_slot[k] < 0) continue;
+        for (int32_t r0 = seg_off[k]; r0 < seg_off[k + 1]; r0 += 64)
+            tiles.push_back({seg_slot[k], r0, seg_off[k + 1] - r0 < 64 ? seg_off[k + 1] - r0 : 64, k});
+    }
+    if (tiles.empty()) return MLORA_OK;
+    const int32_t d_in = s->d.d_in, d_out = s->d.d_out;
+    const int32_t n_slices = (d_out + 511) / 512;
+    const int64_t n_all = (int64_t)tiles.size();
+    // k-slices: enough shrink items to fill the GPU (about two workgroups per CU), within the buffer
+    int32_t ks = tuning("seg_ksplit");
+    if (ks < 1) ks = (int32_t)(512 / n_all);       // not more items than are resident at once
+    if (ks > seg_ksplit_max()) ks = seg_ksplit_max();
+    if (ks < 1) ks = 1;
+    int32_t klen = ((d_in + ks - 1) / ks + 255) / 256 * 256;
+    ks = (d_in + klen - 1) / klen;
+    int64_t batch_tiles = kSegHpBlocks / ks;
+    if (batch_tiles > kSegMaxTiles) batch_tiles = kSegMaxTiles;
+    // tiles per expand run: a run re-reads its 64 KB slice of B_s, so longer runs cost fewer adapter
+    // bytes; shorter runs give more items to balance.  Aim at about four items per CU.
+    int32_t rt = tuning("seg_range_tiles");
+    if (rt < 1) {
+        rt = (int32_t)(n_all * n_slices / 1024);
+        if (rt < 2) rt = 2;
+        if (rt > 8) rt = 8;
+    }
+    for (int64_t t0 = 0; t0 < n_all; t0 += batch_tiles) {
+        const int32_t nt = (int32_t)(n_all - t0 < batch_tiles ? n_all - t0 : batch_tiles);
+        std::vector<int32_t> tab;
+        tab.reserve((size_t)nt * 8);
+        for (int32_t i = 0; i < nt; ++i) {
+            const Tile &t = tiles[t0 + i];
+            tab.push_back(t.slot); tab.push_back(t.row0); tab.push_back(t.rows); tab.push_back(0);
+        }
+        int32_t n_ranges = 0;
+        for (int32_t i = 0; i < nt;) {
+            const Tile &f = tiles[t0 + i];
+            int32_t n = 1, rows = f.rows;
+            while (n < rt && i + n < nt && tiles[t0 + i + n].seg == f.seg) { rows += tiles[t0 + i + n].rows; ++n; }
+            tab.push_back(f.slot); tab.push_back(f.row0); tab.push_back(rows); tab.push_back(i);
+            ++n_ranges;
+            i += n;
+        }
+        if ((int64_t)tab.size() > (int64_t)s->seg_cap * 3) return MLORA_E_UNSUPPORTED;
+        int32_t rc = stage_table(s, tab, st);
+        if (rc) return rc;
+        SegArgs a{};
+        a.x = (const uint16_t *)x; a.ldx = ldx; a.y = (uint16_t *)y; a.ldy = ldy;
+        a.a_tab = s->a_tab; a.b_tab = s->b_tab; a.meta.rank = s->rank; a.meta.scale = s->scale;
+        a.tiles = s->seg_dev; a.n_tiles = nt;
+        a.ranges = s->seg_dev + (int64_t)nt * 4; a.n_ranges = n_ranges;
+        a.d_in = d_in; a.d_out = d_out;
+        a.hcount = (int32_t *)((char *)s->xch + kXchBytes);
+        a.hfin = (uint16_t *)((char *)a.hcount + kSegCountBytes);
+        a.hpart = (float *)((char *)a.hfin + (size_t)kSegMaxTiles * 16384);
+        a.ksplit = ks; a.klen = klen; a.n_slices = n_slices;
+        if (!ok(launch_seg_mfma(a, st))) return MLORA_E_HIP;
+    }
     return MLORA_OK;
 }
 
@@ -533,35 +605,22 @@ int32_t lora_apply_segmented(mlora_site *s, const void *x, int64_t ldx, void *y,
     if (!g.good) return MLORA_E_HIP;
     hipStream_t st = (hipStream_t)stream;
 
-    const bool mfma = s->r_pad == 64 && (s->d.d_in & 15) == 0 && !tuning("seg_no_mfma");
-    const int rows_per = mfma ? 32 : kChunk;
-    const int rec = mfma ? 3 : kRec;
+    const bool mfma = s->r_pad == 64 && (s->d.d_in & 15) == 0 && s->xch && !tuning("seg_no_mfma");
+    if (mfma) return segmented_mfma(s, x, ldx, y, ldy, seg_off, seg_slot, S, st);
     std::vector<int32_t> tab;
     for (int32_t k = 0; k < S; ++k) {
         if (seg_slot[k] < 0) continue;
-        for (int32_t r0 = seg_off[k]; r0 < seg_off[k + 1]; r0 += rows_per) {
-            const int32_t n = seg_off[k + 1] - r0 < rows_per ? seg_off[k + 1] - r0 : rows_per;
-            if (mfma) {
-                tab.push_back(seg_slot[k]); tab.push_back(r0); tab.push_back(n);
-            } else {
-                tab.push_back(seg_slot[k]); tab.push_back(n); tab.push_back(r0); tab.push_back(0);
-                for (int32_t c = 0; c < kChunk; ++c) tab.push_back(r0 + (c < n ? c : n - 1));
-            }
+        for (int32_t r0 = seg_off[k]; r0 < seg_off[k + 1]; r0 += kChunk) {
+            const int32_t n = seg_off[k + 1] - r0 < kChunk ? seg_off[k + 1] - r0 : kChunk;
+            tab.push_back(seg_slot[k]); tab.push_back(n); tab.push_back(r0); tab.push_back(0);
+            for (int32_t c = 0; c < kChunk; ++c) tab.push_back(r0 + (c < n ? c : n - 1));
         }
     }
-    const int32_t n_units = (int32_t)(tab.size() / rec);
+    const int32_t n_units = (int32_t)(tab.size() / kRec);
     if (n_units == 0) return MLORA_OK;
-    if ((int64_t)(n_units + 1) * rec > (int64_t)s->seg_cap * 3) return MLORA_E_UNSUPPORTED;
+    if ((int64_t)(n_units + 1) * kRec > (int64_t)s->seg_cap * 3) return MLORA_E_UNSUPPORTED;
     rc = stage_table(s, tab, st);
     if (rc) return rc;
-    if (mfma) {
-        SegArgs a{};
-        a.x = (const uint16_t *)x; a.ldx = ldx; a.y = (uint16_t *)y; a.ldy = ldy;
-        a.a_tab = s->a_tab; a.b_tab = s->b_tab; a.meta.rank = s->rank; a.meta.scale = s->scale;
-        a.tiles = s->seg_dev; a.n_tiles = n_units; a.d_in = s->d.d_in; a.d_out = s->d.d_out;
-        a.xch = s->xch; a.ctrl = s->ctrl; a.xch_blocks = s->xch ? kSegXchBlocks : 0; a.cluster = 1;
-        return ok(launch_seg_mfma(a, st)) ? MLORA_OK : MLORA_E_HIP;
-    }
     RowsArgs a = rows_args(s, x, ldx, y, ldy);
     a.chunks = s->seg_dev;
     a.grid_chunks = n_units;

@@ -76,22 +76,25 @@ constexpr int kMaxMulti = 4;     // sites per grouped launch
 bool rows_can_group(const RowsArgs &a);
 hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st);
 
-// seg_mfma.hip: rank-64 segmented apply on the matrix cores
+// seg_mfma.hip: rank-64 segmented apply on the matrix cores (a shrink launch, then an expand launch)
 struct SegArgs {
     const uint16_t *x; int64_t ldx;
     uint16_t *y;       int64_t ldy;
     const uint16_t *a_tab; const uint16_t *b_tab;
     MetaView meta;
-    const int32_t *tiles;    // [3 * n_tiles]: slot, first row, rows (<= 32)
+    const int32_t *tiles;    // [4 * n_tiles]: slot, first row, rows (<= 64), 0 -- consecutive pieces of the segments
     int32_t n_tiles;
+    const int32_t *ranges;   // [4 * n_ranges]: slot, first row, rows, first tile -- runs of whole tiles of one segment
+    int32_t n_ranges;
     int32_t d_in, d_out;
-    // exchange area of the site, used when a tile is shared by a cluster of workgroups
-    uint64_t *xch;           // [n_tiles * cluster][32 * 64] words
-    uint32_t *ctrl;          // launch tag / error flag / sign-in counters (same block as the vector kernel's)
-    int32_t xch_blocks;      // capacity of xch in blocks of 32 * 64 words
-    int32_t cluster;         // filled in by the launcher: workgroups per tile (1, 2 or 4)
+    float *hpart;            // [ksplit][n_tiles][64 rows][64] fp32 partial shrink results (unused when ksplit is 1)
+    uint16_t *hfin;          // [n_tiles][64 rows][64 bf16 heads | 64 bf16 tails] scaled shrink result
+    int32_t *hcount;         // [n_tiles] k-slices that have arrived; zero between launches
+    int32_t ksplit, klen;    // k-slices of d_in and their length (a multiple of 256)
+    int32_t n_slices;        // output slices of 512
 };
 hipError_t launch_seg_mfma(const SegArgs &a, hipStream_t st);
+int seg_ksplit_max();
 
 int tuning(const char *name);   // api.hip
 uint64_t *debug_prof();         // api.hip
@@ -174,6 +177,36 @@ __device__ __forceinline__ void st_stream(void *p, const uint4 &v)
     __builtin_nontemporal_store(t, (u32x4_t *)p);
 }
 
+// Stores the compiler's wait-count bookkeeping does not see.  With a store it knows of still in
+// flight, the compiler can only wait for a load result by draining every outstanding memory
+// operation (loads and stores retire in order among themselves, not against each other), which
+// ends any prefetch of the next tile.  Issued this way, a store only makes a later wait a little
+// longer while it is unacknowledged: the hardware counter still includes it.  The data registers
+// are read when the instruction issues; they may be reused right away.
+__device__ __forceinline__ void st_quiet(void *p, const uint4 &v)
+{
+    u32x4_t t = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(p), "v"(t) : "memory");
+}
+__device__ __forceinline__ void st_quiet_stream(void *p, const uint4 &v)
+{
+    u32x4_t t = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off nt" : : "v"(p), "v"(t) : "memory");
+}
+__device__ __forceinline__ void st_quiet(void *p, uint2 v)
+{
+    asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void st_quiet(void *p, uint32_t v)
+{
+    asm volatile("global_store_dword %0, %1, off" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void st_quiet(void *p, uint16_t v)
+{
+    const uint32_t t = v;
+    asm volatile("global_store_short %0, %1, off" : : "v"(p), "v"(t) : "memory");
+}
+
 __device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
@@ -184,7 +217,14 @@ __device__ __forceinline__ uint32_t f2bf(float f)
     if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
-__device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) { return f2bf(lo) | (f2bf(hi) << 16); }
+// Two fp32 -> packed bf16 in one instruction (v_cvt_pk_bf16_f32: round to nearest even, NaN kept);
+// bit-identical to f2bf on every input.
+__device__ __forceinline__ uint32_t pack_bf2(float lo, float hi)
+{
+    typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 
 // a.lo*b.lo + a.hi*b.hi + c on packed bf16 pairs, fp32 accumulate (v_dot2c_f32_bf16).
 __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)

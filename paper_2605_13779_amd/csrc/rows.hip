@@ -590,8 +590,10 @@ static int fused_grid(const RowsArgs &a)
 
 static int items_target(int cap)
 {
+    // the chunk count used for the division is an upper bound; live chunks are fewer, and a launch
+    // whose live items all fit on the GPU at once finishes in one round (measured best at 3/4)
     const int t = tuning("rows_items_target");
-    return t > 0 ? t : cap;
+    return t > 0 ? t : cap * 3 / 4;
 }
 
 template <int RP, int NW>

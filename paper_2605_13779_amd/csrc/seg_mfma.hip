@@ -1,36 +1,45 @@
-// Rank-64 segmented (prefill) LoRA apply on the gfx950 matrix cores.
+// Rank-64 segmented (prefill) LoRA apply on the gfx950 matrix cores, as two launches.
 //
-// A workgroup owns a tile of up to 32 consecutive rows of one segment (all rows of a segment use
-// one adapter: a request's prompt is one contiguous run).  Both halves are dense contractions:
-//   shrink  h[32 x 64]    = X[32 x d_in] * A_s^T[d_in x 64]   v_mfma_f32_32x32x16_bf16, the eight
-//                                                              waves split d_in, partials summed in LDS
-//   scale   h *= alpha / r (fp32), then h is split into bf16 hi + lo so that the expand sees h
-//           to ~16 mantissa bits (the shrink result is not rounded to bf16)
-//   expand  Y[32 x d_out] += h * B_s^T[64 x d_out]             two MFMAs (hi, lo) per 16 ranks; every
-//                                                              wave walks its own 64-wide passes and
-//                                                              stages them in a private LDS tile so
-//                                                              that the in-place bf16 add on y moves
-//                                                              whole 128-byte row segments
-// h never leaves the workgroup.
+// All rows of a segment use one adapter (a request's prompt is one contiguous run), so both halves
+// are dense contractions with v_mfma_f32_32x32x16_bf16:
+//
+//   shrink  hp[j][64 rows x 64]  = X[64 rows x k-slice j] * A_s^T[k-slice j x 64]
+//           A workgroup owns a tile of up to 64 consecutive rows of one segment and one k-slice of
+//           d_in; x and A_s pieces are staged through LDS (coalesced 16-byte loads in, MFMA operand
+//           layout out), so the adapter rows are read once per 64 rows.  The fp32 partial sums go to
+//           a small device buffer (16 KB per tile and k-slice; it stays in L2).  The workgroup that
+//           finishes a tile's last k-slice adds the slices in slice order, scales in fp32 and writes
+//           h as bf16 head + tail (16 mantissa bits reach the expand's MFMA; the shrink result is
+//           never rounded to bf16).  Nobody waits: whoever arrives last does the sum.
+//   expand  Y[rows x 512 outputs] += h * B_s^T
+//           A workgroup owns a run of up to several tiles of one segment and a slice of 512 outputs;
+//           every wave keeps its 64 rows of B_s in registers for the whole run and walks the run 32
+//           rows at a time, with the next block's h and y already requested.  The accumulators pass
+//           through a wave-private LDS tile so that the in-place bf16 add on y moves row-contiguous
+//           16-byte pieces.
+//
+// The stream order between the two launches is the only dependency between workgroups that anyone
+// waits for.  What the tiling buys: per 64 rows the shrink pulls one copy of the adapter's A rows
+// through the CU's L1, and the expand pulls B_s once per run instead of once per 32 rows; with
+// 32-row tiles that re-read both, adapter bytes were more than half of all L1 traffic.
 #include "internal.h"
+#include <type_traits>
 
 namespace mlora {
 
 namespace {
-constexpr int TM = 32;            // rows per tile
+constexpr int TM = 64;            // rows per shrink tile
 constexpr int NW = 8;             // waves per workgroup
 constexpr int NT = NW * 64;
-constexpr int KT = 256;           // elements of d_in per staged k tile (16 MFMA k steps, two per wave)
+constexpr int KT = 256;           // elements of d_in per staged k tile (16 MFMA k steps)
 constexpr int TROW = KT * 2 + 16; // padded byte stride of a staged row (x or A)
-constexpr int TILE_BYTES = (TM + 64) * TROW;
-constexpr int WB = 64;            // outputs per wave per expand pass (two 32-wide MFMA blocks)
-constexpr int BROW = 64 * 2 + 16; // padded byte stride of a staged B row (64 ranks)
-constexpr int ST_LD = WB + 4;     // padded row stride of a wave's staging tile, in floats
-constexpr int WAVE_BYTES = WB * BROW > TM * ST_LD * 4 ? WB * BROW : TM * ST_LD * 4;
-constexpr int RED_BYTES = NW * TM * 64 * 4;              // k-slice partials of the shrink
-constexpr int H_LD = 64;          // row stride of the bf16 h tiles, in elements
-constexpr int cmax(int a, int b) { return a > b ? a : b; }
-constexpr int BUF_BYTES = cmax(cmax(TILE_BYTES, RED_BYTES), NW * WAVE_BYTES);
+constexpr int STAGE_BYTES = (TM + 64) * TROW;
+constexpr int RED_BYTES = 4 * TM * 64 * 4;                // four k-step groups of partials
+constexpr int ES = 512;           // outputs per expand slice (64 per wave)
+constexpr int H_LD = 72;          // padded row stride of the bf16 h tiles, in elements
+constexpr int ST_LD = 68;         // padded row stride of a wave's 16 x 64 staging tile, in floats
+constexpr int kMaxKsplit = 8;
+static_assert(RED_BYTES <= STAGE_BYTES, "partials reuse the staging area");
 }
 
 __device__ __forceinline__ f32x16_t mfma32(const uint4 &a, const uint4 &b, f32x16_t c)
@@ -39,269 +48,298 @@ __device__ __forceinline__ f32x16_t mfma32(const uint4 &a, const uint4 &b, f32x1
                                                    __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
-// Accumulator register i of lane l holds row (i/4)*8 + (l/32)*4 + i%4, column l%32.
-__device__ __forceinline__ int acc_row(int i, int kh) { return (i >> 2) * 8 + kh * 4 + (i & 3); }
-
-// Every global access is a whole 16 bytes per lane with neighbouring lanes on neighbouring
-// addresses (full 128-byte lines per row segment); LDS turns those row-major pieces into the
-// MFMA operand layout, where a lane owns eight consecutive k of one row.  Loading operands
-// straight from global memory in that layout touches 32 different lines per instruction and
-// thrashes the small L1.
-__global__ __launch_bounds__(NT, 4)
-void seg_mfma_kernel(const SegArgs a)
+// 16 x 16 x 32: lane l supplies 8 consecutive k (at 8 * (l / 16)) of row / column l % 16; accumulator
+// register i of lane l is row 4 * (l / 16) + i, column l % 16.
+__device__ __forceinline__ f32x4_t mfma16(const uint4 &a, const uint4 &b, f32x4_t c)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char buf[BUF_BYTES];   // k tiles, then partials + h, then per-wave tiles
-    static_assert(RED_BYTES + 2 * TM * H_LD * 2 <= BUF_BYTES, "the bf16 h tiles sit behind the partials");
-    uint16_t *hh = (uint16_t *)(buf + RED_BYTES);
-    uint16_t *hl = hh + TM * H_LD;
-
-    __shared__ uint32_t s_tag;
-    __shared__ int s_fail;
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, kh = lane >> 5;
-    const int G = a.cluster;                  // workgroups that share one tile: k-slices of the shrink, output slices of the expand
-    const int n_wg = (int)gridDim.x;
-    const bool last_wg = (int)blockIdx.x == n_wg - 1;
-    uint32_t tag = 0;
-    if (G > 1) {
-        if (tid == 0) { tag = tag_read(a.ctrl); s_tag = tag; s_fail = 0; tag_sign_in(a.ctrl, (int)blockIdx.x, tag); }
-        __syncthreads();
-        tag = s_tag;
-    }
-    // neighbouring work ids share an XCD (workgroups are dealt round-robin to 8 XCDs): the tiles of one
-    // segment reuse its adapter in L2, and the members of a cluster sit next to each other in dispatch order
-    const int per_xcd = n_wg >> 3;
-    const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    const int tile = v / G, g = v - tile * G;
-    bool live = tile < a.n_tiles;
-    int slot = -1, row0 = 0, nrows = 1;
-    if (live) { slot = a.tiles[3 * tile]; row0 = a.tiles[3 * tile + 1]; nrows = a.tiles[3 * tile + 2]; }
-    live = live && slot >= 0 && a.meta.rank[slot] > 0;
-    if (!live) {
-        if (G > 1 && last_wg && w == 0) tag_advance(a.ctrl, n_wg, tag, lane);
-        return;
-    }
-    const float scale = a.meta.scale[slot];
-
-    // ---------------- shrink: k tiles of [32 x rows + 64 A rows] x 256 staged through LDS ----------------
-    {
-        // staged row r (0..31 = x rows of the tile, 32..95 = A rows); thread handles rows srow + 16 q, 16-byte segment sseg
-        const int srow = tid >> 5, sseg = tid & 31;
-        const uint16_t *gp[6];
-#pragma unroll
-        for (int q = 0; q < 6; ++q) {
-            const int r = srow + 16 * q;
-            gp[q] = (q < 2) ? a.x + (int64_t)(row0 + min(r, nrows - 1)) * a.ldx + sseg * 8
-                            : a.a_tab + ((int64_t)slot * 64 + (r - 32)) * a.d_in + sseg * 8;
-        }
-        f32x16_t acc0 = {0}, acc1 = {0};
-        const int n_kt_all = (a.d_in + KT - 1) / KT;
-        const int kt_per = (n_kt_all + G - 1) / G;
-        const int kt0 = g * kt_per;                            // this member's k tiles: [kt0, kt0 + n_kt)
-        const int n_kt = max(0, min(n_kt_all, kt0 + kt_per) - kt0);
-        auto fetch = [&](int t, uint4 (&stage)[6]) {
-            const int k0 = (kt0 + t) * KT;
-            const bool in = t < n_kt && k0 + sseg * 8 < a.d_in;   // d_in is a multiple of 16: a segment is in or out as a whole
-#pragma unroll
-            for (int q = 0; q < 6; ++q) {
-                stage[q] = make_uint4(0, 0, 0, 0);
-                if (in) stage[q] = q < 2 ? ld_stream(gp[q] + k0) : *(const uint4 *)(gp[q] + k0);
-            }
-        };
-        auto consume = [&](const uint4 (&stage)[6]) {
-            __syncthreads();                                  // the previous tile has been read by every wave
-#pragma unroll
-            for (int q = 0; q < 6; ++q) *(uint4 *)(buf + (srow + 16 * q) * TROW + sseg * 16) = stage[q];
-            __syncthreads();
-        };
-        auto mma_tile = [&]() {
-#pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                const int kb = (2 * w + s2) * 32 + kh * 16;   // byte offset of this lane's 8 k values
-                const uint4 xv = *(const uint4 *)(buf + m * TROW + kb);
-                const uint4 v0 = *(const uint4 *)(buf + (32 + m) * TROW + kb);
-                const uint4 v1 = *(const uint4 *)(buf + (64 + m) * TROW + kb);
-                acc0 = mfma32(xv, v0, acc0);
-                acc1 = mfma32(xv, v1, acc1);
-            }
-        };
-        // two k tiles are in flight while a third is being multiplied
-        uint4 sa[6], sb[6];
-        fetch(0, sa);
-        fetch(1, sb);
-        for (int t = 0; t < n_kt; t += 2) {
-            consume(sa);
-            fetch(t + 2, sa);
-            mma_tile();
-            if (t + 1 < n_kt) {
-                consume(sb);
-                fetch(t + 3, sb);
-                mma_tile();
-            }
-        }
-        __syncthreads();
-        float *red = (float *)buf + w * (TM * 64);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            red[acc_row(i, kh) * 64 + m] = acc0[i];
-            red[acc_row(i, kh) * 64 + 32 + m] = acc1[i];
-        }
-    }
-    __syncthreads();
-    {
-        float part[4];                                           // TM * 64 / NT elements per thread
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int e = tid + q * NT;
-            float s = 0.f;
-#pragma unroll
-            for (int k = 0; k < NW; ++k) s += ((const float *)buf)[e + k * TM * 64];
-            part[q] = s;
-        }
-        bool ok = true;
-        if (G > 1) {
-            // publish this member's partial, then add the members' partials in member order, so that
-            // every member of the cluster ends up with bit-identical h
-            uint64_t *mine = a.xch + ((int64_t)tile * G + g) * (TM * 64);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) xch_put(mine + tid + q * NT, part[q], tag);
-            float tot[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int gg = 0; gg < G; ++gg) {
-                if (gg == g) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) tot[q] += part[q];
-                    continue;
-                }
-                const uint64_t *src = a.xch + ((int64_t)tile * G + gg) * (TM * 64);
-                uint64_t wv[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) wv[q] = xch_get(src + tid + q * NT);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    int spins = 0;
-                    while ((uint32_t)(wv[q] >> 32) != tag) {
-                        if (++spins > kSpinLimit) { ok = false; break; }
-                        __builtin_amdgcn_s_sleep(1);
-                        wv[q] = xch_get(src + tid + q * NT);
-                    }
-                    tot[q] += __uint_as_float((uint32_t)wv[q]);
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q) part[q] = tot[q];
-        }
-        if (!ok) s_fail = 1;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int e = tid + q * NT;
-            const float s = part[q] * scale;
-            const uint32_t hi = f2bf(s);
-            const uint32_t lo = f2bf(s - __uint_as_float(hi << 16));
-            const int tok = e >> 6, j = e & 63;
-            hh[tok * H_LD + j] = (uint16_t)hi;
-            hl[tok * H_LD + j] = (uint16_t)lo;
-        }
-    }
-    __syncthreads();
-    if (G > 1 && s_fail) {                       // a member never showed up (not expected): leave y alone, raise the flag
-        if (tid == 0) __hip_atomic_store(a.ctrl + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (last_wg && w == 0) tag_advance(a.ctrl, n_wg, tag, lane);
-        return;
-    }
-    uint4 hA[4], lA[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        hA[ks] = *(const uint4 *)(hh + m * H_LD + ks * 16 + kh * 8);
-        lA[ks] = *(const uint4 *)(hl + m * H_LD + ks * 16 + kh * 8);
-    }
-    __syncthreads();                 // buf turns from partials into the waves' private tiles
-
-    // ---------------- expand + in-place add: every wave walks its own 64-wide passes ----------------
-    // A pass stages its 64 B rows in the wave's LDS tile, reads them back as MFMA operands, then
-    // reuses the same tile to turn the accumulators into row-contiguous pieces for the add on y.
-    // The tile is private to the wave and LDS serves a wave's requests in order, so compiler-level
-    // fences are all that is needed between the phases.
-    const uint16_t *Bg = a.b_tab + (int64_t)slot * a.d_out * 64;
-    unsigned char *wt = buf + w * WAVE_BYTES;
-    float *stg = (float *)wt;
-    const int og = lane & 7, tr = lane >> 3;          // 8 lanes cover 128 bytes of one row
-    const int out_per = ((a.d_out + WB * G - 1) / (WB * G)) * WB;      // outputs per member, a multiple of a pass
-    const int out_lo = g * out_per, out_hi = min(a.d_out, out_lo + out_per);
-    for (int n0 = out_lo + w * WB; n0 < out_hi; n0 += NW * WB) {
-        const int oc = n0 + og * 8;
-        uint4 yv[4], braw[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {                 // B rows n0 + 8 i + lane / 8, 16-byte piece lane % 8
-            const int o = min(n0 + 8 * i + tr, a.d_out - 1);
-            braw[i] = *(const uint4 *)(Bg + (int64_t)o * 64 + og * 8);
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int tok = tr + 8 * q;
-            if (tok < nrows && oc < a.d_out) yv[q] = ld_stream(a.y + (int64_t)(row0 + tok) * a.ldy + oc);
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) *(uint4 *)(wt + (8 * i + tr) * BROW + og * 16) = braw[i];
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        f32x16_t acc[2];
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            uint4 bv[4];
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) bv[ks] = *(const uint4 *)(wt + (nb * 32 + m) * BROW + ks * 32 + kh * 16);
-            acc[nb] = f32x16_t{0};
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                acc[nb] = mfma32(hA[ks], bv[ks], acc[nb]);
-                acc[nb] = mfma32(lA[ks], bv[ks], acc[nb]);
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");     // all operand reads precede the reuse of the tile
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) stg[acc_row(i, kh) * ST_LD + nb * 32 + m] = acc[nb][i];
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int tok = tr + 8 * q;
-            if (tok < nrows && oc < a.d_out) {
-                const float4 d0 = *(const float4 *)(stg + tok * ST_LD + og * 8);
-                const float4 d1 = *(const float4 *)(stg + tok * ST_LD + og * 8 + 4);
-                uint4 o;
-                o.x = pack_bf2(bf_lo(yv[q].x) + d0.x, bf_hi(yv[q].x) + d0.y);
-                o.y = pack_bf2(bf_lo(yv[q].y) + d0.z, bf_hi(yv[q].y) + d0.w);
-                o.z = pack_bf2(bf_lo(yv[q].z) + d1.x, bf_hi(yv[q].z) + d1.y);
-                o.w = pack_bf2(bf_lo(yv[q].w) + d1.z, bf_hi(yv[q].w) + d1.w);
-                st_stream(a.y + (int64_t)(row0 + tok) * a.ldy + oc, o);
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    }
-    if (G > 1 && last_wg && w == 0) tag_advance(a.ctrl, n_wg, tag, lane);
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                   __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
-hipError_t launch_seg_mfma(const SegArgs &a_in, hipStream_t st)
+// 32 x 32 x 16: accumulator register i of lane l holds row (i/4)*8 + (l/32)*4 + i%4, column l%32.
+__device__ __forceinline__ int acc_row(int i, int kh) { return (i >> 2) * 8 + kh * 4 + (i & 3); }
+
+template <typename F>
+__device__ __forceinline__ void static_for2(F &&f)
 {
-    if (a_in.n_tiles <= 0) return hipSuccess;
-    SegArgs a = a_in;
-    // Cluster size: more workgroups than CUs evens out the load (tiles are cut per segment, so their
-    // number is rarely a multiple of the CU count) and halves each workgroup's chain of dependent
-    // passes.  Members of a cluster are neighbours in dispatch order, so a member that is not resident
-    // yet gets its slot as soon as any complete cluster retires; waits are bounded anyway.
-    static int cap = 0;
-    if (cap == 0) {
-        int per_cu = 0, cus = 0, dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return hipErrorUnknown;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, seg_mfma_kernel, NT, 0) != hipSuccess) return hipErrorUnknown;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return hipErrorUnknown;
-        cap = per_cu * cus;
+    f(std::integral_constant<int, 0>{});
+    f(std::integral_constant<int, 1>{});
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs; work ids are laid out so that an XCD gets a
+// contiguous range of them (neighbouring ids share adapter bytes, which then sit in that XCD's L2).
+__device__ __forceinline__ int xcd_contiguous_id()
+{
+    const int per_xcd = (int)gridDim.x >> 3;
+    return ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+}
+
+// Every global access is a whole 16 bytes per lane with neighbouring lanes on neighbouring
+// addresses; LDS turns those row-major pieces into the MFMA operand layout, where a lane owns
+// eight consecutive k of one row.  Loading operands straight from global memory in that layout
+// touches 32 different lines per instruction and thrashes the small L1.
+__global__ __launch_bounds__(NT, 4)
+void seg_shrink_kernel(const SegArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char buf[STAGE_BYTES];
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, kh = lane >> 5;
+    const int id = xcd_contiguous_id();
+    if (id >= a.n_tiles * a.ksplit) return;
+    const int j = id / a.n_tiles, tile = id - j * a.n_tiles;      // ids of one k-slice are neighbours
+    const int slot = a.tiles[4 * tile], row0 = a.tiles[4 * tile + 1], nrows = a.tiles[4 * tile + 2];
+    if (slot < 0 || a.meta.rank[slot] <= 0) return;               // the expand skips the same tiles
+
+    const int k_lo = j * a.klen, k_hi = min(a.d_in, k_lo + a.klen);
+    const int n_kt = (k_hi - k_lo + KT - 1) / KT;
+    // staged row r: 0..63 = x rows of the tile, 64..127 = A rows; this thread moves rows srow + 16 q
+    const int srow = tid >> 5, sseg = tid & 31;
+    const char *xb = (const char *)a.x, *ab = (const char *)(a.a_tab + (int64_t)slot * 64 * a.d_in);
+    uint32_t goff[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int r = srow + 16 * q;
+        // 32-bit offsets would overflow on x; they are 64-bit where needed below
+        goff[q] = q < 4 ? 0u : (uint32_t)((r - 64) * a.d_in + sseg * 8) * 2u;
     }
-    int g = tuning("seg_cluster");                        // 0 auto, 1 / 2 / 4 forced
-    if (g != 1 && g != 2 && g != 4) g = a.n_tiles * 2 <= cap + cap / 8 ? 2 : 1;
-    while (g > 1 && (!a.xch || !a.ctrl || (int64_t)a.n_tiles * g > a.xch_blocks || (int64_t)a.n_tiles * g > 2 * (int64_t)cap)) g >>= 1;
-    a.cluster = g;
-    const unsigned grid = (unsigned)(((int64_t)a.n_tiles * g + 7) / 8 * 8);
-    seg_mfma_kernel<<<dim3(grid), dim3(NT), 0, st>>>(a);
+    int64_t xoff[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) xoff[q] = ((int64_t)(row0 + min(srow + 16 * q, nrows - 1)) * a.ldx + sseg * 8) * 2;
+
+    uint4 st[8];
+    auto fetch = [&](int t) {
+        const int k0 = k_lo + t * KT;
+        const bool in = k0 + sseg * 8 < k_hi;          // d_in and the k-slices are multiples of 16
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            st[q] = make_uint4(0, 0, 0, 0);
+            if (in) st[q] = q < 4 ? ld_stream(xb + xoff[q] + (int64_t)k0 * 2)
+                                  : *(const uint4 *)(ab + goff[q] + (uint32_t)k0 * 2u);
+        }
+    };
+    // wave w multiplies row block rb against both 32-wide blocks of adapter rows, k steps kq*4 .. kq*4+3 of each tile
+    const int rb = w & 1, kq = w >> 1;
+    f32x16_t acc0 = {0}, acc1 = {0};
+    fetch(0);
+    for (int t = 0; t < n_kt; ++t) {
+        __syncthreads();                               // the previous tile has been read by every wave
+#pragma unroll
+        for (int q = 0; q < 8; ++q) *(uint4 *)(buf + (srow + 16 * q) * TROW + sseg * 16) = st[q];
+        __syncthreads();
+        if (t + 1 < n_kt) fetch(t + 1);                // in flight while this tile is multiplied
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int kb = (kq * 4 + s) * 32 + kh * 16;   // byte offset of this lane's 8 k values
+            const uint4 xv = *(const uint4 *)(buf + (rb * 32 + m) * TROW + kb);
+            const uint4 v0 = *(const uint4 *)(buf + (64 + m) * TROW + kb);
+            const uint4 v1 = *(const uint4 *)(buf + (96 + m) * TROW + kb);
+            acc0 = mfma32(xv, v0, acc0);
+            acc1 = mfma32(xv, v1, acc1);
+        }
+    }
+    __syncthreads();
+    float *red = (float *)buf;                         // [kq][64 rows][64 adapter rows]
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        float *p = red + ((kq * TM) + rb * 32 + acc_row(i, kh)) * 64;
+        p[m] = acc0[i];
+        p[32 + m] = acc1[i];
+    }
+    __syncthreads();
+    // this k-slice's sums, for whoever finishes the tile: 64-bit words written through to device scope
+    uint64_t *part = (uint64_t *)(a.hpart + ((int64_t)j * a.n_tiles + tile) * (TM * 64));
+    float4 mine[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int e4 = tid + NT * q, row = e4 >> 4, c4 = e4 & 15;
+        float4 s = *(const float4 *)(red + row * 64 + c4 * 4);
+#pragma unroll
+        for (int k = 1; k < 4; ++k) {
+            const float4 v = *(const float4 *)(red + (k * TM + row) * 64 + c4 * 4);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        mine[q] = s;
+        if (a.ksplit > 1 && row < nrows) {
+            __hip_atomic_store(part + e4 * 2, ((uint64_t)__float_as_uint(s.y) << 32) | __float_as_uint(s.x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(part + e4 * 2 + 1, ((uint64_t)__float_as_uint(s.w) << 32) | __float_as_uint(s.z), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    __shared__ int s_last;
+    if (a.ksplit > 1) {
+        // Every thread's words have been acknowledged at device scope before the tile's counter moves,
+        // and the last arriver reads them with device-scope loads after it has seen the count.  (Release
+        // and acquire fences would do the same by writing back and invalidating the whole L2, which
+        // holds the adapter rows everybody is reading.)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+            const int old = __hip_atomic_fetch_add(a.hcount + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = old == a.ksplit - 1;
+            if (s_last) __hip_atomic_store(a.hcount + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+        }
+        __syncthreads();
+        if (!s_last) return;
+    }
+    const float scale = a.meta.scale[slot];
+    uint16_t *hf = a.hfin + (int64_t)tile * (TM * 128);          // per row: 64 heads, then 64 tails
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int e4 = tid + NT * q, row = e4 >> 4, c4 = e4 & 15;
+        if (row >= nrows) continue;
+        float4 s = mine[q];
+        if (a.ksplit > 1) {
+            s = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int k = 0; k < a.ksplit; ++k) {       // slice order, whoever is last
+                const uint64_t *src = (const uint64_t *)(a.hpart + ((int64_t)k * a.n_tiles + tile) * (TM * 64)) + e4 * 2;
+                const uint64_t w0 = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const uint64_t w1 = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s.x += __uint_as_float((uint32_t)w0); s.y += __uint_as_float((uint32_t)(w0 >> 32));
+                s.z += __uint_as_float((uint32_t)w1); s.w += __uint_as_float((uint32_t)(w1 >> 32));
+            }
+        }
+        const float f[4] = {s.x * scale, s.y * scale, s.z * scale, s.w * scale};
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            hi[k] = f2bf(f[k]);
+            lo[k] = f2bf(f[k] - __uint_as_float(hi[k] << 16));
+        }
+        *(uint2 *)(hf + row * 128 + c4 * 4) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
+        *(uint2 *)(hf + row * 128 + 64 + c4 * 4) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+    }
+}
+
+// Loads are issued unconditionally (clamped addresses): the compiler can wait for one load while
+// younger ones stay in flight only if it knows how many were issued after it; a load under a
+// run-time condition turns every later wait into a full drain.
+__global__ __launch_bounds__(NT, 4)
+void seg_expand_kernel(const SegArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t hh[2][32 * H_LD], hl[2][32 * H_LD];
+    __shared__ __attribute__((aligned(16))) float stg_all[NW][16 * ST_LD];
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, kh = lane >> 5;
+    const int id = xcd_contiguous_id();
+    if (id >= a.n_ranges * a.n_slices) return;
+    const int sl = id / a.n_ranges, rg = id - sl * a.n_ranges;    // ids of one output slice are neighbours
+    const int slot = a.ranges[4 * rg], row0 = a.ranges[4 * rg + 1], nrows = a.ranges[4 * rg + 2];
+    const int tile0 = a.ranges[4 * rg + 3];
+    if (slot < 0 || a.meta.rank[slot] <= 0) return;
+    const float scale = a.meta.scale[slot];
+
+    // this wave's 64 rows of B_s, as operands of the 16 x 16 x 32 MFMA: bv[cb][ks] = ranks
+    // ks*32 + kq*8 .. +7 of row o_w + cb*16 + mm
+    const int mm = lane & 15, kq = lane >> 4;
+    const int o_w = sl * ES + w * 64;
+    uint4 bv[4][2];
+    {
+        const uint16_t *Bg = a.b_tab + (int64_t)slot * a.d_out * 64;
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) {
+            const int o = min(o_w + cb * 16 + mm, a.d_out - 1);
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) bv[cb][ks] = *(const uint4 *)(Bg + (int64_t)o * 64 + ks * 32 + kq * 8);
+        }
+    }
+    // h of a 32-row block is 32 x 256 bytes (64 heads, 64 tails per row): one 16-byte piece per thread
+    const int hrow = tid >> 4, hpc = tid & 15;
+    const uint16_t *hf0 = a.hfin + (int64_t)tile0 * (TM * 128) + hpc * 8;
+    uint4 hv;
+    auto h_fetch = [&](int blk) {
+        const int r = min(blk * 32 + hrow, nrows - 1);
+        hv = *(const uint4 *)(hf0 + (int64_t)r * 128);
+    };
+    auto h_store = [&](int buf_i) {
+        uint16_t *dst = hpc < 8 ? hh[buf_i] + hrow * H_LD + hpc * 8 : hl[buf_i] + hrow * H_LD + (hpc - 8) * 8;
+        *(uint4 *)dst = hv;
+    };
+
+    // y pieces: 8 lanes cover the 128 bytes (64 outputs) of one row, 8 rows per round; a block is
+    // handled as two halves of 16 rows so that the wave's staging tile stays small
+    const int og = lane & 7, tr = lane >> 3;
+    const int oc = min(o_w + og * 8, a.d_out - 8);
+    const bool col_ok = o_w + og * 8 < a.d_out;
+    float *stg = stg_all[w];
+    uint4 yv[2][2];
+    auto y_fetch = [&](int blk, auto half_c) {
+        constexpr int half = decltype(half_c)::value;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int tok = min(blk * 32 + half * 16 + tr + 8 * q, nrows - 1);
+            yv[half][q] = *(const uint4 *)(a.y + (int64_t)(row0 + tok) * a.ldy + oc);
+        }
+    };
+
+    // One 32-row block: MORE = a next block exists; its h and y pieces are requested while this block
+    // is worked on (unconditionally, so that the waits can leave them in flight).
+    auto block = [&](int blk, auto more_c) {
+        constexpr bool MORE = decltype(more_c)::value;
+        const int cur = blk & 1;
+        if constexpr (MORE) h_fetch(blk + 1);
+        static_for2([&](auto half_c) {
+            constexpr int half = decltype(half_c)::value;
+            // 16 rows x 64 outputs: four 16-wide blocks, two k steps of 32 ranks, head and tail of h
+            f32x4_t acc[4];
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb) acc[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const uint4 hA = *(const uint4 *)(hh[cur] + (half * 16 + mm) * H_LD + ks * 32 + kq * 8);
+                const uint4 lA = *(const uint4 *)(hl[cur] + (half * 16 + mm) * H_LD + ks * 32 + kq * 8);
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb) {
+                    acc[cb] = mfma16(hA, bv[cb][ks], acc[cb]);
+                    acc[cb] = mfma16(lA, bv[cb][ks], acc[cb]);
+                }
+            }
+            // The staging tile is private to the wave and LDS serves a wave's requests in order, so
+            // compiler-level fences are all that is needed between its phases.
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) stg[(4 * kq + i) * ST_LD + cb * 16 + mm] = acc[cb][i];
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int trow = tr + 8 * q, tok = blk * 32 + half * 16 + trow;
+                const float4 d0 = *(const float4 *)(stg + trow * ST_LD + og * 8);
+                const float4 d1 = *(const float4 *)(stg + trow * ST_LD + og * 8 + 4);
+                const uint4 yo = yv[half][q];
+                uint4 o;
+                o.x = pack_bf2(bf_lo(yo.x) + d0.x, bf_hi(yo.x) + d0.y);
+                o.y = pack_bf2(bf_lo(yo.y) + d0.z, bf_hi(yo.y) + d0.w);
+                o.z = pack_bf2(bf_lo(yo.z) + d1.x, bf_hi(yo.z) + d1.y);
+                o.w = pack_bf2(bf_lo(yo.w) + d1.z, bf_hi(yo.w) + d1.w);
+                if (tok < nrows && col_ok) st_quiet(a.y + (int64_t)(row0 + tok) * a.ldy + oc, o);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");     // reads of the tile precede its reuse
+            if constexpr (MORE) y_fetch(blk + 1, half_c);              // into the registers just used
+        });
+        if constexpr (MORE) {
+            h_store(cur ^ 1);
+            __syncthreads();                           // h tile cur has been read by all; tile cur^1 is complete
+        }
+    };
+    const int n_blk = (nrows + 31) >> 5;
+    h_fetch(0);
+    y_fetch(0, std::integral_constant<int, 0>{});
+    y_fetch(0, std::integral_constant<int, 1>{});
+    h_store(0);
+    __syncthreads();
+    for (int blk = 0; blk + 1 < n_blk; ++blk) block(blk, std::true_type{});
+    block(n_blk - 1, std::false_type{});
+}
+
+int seg_ksplit_max() { return kMaxKsplit; }
+
+hipError_t launch_seg_mfma(const SegArgs &a, hipStream_t st)
+{
+    if (a.n_tiles <= 0 || a.n_ranges <= 0) return hipSuccess;
+    if (a.ksplit < 1 || a.ksplit > kMaxKsplit || a.klen % KT != 0 || (int64_t)a.klen * a.ksplit < a.d_in) return hipErrorInvalidValue;
+    const unsigned gs = (unsigned)(((int64_t)a.n_tiles * a.ksplit + 7) / 8 * 8);
+    seg_shrink_kernel<<<dim3(gs), dim3(NT), 0, st>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const unsigned ge = (unsigned)(((int64_t)a.n_ranges * a.n_slices + 7) / 8 * 8);
+    seg_expand_kernel<<<dim3(ge), dim3(NT), 0, st>>>(a);
     return hipGetLastError();
 }
 
