@@ -45,7 +45,7 @@ constexpr int32_t kSegCap = 65536;             // segment tiles / chunks per cal
 constexpr int32_t kXchChunks = 256;            // chunks per launch that may use the split shape
 constexpr size_t kCtrlBytes = 1024;
 constexpr size_t kXchBytes = (size_t)kXchChunks * 128 * kChunk * 8;   // <= 128 values per row of a chunk
-constexpr size_t kSegXchBytes = (size_t)16 << 20;   // rank-64 sites: exchange words, then the prefill's partial shrink results
+constexpr size_t kSegXchBytes = (size_t)24 << 20;   // rank-64 sites: exchange words, then the prefill's partial shrink results
 // behind the exchange words: tile counters (16 KB), then per tile 16 KB of h (bf16 head + tail), then the
 // fp32 partials of the k-slices
 constexpr int32_t kSegMaxTiles = 256;              // tiles of 64 rows per batch of launches
@@ -220,15 +220,13 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
     const int32_t d_in = s->d.d_in, d_out = s->d.d_out;
     const int32_t n_slices = (d_out + 511) / 512;
     const int64_t n_all = (int64_t)tiles.size();
-    // k-slices: enough shrink items to fill the GPU (about two workgroups per CU), within the buffer
-    int32_t ks = tuning("seg_ksplit");
-    if (ks < 1) ks = (int32_t)(512 / n_all);       // not more items than are resident at once
-    if (ks > seg_ksplit_max()) ks = seg_ksplit_max();
-    if (ks < 1) ks = 1;
-    int32_t klen = ((d_in + ks - 1) / ks + 255) / 256 * 256;
-    ks = (d_in + klen - 1) / klen;
-    int64_t batch_tiles = kSegHpBlocks / ks;
-    if (batch_tiles > kSegMaxTiles) batch_tiles = kSegMaxTiles;
+    const int32_t upt = (d_in + seg_unit() - 1) / seg_unit();
+    const int32_t cap = seg_shrink_capacity();
+    if (cap <= 0) return MLORA_E_HIP;
+    // a batch of launches covers at most kSegMaxTiles tiles, and its shrink pieces fit the buffer
+    int64_t batch_tiles = kSegMaxTiles;
+    if (batch_tiles > kSegHpBlocks - cap) batch_tiles = kSegHpBlocks - cap;
+    if (batch_tiles < 1) return MLORA_E_UNSUPPORTED;
     // tiles per expand run: a run re-reads its 64 KB slice of B_s, so longer runs cost fewer adapter
     // bytes; shorter runs give more items to balance.  Aim at about four items per CU.
     int32_t rt = tuning("seg_range_tiles");
@@ -266,7 +264,12 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
         a.hcount = (int32_t *)((char *)s->xch + kXchBytes);
         a.hfin = (uint16_t *)((char *)a.hcount + kSegCountBytes);
         a.hpart = (float *)((char *)a.hfin + (size_t)kSegMaxTiles * 16384);
-        a.ksplit = ks; a.klen = klen; a.n_slices = n_slices;
+        a.upt = upt; a.n_slices = n_slices;
+        int64_t swg = (int64_t)nt * upt / 3;               // every workgroup keeps three units in flight
+        const int tuned = tuning("seg_shrink_wgs");
+        if (swg > (tuned > 0 ? tuned : cap)) swg = tuned > 0 ? tuned : cap;
+        if (swg > kSegHpBlocks - nt) swg = kSegHpBlocks - nt;     // one partial block per (workgroup, tile) piece
+        a.n_swg = (int32_t)(swg < 1 ? 1 : swg);
         if (!ok(launch_seg_mfma(a, st))) return MLORA_E_HIP;
     }
     return MLORA_OK;

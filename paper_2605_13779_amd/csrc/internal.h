@@ -87,14 +87,16 @@ struct SegArgs {
     const int32_t *ranges;   // [4 * n_ranges]: slot, first row, rows, first tile -- runs of whole tiles of one segment
     int32_t n_ranges;
     int32_t d_in, d_out;
-    float *hpart;            // [ksplit][n_tiles][64 rows][64] fp32 partial shrink results (unused when ksplit is 1)
+    float *hpart;            // [n_swg + n_tiles][64 rows][64] fp32 partial shrink results, one block per (workgroup, tile) piece
     uint16_t *hfin;          // [n_tiles][64 rows][64 bf16 heads | 64 bf16 tails] scaled shrink result
-    int32_t *hcount;         // [n_tiles] k-slices that have arrived; zero between launches
-    int32_t ksplit, klen;    // k-slices of d_in and their length (a multiple of 256)
+    int32_t *hcount;         // [n_tiles] pieces that have arrived; zero between launches
+    int32_t upt;             // units of d_in per tile (a unit is seg_unit() elements)
+    int32_t n_swg;           // workgroups of the shrink launch; n_swg * 3 <= n_tiles * upt
     int32_t n_slices;        // output slices of 512
 };
 hipError_t launch_seg_mfma(const SegArgs &a, hipStream_t st);
-int seg_ksplit_max();
+int seg_unit();
+int seg_shrink_capacity();
 
 int tuning(const char *name);   // api.hip
 uint64_t *debug_prof();         // api.hip

@@ -31,14 +31,13 @@ namespace {
 constexpr int TM = 64;            // rows per shrink tile
 constexpr int NW = 8;             // waves per workgroup
 constexpr int NT = NW * 64;
-constexpr int KT = 256;           // elements of d_in per staged k tile (16 MFMA k steps)
-constexpr int TROW = KT * 2 + 16; // padded byte stride of a staged row (x or A)
-constexpr int STAGE_BYTES = (TM + 64) * TROW;
-constexpr int RED_BYTES = 4 * TM * 64 * 4;                // four k-step groups of partials
+constexpr int KU = 128;           // elements of d_in per unit of the shrink (8 MFMA k steps)
+constexpr int UROW = KU * 2 + 16; // padded byte stride of a staged row (x or A)
+constexpr int STAGE_BYTES = (TM + 64) * UROW;
+constexpr int RED_BYTES = 2 * TM * 64 * 4;                // the two k halves of a unit
 constexpr int ES = 512;           // outputs per expand slice (64 per wave)
 constexpr int H_LD = 72;          // padded row stride of the bf16 h tiles, in elements
 constexpr int ST_LD = 68;         // padded row stride of a wave's 16 x 64 staging tile, in floats
-constexpr int kMaxKsplit = 8;
 static_assert(RED_BYTES <= STAGE_BYTES, "partials reuse the staging area");
 }
 
@@ -74,138 +73,189 @@ __device__ __forceinline__ int xcd_contiguous_id()
     return ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
 }
 
+// Shrink.  The work is the list of all (tile, k-unit) pairs, tile-major (a k-unit is KU elements of
+// d_in); workgroup b of n takes the contiguous share [b*U/n, (b+1)*U/n) of it, so every workgroup
+// moves the same number of bytes whatever the segment lengths are.  A share usually covers the end
+// of one tile and the start of the next; each piece is a partial sum, and the workgroup that delivers
+// a tile's last piece adds the pieces in share order (a fixed order: the result does not depend on
+// who is last) and writes h.
+//
 // Every global access is a whole 16 bytes per lane with neighbouring lanes on neighbouring
 // addresses; LDS turns those row-major pieces into the MFMA operand layout, where a lane owns
-// eight consecutive k of one row.  Loading operands straight from global memory in that layout
-// touches 32 different lines per instruction and thrashes the small L1.
+// eight consecutive k of one row.  (Loading operands straight from global memory in that layout
+// touches 32 different lines per instruction and thrashes the small L1.)  Three units are in flight
+// in registers while a fourth is multiplied; their loads are unconditional, so that the compiler can
+// wait for the oldest and leave the others in flight.
+struct ShrinkShare {
+    int64_t U;        // all units
+    int32_t n;        // workgroups
+    // workgroup that owns unit u: the smallest b with (b + 1) * U / n > u
+    __device__ int owner(int64_t u) const { return (int)(((u + 1) * n + U - 1) / U) - 1; }
+};
+
 __global__ __launch_bounds__(NT, 4)
 void seg_shrink_kernel(const SegArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char buf[STAGE_BYTES];
+    __shared__ int s_last;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, kh = lane >> 5;
-    const int id = xcd_contiguous_id();
-    if (id >= a.n_tiles * a.ksplit) return;
-    const int j = id / a.n_tiles, tile = id - j * a.n_tiles;      // ids of one k-slice are neighbours
-    const int slot = a.tiles[4 * tile], row0 = a.tiles[4 * tile + 1], nrows = a.tiles[4 * tile + 2];
-    if (slot < 0 || a.meta.rank[slot] <= 0) return;               // the expand skips the same tiles
+    const int b = xcd_contiguous_id();
+    if (b >= a.n_swg) return;
+    const ShrinkShare sh{(int64_t)a.n_tiles * a.upt, a.n_swg};
+    const int64_t u0 = (int64_t)b * sh.U / sh.n, u1 = (int64_t)(b + 1) * sh.U / sh.n;
+    const int n = (int)(u1 - u0);
+    if (n <= 0) return;
 
-    const int k_lo = j * a.klen, k_hi = min(a.d_in, k_lo + a.klen);
-    const int n_kt = (k_hi - k_lo + KT - 1) / KT;
-    // staged row r: 0..63 = x rows of the tile, 64..127 = A rows; this thread moves rows srow + 16 q
-    const int srow = tid >> 5, sseg = tid & 31;
-    const char *xb = (const char *)a.x, *ab = (const char *)(a.a_tab + (int64_t)slot * 64 * a.d_in);
-    uint32_t goff[8];
+    // staged row r: 0..63 = x rows of the tile, 64..127 = A rows; this thread moves rows srow + 32 q
+    const int srow = tid >> 4, sseg = tid & 15;
+    // ---- fetch side: walks the share unit by unit ----
+    int f_tile = (int)(u0 / a.upt), f_ku = (int)(u0 - (int64_t)f_tile * a.upt), f_left = n;
+    const char *f_a = nullptr;
+    int64_t f_x[2];
+    auto f_open = [&]() {                              // addresses for the tile the fetch side is in
+        const int slot = max(a.tiles[4 * f_tile], 0), row0 = a.tiles[4 * f_tile + 1], nrows = a.tiles[4 * f_tile + 2];
+        f_a = (const char *)(a.a_tab + (int64_t)slot * 64 * a.d_in);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        const int r = srow + 16 * q;
-        // 32-bit offsets would overflow on x; they are 64-bit where needed below
-        goff[q] = q < 4 ? 0u : (uint32_t)((r - 64) * a.d_in + sseg * 8) * 2u;
-    }
-    int64_t xoff[4];
+        for (int q = 0; q < 2; ++q) f_x[q] = (int64_t)(row0 + min(srow + 32 * q, nrows - 1)) * a.ldx * 2;
+    };
+    f_open();
+    auto fetch = [&](uint4 (&st)[4]) {                 // unconditional; past the share it repeats the last unit
+        const int k = min(f_ku * KU + sseg * 8, a.d_in - 8);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) xoff[q] = ((int64_t)(row0 + min(srow + 16 * q, nrows - 1)) * a.ldx + sseg * 8) * 2;
-
-    uint4 st[8];
-    auto fetch = [&](int t) {
-        const int k0 = k_lo + t * KT;
-        const bool in = k0 + sseg * 8 < k_hi;          // d_in and the k-slices are multiples of 16
+        for (int q = 0; q < 2; ++q) st[q] = ld_stream((const char *)a.x + f_x[q] + (int64_t)k * 2);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            st[q] = make_uint4(0, 0, 0, 0);
-            if (in) st[q] = q < 4 ? ld_stream(xb + xoff[q] + (int64_t)k0 * 2)
-                                  : *(const uint4 *)(ab + goff[q] + (uint32_t)k0 * 2u);
+        for (int q = 0; q < 2; ++q) st[2 + q] = *(const uint4 *)(f_a + ((int64_t)(srow + 32 * q) * a.d_in + k) * 2);
+        if (--f_left > 0) {
+            if (++f_ku == a.upt) { f_ku = 0; ++f_tile; f_open(); }
         }
     };
-    // wave w multiplies row block rb against both 32-wide blocks of adapter rows, k steps kq*4 .. kq*4+3 of each tile
-    const int rb = w & 1, kq = w >> 1;
-    f32x16_t acc0 = {0}, acc1 = {0};
-    fetch(0);
-    for (int t = 0; t < n_kt; ++t) {
-        __syncthreads();                               // the previous tile has been read by every wave
+    // ---- multiply side ----
+    // wave w: row block rb against adapter-row block cb, k steps kh2*4 .. kh2*4+3 of each unit
+    const int rb = w & 1, cb = (w >> 1) & 1, kh2 = w >> 2;
+    int c_tile = (int)(u0 / a.upt), c_ku = (int)(u0 - (int64_t)c_tile * a.upt);
+    f32x16_t acc = {0};
+    auto finish_tile = [&]() {                         // this share's piece of tile c_tile is complete
+        const int slot = a.tiles[4 * c_tile], nrows = a.tiles[4 * c_tile + 2];
+        __syncthreads();                               // the staged unit has been read by every wave
+        float *red = (float *)buf;                     // [k half][64 rows][64 adapter rows]
 #pragma unroll
-        for (int q = 0; q < 8; ++q) *(uint4 *)(buf + (srow + 16 * q) * TROW + sseg * 16) = st[q];
+        for (int i = 0; i < 16; ++i) red[((kh2 * TM) + rb * 32 + acc_row(i, kh)) * 64 + cb * 32 + m] = acc[i];
+        acc = f32x16_t{0};
         __syncthreads();
-        if (t + 1 < n_kt) fetch(t + 1);                // in flight while this tile is multiplied
+        const bool live = slot >= 0 && a.meta.rank[slot] > 0;     // the expand skips the same tiles
+        const int first = sh.owner((int64_t)c_tile * a.upt), pieces = sh.owner((int64_t)c_tile * a.upt + a.upt - 1) - first + 1;
+        float4 mine[2];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int kb = (kq * 4 + s) * 32 + kh * 16;   // byte offset of this lane's 8 k values
-            const uint4 xv = *(const uint4 *)(buf + (rb * 32 + m) * TROW + kb);
-            const uint4 v0 = *(const uint4 *)(buf + (64 + m) * TROW + kb);
-            const uint4 v1 = *(const uint4 *)(buf + (96 + m) * TROW + kb);
-            acc0 = mfma32(xv, v0, acc0);
-            acc1 = mfma32(xv, v1, acc1);
+        for (int q = 0; q < 2; ++q) {
+            const int e4 = tid + NT * q, row = e4 >> 4, c4 = e4 & 15;
+            const float4 p0 = *(const float4 *)(red + row * 64 + c4 * 4);
+            const float4 p1 = *(const float4 *)(red + (TM + row) * 64 + c4 * 4);
+            mine[q] = make_float4(p0.x + p1.x, p0.y + p1.y, p0.z + p1.z, p0.w + p1.w);
         }
-    }
-    __syncthreads();
-    float *red = (float *)buf;                         // [kq][64 rows][64 adapter rows]
+        bool last = true;
+        if (live && pieces > 1) {
+            // piece ids are unique: workgroup + tile grows from one piece to the next
+            uint64_t *part = (uint64_t *)(a.hpart + (int64_t)(b + c_tile) * (TM * 64));
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        float *p = red + ((kq * TM) + rb * 32 + acc_row(i, kh)) * 64;
-        p[m] = acc0[i];
-        p[32 + m] = acc1[i];
-    }
-    __syncthreads();
-    // this k-slice's sums, for whoever finishes the tile: 64-bit words written through to device scope
-    uint64_t *part = (uint64_t *)(a.hpart + ((int64_t)j * a.n_tiles + tile) * (TM * 64));
-    float4 mine[2];
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int e4 = tid + NT * q, row = e4 >> 4, c4 = e4 & 15;
-        float4 s = *(const float4 *)(red + row * 64 + c4 * 4);
-#pragma unroll
-        for (int k = 1; k < 4; ++k) {
-            const float4 v = *(const float4 *)(red + (k * TM + row) * 64 + c4 * 4);
-            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+            for (int q = 0; q < 2; ++q) {
+                const int e4 = tid + NT * q;
+                if ((e4 >> 4) < nrows) {
+                    __hip_atomic_store(part + e4 * 2, ((uint64_t)__float_as_uint(mine[q].y) << 32) | __float_as_uint(mine[q].x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(part + e4 * 2 + 1, ((uint64_t)__float_as_uint(mine[q].w) << 32) | __float_as_uint(mine[q].z), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            // Every thread's words have been acknowledged at device scope before the tile's counter
+            // moves, and the last arriver reads them with device-scope loads after it has seen the
+            // count.  (Release and acquire fences would do the same by writing back and invalidating
+            // the whole L2, which holds the adapter rows everybody is reading.)  The wait also drains
+            // the units in flight; it happens once or twice per workgroup.
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (tid == 0) {
+                const int old = __hip_atomic_fetch_add(a.hcount + c_tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_last = old == pieces - 1;
+                if (s_last) __hip_atomic_store(a.hcount + c_tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+            }
+            __syncthreads();
+            last = s_last != 0;
         }
-        mine[q] = s;
-        if (a.ksplit > 1 && row < nrows) {
-            __hip_atomic_store(part + e4 * 2, ((uint64_t)__float_as_uint(s.y) << 32) | __float_as_uint(s.x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(part + e4 * 2 + 1, ((uint64_t)__float_as_uint(s.w) << 32) | __float_as_uint(s.z), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-    __shared__ int s_last;
-    if (a.ksplit > 1) {
-        // Every thread's words have been acknowledged at device scope before the tile's counter moves,
-        // and the last arriver reads them with device-scope loads after it has seen the count.  (Release
-        // and acquire fences would do the same by writing back and invalidating the whole L2, which
-        // holds the adapter rows everybody is reading.)
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (tid == 0) {
-            const int old = __hip_atomic_fetch_add(a.hcount + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = old == a.ksplit - 1;
-            if (s_last) __hip_atomic_store(a.hcount + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
-        }
-        __syncthreads();
-        if (!s_last) return;
-    }
-    const float scale = a.meta.scale[slot];
-    uint16_t *hf = a.hfin + (int64_t)tile * (TM * 128);          // per row: 64 heads, then 64 tails
+        if (live && last) {
+            const float scale = a.meta.scale[slot];
+            uint16_t *hf = a.hfin + (int64_t)c_tile * (TM * 128);  // per row: 64 heads, then 64 tails
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int e4 = tid + NT * q, row = e4 >> 4, c4 = e4 & 15;
-        if (row >= nrows) continue;
-        float4 s = mine[q];
-        if (a.ksplit > 1) {
-            s = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int k = 0; k < a.ksplit; ++k) {       // slice order, whoever is last
-                const uint64_t *src = (const uint64_t *)(a.hpart + ((int64_t)k * a.n_tiles + tile) * (TM * 64)) + e4 * 2;
-                const uint64_t w0 = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const uint64_t w1 = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                s.x += __uint_as_float((uint32_t)w0); s.y += __uint_as_float((uint32_t)(w0 >> 32));
-                s.z += __uint_as_float((uint32_t)w1); s.w += __uint_as_float((uint32_t)(w1 >> 32));
+            for (int q = 0; q < 2; ++q) {
+                const int e4 = tid + NT * q, row = e4 >> 4, c4 = e4 & 15;
+                if (row >= nrows) continue;
+                float4 s = mine[q];
+                if (pieces > 1) {
+                    s = make_float4(0.f, 0.f, 0.f, 0.f);
+                    const uint64_t *src = (const uint64_t *)(a.hpart + (int64_t)(first + c_tile) * (TM * 64)) + e4 * 2;
+                    for (int k0 = 0; k0 < pieces; k0 += 4) {       // four pieces in flight at a time, added in order
+                        uint64_t w0[4], w1[4];
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const int kk = min(k0 + k, pieces - 1);
+                            w0[k] = __hip_atomic_load(src + (int64_t)kk * (TM * 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            w1[k] = __hip_atomic_load(src + (int64_t)kk * (TM * 32) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            if (k0 + k < pieces) {
+                                s.x += __uint_as_float((uint32_t)w0[k]); s.y += __uint_as_float((uint32_t)(w0[k] >> 32));
+                                s.z += __uint_as_float((uint32_t)w1[k]); s.w += __uint_as_float((uint32_t)(w1[k] >> 32));
+                            }
+                        }
+                    }
+                }
+                const float f[4] = {s.x * scale, s.y * scale, s.z * scale, s.w * scale};
+                uint32_t hi[4], lo[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    hi[k] = f2bf(f[k]);
+                    lo[k] = f2bf(f[k] - __uint_as_float(hi[k] << 16));
+                }
+                *(uint2 *)(hf + row * 128 + c4 * 4) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
+                *(uint2 *)(hf + row * 128 + 64 + c4 * 4) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
             }
         }
-        const float f[4] = {s.x * scale, s.y * scale, s.z * scale, s.w * scale};
-        uint32_t hi[4], lo[4];
+        __syncthreads();                               // the partials' LDS is staged into again
+    };
+    int c_left = n;
+    auto consume = [&](uint4 (&st)[4]) {
+        const bool in = c_ku * KU + sseg * 8 < a.d_in; // d_in is a multiple of 16: a 16-byte piece is in or out as a whole
+        __syncthreads();                               // the previous unit has been read by every wave
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            hi[k] = f2bf(f[k]);
-            lo[k] = f2bf(f[k] - __uint_as_float(hi[k] << 16));
+        for (int q = 0; q < 4; ++q) *(uint4 *)(buf + (srow + 32 * q) * UROW + sseg * 16) = in ? st[q] : make_uint4(0, 0, 0, 0);
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int kb = (kh2 * 4 + s) * 32 + kh * 16;   // byte offset of this lane's 8 k values
+            const uint4 xv = *(const uint4 *)(buf + (rb * 32 + m) * UROW + kb);
+            const uint4 av = *(const uint4 *)(buf + (64 + cb * 32 + m) * UROW + kb);
+            acc = mfma32(xv, av, acc);
         }
-        *(uint2 *)(hf + row * 128 + c4 * 4) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
-        *(uint2 *)(hf + row * 128 + 64 + c4 * 4) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+        --c_left;
+        if (++c_ku == a.upt || c_left == 0) {
+            finish_tile();
+            c_ku = 0; ++c_tile;
+        }
+    };
+
+    uint4 s0[4], s1[4], s2[4];
+    fetch(s0); fetch(s1); fetch(s2);
+    const int rounds = n / 3, rest = n - rounds * 3;
+    for (int r = 0; r + 1 < rounds; ++r) {
+        consume(s0); fetch(s0);
+        consume(s1); fetch(s1);
+        consume(s2); fetch(s2);
     }
+    if (rounds > 0) {                                  // last full round: refill only what the rest needs
+        consume(s0); if (rest > 0) fetch(s0);
+        consume(s1); if (rest > 1) fetch(s1);
+        consume(s2);
+    }
+    if (rest > 0) consume(s0);
+    if (rest > 1) consume(s1);
 }
 
 // Loads are issued unconditionally (clamped addresses): the compiler can wait for one load while
@@ -328,13 +378,26 @@ void seg_expand_kernel(const SegArgs a)
     block(n_blk - 1, std::false_type{});
 }
 
-int seg_ksplit_max() { return kMaxKsplit; }
+int seg_unit() { return KU; }
+
+int seg_shrink_capacity()
+{
+    static int cap = 0;
+    if (cap == 0) {
+        int per_cu = 0, cus = 0, dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, seg_shrink_kernel, NT, 0) != hipSuccess) return 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cap = per_cu * cus;
+    }
+    return cap;
+}
 
 hipError_t launch_seg_mfma(const SegArgs &a, hipStream_t st)
 {
     if (a.n_tiles <= 0 || a.n_ranges <= 0) return hipSuccess;
-    if (a.ksplit < 1 || a.ksplit > kMaxKsplit || a.klen % KT != 0 || (int64_t)a.klen * a.ksplit < a.d_in) return hipErrorInvalidValue;
-    const unsigned gs = (unsigned)(((int64_t)a.n_tiles * a.ksplit + 7) / 8 * 8);
+    if (a.n_swg < 1 || a.upt != (a.d_in + KU - 1) / KU) return hipErrorInvalidValue;
+    const unsigned gs = (unsigned)((a.n_swg + 7) / 8 * 8);
     seg_shrink_kernel<<<dim3(gs), dim3(NT), 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
