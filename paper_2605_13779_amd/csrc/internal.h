@@ -69,6 +69,7 @@ struct RowsArgs {
     int32_t ksplit, kslice_units, ntiles;
     int32_t tile_par;        // parts a chunk is cut into (one item each; 1 = one item per chunk): part p expands
     int32_t out_per_part;    // outputs [p * out_per_part, ...) and, in mode 2, shrinks k-slice p
+    int32_t poll_limit;      // polls of an exchange word before a reader takes the item on its own
     uint64_t *prof;          // debug: per-workgroup phase timestamps (null in normal use)
 };
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st);

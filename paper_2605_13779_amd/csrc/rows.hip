@@ -374,7 +374,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                                 if (do_shrink && k0 + k == kslice) { s += own; continue; }
                                 int spins = 0;
                                 while ((uint32_t)(wv[k] >> 32) != tag) {
-                                    if (++spins > kPollLimit) { gave_up = true; break; }
+                                    if (++spins > a.poll_limit) { gave_up = true; break; }
                                     __builtin_amdgcn_s_sleep(1);
                                     wv[k] = xch_get(xw + (int64_t)(k0 + k) * kChunk * RP);
                                 }
@@ -574,6 +574,10 @@ static void set_parts(RowsArgs &a, int parts, bool exchange)
     a.out_per_part = gpp * 64;
     a.tile_par = (groups + gpp - 1) / gpp;
     a.mode = 0; a.ksplit = 1; a.kslice_units = U;
+    // "rows_poll_limit" (testing): a negative value makes every reader give up at once, so that each
+    // item runs the path that does not depend on other workgroups
+    const int pl = tuning("rows_poll_limit");
+    a.poll_limit = pl < 0 ? 0 : (pl > 0 ? pl : kPollLimit);
     if (exchange && a.tile_par > 1) {
         int ku = (U + a.tile_par - 1) / a.tile_par;
         ku = (ku + 63) & ~63;
@@ -609,6 +613,7 @@ static hipError_t launch_rp(RowsArgs a, hipStream_t st)
     if (cap <= 0) return hipErrorUnknown;
     if (mode == 2 && can_exchange(a) && ksplit <= 8 && ksplit * RP <= 128) {
         a.mode = 1;
+        a.poll_limit = kPollLimit;
         a.ksplit = ksplit;
         a.kslice_units = (U + ksplit - 1) / ksplit;
         a.tile_par = 1; a.out_per_part = a.d_out;

@@ -185,6 +185,40 @@ def test_decode_multi_site_launch(M, oracle):
         P.noop_must_fail(c.y0, dref, np.nonzero(c.token_slot >= 0)[0])
 
 
+def test_decode_parts_when_partners_never_answer(M, oracle):
+    """A chunk of a dense site is cut into parts that trade partial sums.  With the wait for a
+    partner's words cut to nothing, every part that has not been answered yet takes its item on its
+    own (whole shrink): the result must meet the same bar, alone and in a grouped launch."""
+    shapes = [(2304, 1032, 16), (4096, 520, 8), (2304, 2056, 16)]
+    slots = W.rng(37).integers(-1, 6, size=77).astype(np.int32)
+    cases = [W.dense_case(f"solo{i}", 3300 + i, 77, di, do, 6, r, 32.0, token_slot=slots, std_a=0.05, std_b=0.05)
+             for i, (di, do, r) in enumerate(shapes)]
+    sites = [dense_site(M, c) for c in cases]
+    plan = M.Plan(77, 6)
+    M.lora_plan_decode(plan, torch.from_numpy(slots).cuda(), 6)
+    M.set_tuning("rows_poll_limit", -1)
+    try:
+        for c, site in zip(cases, sites):
+            y = P.dev_bf16(c.y0)
+            M.lora_apply_decode_planned(site, plan, P.dev_bf16(c.x), y)
+            torch.cuda.synchronize()
+            ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+            P.check_close(P.host_bits(y), ref, c.name)
+            P.check_untouched(P.host_bits(y), c.y0, c.token_slot < 0, c.name)
+            site.check()
+        grp = [0, 2]                                   # same rank: one launch
+        xs = [P.dev_bf16(cases[k].x) for k in grp]
+        ys = [P.dev_bf16(cases[k].y0) for k in grp]
+        M.lora_apply_decode_multi([sites[k] for k in grp], plan, xs, ys)
+        torch.cuda.synchronize()
+        for k, y in zip(grp, ys):
+            c = cases[k]
+            ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+            P.check_close(P.host_bits(y), ref, c.name + " (grouped)")
+    finally:
+        M.set_tuning("rows_poll_limit", 0)
+
+
 def test_graph_replay_keeps_results_right(M, oracle):
     """A captured graph replays the same kernel arguments; the launches that exchange partial
     results between workgroups must still tell one replay from the next.  Inputs change between
