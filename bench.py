@@ -345,8 +345,9 @@ def main():
     s = per["c2_layer"]
     achieved = head["dom_bytes_per_launch"] / (head["dom_us_per_launch"] * 1e-6) / 1e9
     roofline = {"bound": "hbm",
-                "kernel": "rows_multi_kernel<16,16> (grouped decode launch: shrink -> scale -> expand -> add; "
-                          "q/k/v in one launch, gate/up in one launch)",
+                "kernel": "rows_multi_kernel<16,8,*> (the two grouped decode launches of a layer, averaged: shrink -> "
+                          "scale -> expand -> add; q|k|v with one item per chunk, gate|up with chunks cut into parts "
+                          "that trade k-slice sums)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(),
                 "alg_bytes_per_launch": head["dom_bytes_per_launch"],
