@@ -33,8 +33,9 @@ struct RowsCfg {
     static constexpr int NV  = CS * JPW;                 // values per lane per pass (8)
     static constexpr int OPL = RP >= 8 ? 1 : 8 / RP;     // outputs per lane in the expand
     static constexpr int BV  = RP >= 8 ? RP / 8 : 1;     // 16-byte loads of B per lane
-    static constexpr int TILE = RP <= 4 ? NT * OPL : (RP <= 16 ? 1024 : 512);   // outputs per expand tile
-    static constexpr int DEPTH = NW == 16 ? 2 : 1;       // expand tiles kept in flight by an item that walks several
+    static constexpr bool MX0 = (RP == 8 || RP == 16) && kChunk == 4;
+    static constexpr int TILE = RP <= 4 ? NT * OPL : (RP <= 16 ? ((MX0 && NW == 8) ? 512 : 1024) : 512);   // outputs per expand tile
+    static constexpr int DEPTH = NW == 16 ? 2 : ((MX0 && NW == 8) ? 2 : 1);   // expand tiles kept in flight by an item that walks several
     static constexpr int EU  = TILE / (NT * OPL);        // outputs groups per lane per flight
     // The expand of a 4-row chunk is a small dense contraction (4 x RP times RP x 64 per wave and
     // output group); on the vector ALU it costs 4 * RP multiply-adds per lane and was what bounded
@@ -268,8 +269,8 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
 #pragma unroll
                 for (int q = 0; q < C::BV; ++q) braw[d][e][q] = *(const uint4 *)((const char *)Bg + (oc * (uint32_t)(RP * 2) + (uint32_t)(q * 16)));
 #pragma unroll
-                for (int c = 0; c < kChunk; ++c)
-                    if (c < cnt) yraw[d][e][c] = *(const yvec_t *)((const char *)yrow[c] + oc * 2u);
+                for (int c = 0; c < kChunk; ++c)      // rows past the chunk's count repeat its first row: every load is issued
+                    yraw[d][e][c] = *(const yvec_t *)((const char *)yrow[c] + oc * 2u);
             }
         };
         const char *Ag = (const char *)(a.a_tab + (int64_t)key * RP * a.d_in + (int64_t)(jg * C::JPW) * a.d_in);
@@ -284,8 +285,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
 #pragma unroll
             for (int jj = 0; jj < C::JPW; ++jj) av[jj] = *(const uint4 *)(Ag + (size_t)((uint32_t)jj * a_row_bytes) + ub);
 #pragma unroll
-            for (int c = 0; c < kChunk; ++c)
-                if (c < cnt) xv[c] = *(const uint4 *)((const char *)xp[c] + ub);
+            for (int c = 0; c < kChunk; ++c) xv[c] = *(const uint4 *)((const char *)xp[c] + ub);
         };
         // Tiles 1 .. DEPTH-1 of the expand are requested once the shrink's operands have been consumed
         // (their registers are free then) and travel while the partial sums are reduced and traded.
@@ -447,7 +447,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                                         yf[0] += d0[c] + d1[c];
                                         yvec_t out;
                                         y_pack(yf, out);
-                                        *(yvec_t *)((char *)yrow[c] + (uint32_t)o * 2u) = out;
+                                        st_quiet((char *)yrow[c] + (uint32_t)o * 2u, out);
                                     }
                                 }
                             } else {
@@ -477,7 +477,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                                         }
                                         yvec_t out;
                                         y_pack(yf, out);
-                                        *(yvec_t *)(yrow[c] + o) = out;
+                                        st_quiet(yrow[c] + o, out);
                                     }
                                 }
                             }

@@ -307,6 +307,21 @@ def test_segmented_small(M, oracle, r, d_in, d_out):
     P.check_close(b, ref, "dec")
 
 
+def test_segmented_many_tiles_in_batches(M, oracle):
+    """More 64-row tiles than one pair of prefill launches covers (several batches per call), one
+    long segment, many short ones, segments without adapter and on an empty slot, d_in that is not
+    a multiple of the k-unit and d_out that is not a multiple of a wave's 64 outputs."""
+    g = W.rng(51)
+    lens = [3000] + g.integers(1, 110, size=329).tolist()
+    T = int(sum(lens))                                 # about 21000 rows, about 650 tiles
+    seg_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    seg_slot = g.integers(-1, 6, size=len(lens)).astype(np.int32)
+    c = W.seg_case("seg_batches", 4100, T, len(lens), 272, 136, 6, 64, 128.0, ranks=[64, 64, 0, 48, 64, 17],
+                   seg_off=seg_off, seg_slot=seg_slot, std_a=0.05, std_b=0.05)
+    site = dense_site(M, c)
+    check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0))
+
+
 def test_segmented_rejects_bad_offsets(M):
     site = M.Site(64, 64, 64, 2)
     x = torch.zeros((10, 64), dtype=torch.bfloat16, device="cuda")
