@@ -65,8 +65,8 @@ struct RowsArgs {
     uint32_t *ctrl;          // [0] launch tag, [1] error flag, [2] top sign-in, [8..72) group sign-ins
     int32_t xch_chunks;
     // filled in by the launcher
-    int32_t mode;            // 0 nothing crosses workgroups; 1 shrink items + expand items; 2 parts that trade k-slices
-    int32_t ksplit, kslice_units, ntiles;
+    int32_t mode;            // 0 nothing crosses workgroups; 2 parts that trade k-slices
+    int32_t ksplit, kslice_units;
     int32_t tile_par;        // parts a chunk is cut into (one item each; 1 = one item per chunk): part p expands
     int32_t out_per_part;    // outputs [p * out_per_part, ...) and, in mode 2, shrinks k-slice p
     int32_t poll_limit;      // polls of an exchange word before a reader takes the item on its own

@@ -8,16 +8,18 @@
 // run to the padded rank.
 //
 // These launches last microseconds, so what matters is how few dependent memory round trips a
-// workgroup makes: every work item issues all of its loads in one flight.  Two shapes of launch:
-//   fused  one item per chunk: shrink, then expand, h stays in LDS (MoE sites, small d_in*d_out).
-//   split  the chunk's work is cut into k-slices of the shrink and tiles of the expand, all in
-//          ONE launch.  Shrink items publish their partial h (fp32, a few hundred bytes) through
-//          a small L2-resident exchange buffer; expand items prefetch their B rows and y values,
-//          then pick the partials up.  No adapter byte is read twice and a big d_in or d_out
-//          spreads over many CUs.  Each word of the exchange carries value and launch tag in one
-//          64-bit store, so no fences are needed; the launch grid never exceeds what the GPU
-//          keeps resident and every workgroup runs its shrink items before its expand items,
-//          so a waiting expand item always waits for a workgroup that is running and not waiting.
+// workgroup makes: every work item issues its loads in one flight.  Two shapes of launch:
+//   one item per chunk   shrink, then expand, h stays in LDS (MoE sites, rank-1 sites, and dense
+//                        launches that have enough chunks to fill the GPU).
+//   chunk parts          a dense launch with fewer chunks than the GPU has CUs cuts every chunk
+//                        into parts.  Part p shrinks k-slice p of d_in and expands its own range of
+//                        outputs; the parts trade their partial h (fp32, a few hundred bytes)
+//                        through a small L2-resident exchange buffer, while the B rows and y
+//                        values of the expand are already on their way.  No adapter byte is read
+//                        twice and a big d_in or d_out spreads over many CUs.  Each word of the
+//                        exchange carries value and launch tag in one 64-bit store, so no fences
+//                        are needed; a part whose partners have not published after a bounded
+//                        number of polls takes its item again on its own, with the whole shrink.
 #include "internal.h"
 
 namespace mlora {
@@ -35,7 +37,7 @@ struct RowsCfg {
     static constexpr int BV  = RP >= 8 ? RP / 8 : 1;     // 16-byte loads of B per lane
     static constexpr bool MX0 = (RP == 8 || RP == 16) && kChunk == 4;
     static constexpr int TILE = RP <= 4 ? NT * OPL : (RP <= 16 ? ((MX0 && NW == 8) ? 512 : 1024) : 512);   // outputs per expand tile
-    static constexpr int DEPTH = NW == 16 ? 2 : ((MX0 && NW == 8) ? 2 : 1);   // expand tiles kept in flight by an item that walks several
+    static constexpr int DEPTH = (MX0 && NW == 8) ? 2 : 1;   // expand tiles kept in flight by an item that walks several
     static constexpr int EU  = TILE / (NT * OPL);        // outputs groups per lane per flight
     // The expand of a 4-row chunk is a small dense contraction (4 x RP times RP x 64 per wave and
     // output group); on the vector ALU it costs 4 * RP multiply-adds per lane and was what bounded
@@ -147,7 +149,7 @@ __device__ __forceinline__ void y_pack(const float *f, uint4 &r)
 }
 
 // Work of workgroup `wg` out of `n_wg` on one site (one launch may cover several sites).
-// XCH: the kernel can pass partial shrink results between workgroups (a.mode 1 or 2).
+// XCH: the kernel can pass partial shrink results between workgroups (a.mode 2).
 template <int RP, int NW, bool XCH>
 __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const int n_wg)
 {
@@ -165,12 +167,9 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
     if (prof && tid == 0) { prof[0] = wall_clock64(); prof[7] = 0; }
 
     const bool use_x = XCH && a.mode != 0;                   // this site's items exchange partial results
-    const bool two_kinds = XCH && a.mode == 1;               // shrink items and expand items
     // Items are numbered over the upper bound of chunks, so an item's chunk record can be fetched
     // together with the live chunk count (and the launch tag) in one round trip.
-    const int n_shr = two_kinds ? a.grid_chunks * a.ksplit : 0;
-    const int n_items = two_kinds ? n_shr + a.grid_chunks * a.ntiles
-                                  : (a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : ((a.grid_chunks + 63) & ~63));
+    const int n_items = a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : ((a.grid_chunks + 63) & ~63);
 
     // Launches that exchange carry a tag that must differ from launch to launch, also when a
     // captured graph replays the same kernel arguments, so it lives in device memory: every
@@ -193,15 +192,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         bool do_shrink = true, do_expand = true;
         const bool solo = solo_next;
         solo_next = false;
-        if (two_kinds) {
-            if (item < n_shr) { chunk = item / a.ksplit; kslice = item - chunk * a.ksplit; do_expand = false; }
-            else {
-                const int e = item - n_shr;
-                chunk = e / a.ntiles;
-                out0 = (e - chunk * a.ntiles) * C::TILE; out1 = min(a.d_out, out0 + C::TILE);
-                do_shrink = solo;
-            }
-        } else if (a.tile_par > 1) {
+        if (a.tile_par > 1) {
             // workgroups are dealt round-robin to the 8 XCDs: keep the parts of one chunk (they share
             // the chunk's rows of x and its exchange words) on one XCD and its L2, and deal the chunks
             // over the XCDs
@@ -603,25 +594,9 @@ static int items_target(int cap)
 template <int RP, int NW>
 static hipError_t launch_rp(RowsArgs a, hipStream_t st)
 {
-    using C = RowsCfg<RP, NW>;
-    const int U = a.d_in >> 3;
-    const int ntiles = (a.d_out + C::TILE - 1) / C::TILE;
-    const int ksplit = (U + C::FLU - 1) / C::FLU;
-    a.ntiles = ntiles;
-    const int mode = tuning("rows_mode");     // 0 auto, 1 parts that redo the shrink, 2 shrink items + expand items, 3 one item per chunk
+    const int mode = tuning("rows_mode");     // 0 auto, 1 parts that redo the shrink, 3 one item per chunk
     const int cap = rows_capacity<RP, NW, true>();
     if (cap <= 0) return hipErrorUnknown;
-    if (mode == 2 && can_exchange(a) && ksplit <= 8 && ksplit * RP <= 128) {
-        a.mode = 1;
-        a.poll_limit = kPollLimit;
-        a.ksplit = ksplit;
-        a.kslice_units = (U + ksplit - 1) / ksplit;
-        a.tile_par = 1; a.out_per_part = a.d_out;
-        int64_t items = (int64_t)a.grid_chunks * (ksplit + ntiles);
-        if (items > cap) items = cap;
-        rows_kernel<RP, NW, true><<<dim3((unsigned)items), dim3(NW * 64), 0, st>>>(a);
-        return hipGetLastError();
-    }
     const bool exchange = can_exchange(a) && mode == 0;
     set_parts(a, mode == 3 ? 1 : items_target(cap) / a.grid_chunks, exchange);
     if (a.mode == 2) rows_kernel<RP, NW, true><<<dim3((unsigned)fused_grid(a)), dim3(NW * 64), 0, st>>>(a);
@@ -634,16 +609,8 @@ static hipError_t launch_nw(const RowsArgs &a, hipStream_t st)
 {
     const int U = a.d_in >> 3;
     int nw = tuning("rows_waves");
-    if (nw != 4 && nw != 8 && nw != 16) {
-        // 16 waves when one flight of them covers all of d_in (then every item is shrink + one tile,
-        // nothing crosses workgroups); else 8, or 4 when 8 would be mostly idle lanes
-        nw = U >= RowsCfg<RP, 8>::FLU * 3 / 4 ? 8 : 4;
-        if constexpr (RP >= 8 && RP <= 16) {
-            if (a.n_experts == 1 && U > RowsCfg<RP, 8>::FLU && U <= RowsCfg<RP, 16>::FLU && tuning("rows_single_waves") == 16) nw = 16;
-        }
-    }
+    if (nw != 4 && nw != 8) nw = U >= RowsCfg<RP, 8>::FLU * 3 / 4 ? 8 : 4;   // 4 when 8 would be mostly idle lanes
     if constexpr (RP >= 64) nw = 8;
-    if constexpr (RP >= 8 && RP <= 16) { if (nw == 16) return launch_rp<RP, 16>(a, st); }
     if (nw >= 8) return launch_rp<RP, 8>(a, st);
     if constexpr (RP < 64) return launch_rp<RP, 4>(a, st);
     return hipErrorInvalidValue;
@@ -675,19 +642,13 @@ static hipError_t launch_multi_rp(const RowsArgs *sites, int n, hipStream_t st)
     return hipGetLastError();
 }
 
-static int group_waves()
-{
-    const int nw = tuning("rows_group_waves");
-    return nw == 16 ? 16 : 8;
-}
-
 // Dense sites of rank 8 or 16 whose d_in keeps most lanes of the shrink busy can share a launch.
 bool rows_can_group(const RowsArgs &a)
 {
     if (a.r_pad != 8 && a.r_pad != 16) return false;
     const int U = a.d_in >> 3;
     const int flu8 = a.r_pad == 8 ? RowsCfg<8, 8>::FLU : RowsCfg<16, 8>::FLU;
-    return a.n_experts == 1 && U >= flu8 * 3 / 4 && tuning("rows_mode") != 2 && !tuning("rows_waves");
+    return a.n_experts == 1 && U >= flu8 * 3 / 4 && !tuning("rows_waves");
 }
 
 hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st)
@@ -696,8 +657,6 @@ hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st)
     for (int k = 0; k < n; ++k)
         if (sites[k].r_pad != sites[0].r_pad || !rows_can_group(sites[k])) return hipErrorInvalidValue;
     if (sites[0].grid_chunks <= 0) return hipSuccess;
-    if (group_waves() == 16)
-        return sites[0].r_pad == 8 ? launch_multi_rp<8, 16>(sites, n, st) : launch_multi_rp<16, 16>(sites, n, st);
     return sites[0].r_pad == 8 ? launch_multi_rp<8, 8>(sites, n, st) : launch_multi_rp<16, 8>(sites, n, st);
 }
 
