@@ -96,7 +96,7 @@ struct ShrinkShare {
 __global__ __launch_bounds__(NT, 4)
 void seg_shrink_kernel(const SegArgs a)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char buf[STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char buf2[2 * STAGE_BYTES];   // two stage buffers, used in turn
     __shared__ int s_last;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, kh = lane >> 5;
     const int b = xcd_contiguous_id();
@@ -134,7 +134,8 @@ void seg_shrink_kernel(const SegArgs a)
     const int rb = w & 1, cb = (w >> 1) & 1, kh2 = w >> 2;
     int c_tile = (int)(u0 / a.upt), c_ku = (int)(u0 - (int64_t)c_tile * a.upt);
     f32x16_t acc = {0};
-    auto finish_tile = [&]() {                         // this share's piece of tile c_tile is complete
+    // this share's piece of tile c_tile is complete; buf is the stage buffer that was multiplied last
+    auto finish_tile = [&](unsigned char *buf) {
         const int slot = a.tiles[4 * c_tile], nrows = a.tiles[4 * c_tile + 2];
         __syncthreads();                               // the staged unit has been read by every wave
         float *red = (float *)buf;                     // [k half][64 rows][64 adapter rows]
@@ -221,9 +222,13 @@ void seg_shrink_kernel(const SegArgs a)
         __syncthreads();                               // the partials' LDS is staged into again
     };
     int c_left = n;
+    // One barrier per unit: a unit is written into the buffer that was multiplied two units ago, and
+    // every wave has passed the barrier in between.
+    int c_par = 0;
     auto consume = [&](uint4 (&st)[4]) {
         const bool in = c_ku * KU + sseg * 8 < a.d_in; // d_in is a multiple of 16: a 16-byte piece is in or out as a whole
-        __syncthreads();                               // the previous unit has been read by every wave
+        unsigned char *buf = buf2 + c_par * STAGE_BYTES;
+        c_par ^= 1;
 #pragma unroll
         for (int q = 0; q < 4; ++q) *(uint4 *)(buf + (srow + 32 * q) * UROW + sseg * 16) = in ? st[q] : make_uint4(0, 0, 0, 0);
         __syncthreads();
@@ -236,7 +241,7 @@ void seg_shrink_kernel(const SegArgs a)
         }
         --c_left;
         if (++c_ku == a.upt || c_left == 0) {
-            finish_tile();
+            finish_tile(buf);
             c_ku = 0; ++c_tile;
         }
     };
