@@ -120,7 +120,7 @@ int32_t lora_apply_decode_planned(mlora_site *site, const mlora_plan *plan,
 
 /* Several dense sites that take the same batch plan, applied with as few launches as possible
  * (q/k/v of one layer, or gate/up, are independent of each other and can share one launch; sites
- * whose shape needs the split launch get one of their own).  sites, xs, ldxs, ys, ldys are HOST
+ * of another rank, MoE sites and sites with a small d_in get a launch of their own).  sites, xs, ldxs, ys, ldys are HOST
  * arrays of length n_sites; each (site, x, y) triple follows the rules of
  * lora_apply_decode_planned.  The result is that of n_sites separate calls up to the order in which
  * the fp32 partial sums of the shrink are added (a launch may cut d_in into more or fewer slices). */

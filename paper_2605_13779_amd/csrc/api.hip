@@ -27,7 +27,7 @@ struct mlora_site {
     float *scale;
     int64_t *catalog;
     mlora_plan priv;            // private plan living in the caller-provided scratch
-    uint32_t *ctrl;             // dense sites: launch tag / sign-in counters of split launches
+    uint32_t *ctrl;             // dense sites: launch tag / sign-in counters of launches whose workgroups trade partial sums
     uint64_t *xch;              // dense sites: partial shrink results in flight between workgroups
     int32_t *seg_dev;           // device area for segment tiles / chunks
     int32_t seg_cap;            // in entries of 3 ints
@@ -42,7 +42,7 @@ namespace {
 constexpr int32_t kDensePrivItems = 1024;      // rows per private dense plan (one-workgroup planner)
 constexpr int32_t kMoePrivItems = 131072;      // pairs per private MoE plan
 constexpr int32_t kSegCap = 65536;             // segment tiles / chunks per call
-constexpr int32_t kXchChunks = 256;            // chunks per launch that may use the split shape
+constexpr int32_t kXchChunks = 256;            // chunks per launch whose parts may trade partial sums
 constexpr size_t kCtrlBytes = 1024;
 constexpr size_t kXchBytes = (size_t)kXchChunks * 128 * kChunk * 8;   // <= 128 values per row of a chunk
 constexpr size_t kSegXchBytes = (size_t)24 << 20;   // rank-64 sites: exchange words, then the prefill's partial shrink results

@@ -223,7 +223,7 @@ def test_graph_replay_keeps_results_right(M, oracle):
     """A captured graph replays the same kernel arguments; the launches that exchange partial
     results between workgroups must still tell one replay from the next.  Inputs change between
     replays, every replay is compared with the eager result."""
-    c = W.dense_case("graph", 3200, 40, 4608, 264, 4, 16, 32.0, std_a=0.05, std_b=0.05)     # d_in needs the split launch
+    c = W.dense_case("graph", 3200, 40, 4608, 264, 4, 16, 32.0, std_a=0.05, std_b=0.05)     # few chunks, large d_in: the chunk parts trade k-slice sums through the tagged exchange words
     site = dense_site(M, c)
     plan = M.Plan(40, 4)
     ts = torch.from_numpy(c.token_slot).cuda()
