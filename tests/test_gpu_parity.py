@@ -255,13 +255,18 @@ def test_graph_replay_keeps_results_right(M, oracle):
 
 
 def test_c2_dense_decode_layer(M, oracle):
+    """The seven projections at full size, each in a launch of its own and then in the launch
+    configuration the benchmark times (q|k|v and gate|up grouped, o and down alone); 48 sampled
+    rows go to the oracle."""
     cases = W.c2_dense_decode()
     ts = torch.from_numpy(cases[0].token_slot).cuda()
     plan = M.Plan(256, 64)
     M.lora_plan_decode(plan, ts, 64)
     sample = W.rng(77).permutation(256)[:48]
+    sites = []
     for c in cases:
         site = dense_site(M, c)
+        sites.append(site)
 
         def runner(y0, site=site, c=c):
             x, y = P.dev_bf16(c.x), P.dev_bf16(y0)
@@ -269,6 +274,20 @@ def test_c2_dense_decode_layer(M, oracle):
             torch.cuda.synchronize()
             return P.host_bits(y)
         check_dense(M, oracle, c, runner, rows=sample)
+    xs = [P.dev_bf16(c.x) for c in cases]
+    ys = [P.dev_bf16(c.y0) for c in cases]
+    for grp in [(0, 1, 2), (3,), (4, 5), (6,)]:
+        if len(grp) == 1:
+            M.lora_apply_decode_planned(sites[grp[0]], plan, xs[grp[0]], ys[grp[0]])
+        else:
+            M.lora_apply_decode_multi([sites[k] for k in grp], plan, [xs[k] for k in grp], [ys[k] for k in grp])
+    torch.cuda.synchronize()
+    for c, site, y in zip(cases, sites, ys):
+        ref = oracle.apply_decode(c.x[sample], c.y0[sample], c.A, c.B, c.rank, c.alpha, c.token_slot[sample])
+        got = P.host_bits(y)
+        P.check_close(got[sample], ref, c.name + " (layer launches)")
+        P.check_untouched(got, c.y0, c.token_slot < 0, c.name)
+        site.check()
         site.close()
 
 
