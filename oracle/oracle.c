@@ -216,6 +216,58 @@ int oracle_apply_moe(const uint16_t *x, const uint16_t *y_in, double *y_out,
 }
 
 /*
+ * MoE down projection with the routing-weight combine (the per-expert LoRA tensors of Section 3.4
+ * on the expert down projection; the packed adapter of Section 4.4 stacks them per expert like the
+ * gate and up ones).  Pair p = t*K + k has its own input row (the expert's intermediate
+ * activation) and the K pairs of a token add into ONE output row, each times its routing weight:
+ *
+ *   y_out[t, :] = y_in[t, :] + sum_{k=0..K-1} w[t,k] * (alpha_s / r_s) * B_{s,e(t,k)} * (A_{s,e(t,k)} * x[t*K+k, :])
+ *
+ *   x [T*K, d_in] bf16 bits; y_in [T, d_out] bf16 bits; w [T, K] fp64 (fp32 values widened);
+ *   A_tab [n_slots, E, r_max, d_in]; B_tab [n_slots, E, d_out, r_max]; topk [T, K].
+ * k runs upwards.  Tokens without a usable slot are copied.  Return codes as oracle_apply_moe.
+ */
+int oracle_apply_moe_down(const uint16_t *x, const uint16_t *y_in, double *y_out,
+                          const uint16_t *A_tab, const uint16_t *B_tab,
+                          const int32_t *rank, const double *alpha,
+                          const int32_t *topk, const double *w, const int32_t *token_slot,
+                          int64_t T, int64_t K, int64_t E,
+                          int64_t d_in, int64_t d_out, int64_t n_slots, int64_t r_max)
+{
+    for (int64_t t = 0; t < T; ++t) {
+        if (token_slot[t] < -1 || token_slot[t] >= n_slots) return -1;
+        for (int64_t k = 0; k < K; ++k)
+            if (topk[t * K + k] < 0 || topk[t * K + k] >= E) return -3;
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t t = 0; t < T; ++t) {
+        int32_t s = token_slot[t];
+        copy_row(y_in + t * d_out, y_out + t * d_out, d_out);
+        if (s < 0 || rank[s] <= 0) continue;
+        int r = rank[s];
+        double scale = alpha[s] / (double)r;
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t p = t * K + k;
+            int64_t g = (int64_t)s * E + topk[p];
+            const uint16_t *A = A_tab + g * r_max * d_in, *B = B_tab + g * d_out * r_max;
+            double h[r];
+            for (int j = 0; j < r; ++j) {
+                double acc = 0.0;
+                for (int64_t i = 0; i < d_in; ++i)
+                    acc += oracle_bf16_to_f64(x[p * d_in + i]) * oracle_bf16_to_f64(A[(int64_t)j * d_in + i]);
+                h[j] = acc;
+            }
+            for (int64_t o = 0; o < d_out; ++o) {
+                double acc = 0.0;
+                for (int j = 0; j < r; ++j) acc += h[j] * oracle_bf16_to_f64(B[o * r_max + j]);
+                y_out[t * d_out + o] += w[p] * (scale * acc);
+            }
+        }
+    }
+    return 0;
+}
+
+/*
  * Route index build.  Eligible pairs (slot >= 0 and rank[slot] > 0) are sorted by
  * key = slot*E + expert with a stable counting sort, so ties keep ascending p.
  *   sorted_pair [T*K]  (first group_off[n_slots*E] entries valid, rest set to -1)

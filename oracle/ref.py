@@ -126,6 +126,33 @@ def apply_moe(x, y, A_tab, B_tab, rank, alpha, topk, token_slot):
     return out
 
 
+def apply_moe_down(x, y, A_tab, B_tab, rank, alpha, topk, w, token_slot):
+    """Down projection with the routing-weight combine.  x [T*K,d_in] (one input row per pair);
+    y [T,d_out]; w [T,K] routing weights; A_tab [S,E,r_max,d_in]; B_tab [S,E,d_out,r_max]."""
+    x, y, A_tab, B_tab = _u16(x), _u16(y), _u16(A_tab), _u16(B_tab)
+    topk = _i32(topk)
+    T, K = topk.shape
+    d_in, d_out = x.shape[1], y.shape[1]
+    S, E, r_max, _ = A_tab.shape
+    assert A_tab.shape == (S, E, r_max, d_in) and B_tab.shape == (S, E, d_out, r_max)
+    assert x.shape[0] == T * K and y.shape[0] == T
+    w = np.ascontiguousarray(np.asarray(w, dtype=np.float64))
+    assert w.shape == (T, K)
+    rank = _i32(rank)
+    alpha = np.ascontiguousarray(np.asarray(alpha, dtype=np.float64))
+    token_slot = _i32(token_slot)
+    out = np.empty((T, d_out), dtype=np.float64)
+    rc = lib().oracle_apply_moe_down(
+        _p(x, C.c_uint16), _p(y, C.c_uint16), _p(out, C.c_double),
+        _p(A_tab, C.c_uint16), _p(B_tab, C.c_uint16), _p(rank, C.c_int32), _p(alpha, C.c_double),
+        _p(topk, C.c_int32), _p(w, C.c_double), _p(token_slot, C.c_int32),
+        C.c_int64(T), C.c_int64(K), C.c_int64(E),
+        C.c_int64(d_in), C.c_int64(d_out), C.c_int64(S), C.c_int64(r_max))
+    if rc != 0:
+        raise ValueError(f"oracle_apply_moe_down rc={rc}")
+    return out
+
+
 def route_sort(topk, token_slot, rank, n_experts):
     """Returns (sorted_pair [T*K] int32 with -1 tail, group_off [S*E+1] int32)."""
     topk = _i32(topk)

@@ -253,6 +253,83 @@ def test_moe_same_slot_is_a_grouped_gemm(oracle):
     np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
 
 
+def down_small(seed, **kw):
+    p = dict(T=9, K=3, E=5, d_in=20, d_out=14, n_slots=3, r_max=2, alpha=4.0)
+    p.update(kw)
+    return W.moe_down_case("d", seed, **p)
+
+
+def down_numpy(c, w=None):
+    """The definition with numpy matmuls on independently widened values."""
+    w = c.w.astype(np.float64) if w is None else w
+    x, want, A, B = f64(c.x), f64(c.y0).copy(), f64(c.A), f64(c.B)
+    for t in range(c.T):
+        s = c.token_slot[t]
+        if s < 0 or c.rank[s] == 0:
+            continue
+        for k in range(c.K):
+            p, e = t * c.K + k, c.topk[t, k]
+            want[t] += w[t, k] * (c.alpha[s] / c.rank[s]) * (B[s, e] @ (A[s, e] @ x[p]))
+    return want
+
+
+def test_moe_down_against_numpy_matmul(oracle):
+    c = down_small(111, ranks=[2, 1, 2])
+    c.token_slot[4] = -1
+    got = oracle.apply_moe_down(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, c.w, c.token_slot)
+    np.testing.assert_allclose(got, down_numpy(c), rtol=1e-12, atol=1e-13)
+    assert np.array_equal(got[4], f64(c.y0)[4])                       # no slot: copied
+
+
+def test_moe_down_merged_weight_brute_force(oracle):
+    """Tiny case against the merged per-(slot, expert) matrix W' = (alpha/r) B A, formed first."""
+    c = down_small(112, T=5, K=2, E=3, d_in=6, d_out=4, r_max=2)
+    got = oracle.apply_moe_down(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, c.w, c.token_slot)
+    x, want, A, B = f64(c.x), f64(c.y0).copy(), f64(c.A), f64(c.B)
+    Wm = np.einsum("seoj,seji->seoi", B, A) * (c.alpha / c.rank)[:, None, None, None]
+    for t in range(c.T):
+        for k in range(c.K):
+            for o in range(c.d_out):
+                for i in range(c.d_in):
+                    want[t, o] += float(c.w[t, k]) * Wm[c.token_slot[t], c.topk[t, k], o, i] * x[t * c.K + k, i]
+    np.testing.assert_allclose(got, want, rtol=1e-11, atol=1e-12)
+
+
+def test_moe_down_single_pair_with_unit_weight_is_the_gate_up_form(oracle):
+    """K = 1 and w = 1: one input row and one output row per token, i.e. the pair-major apply."""
+    c = down_small(113, K=1)
+    ones = np.ones((c.T, 1), dtype=np.float32)
+    got = oracle.apply_moe_down(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, ones, c.token_slot)
+    ref = oracle.apply_moe(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, c.token_slot)
+    np.testing.assert_allclose(got, ref, rtol=1e-13, atol=1e-14)
+
+
+def test_moe_down_weights_are_linear_and_zero_weight_pairs_vanish(oracle):
+    c = down_small(114)
+    y0 = f64(c.y0)
+    base = oracle.apply_moe_down(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, c.w, c.token_slot) - y0
+    twice = oracle.apply_moe_down(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, 2 * c.w, c.token_slot) - y0
+    np.testing.assert_allclose(twice, 2 * base, rtol=1e-12, atol=1e-13)
+    none = oracle.apply_moe_down(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, 0 * c.w, c.token_slot)
+    assert np.array_equal(none, y0)
+    w1 = c.w.copy()
+    w1[:, 1:] = 0                                                     # only the first pair of each token counts
+    first = oracle.apply_moe_down(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, w1, c.token_slot)
+    np.testing.assert_allclose(first, down_numpy(c, w1.astype(np.float64)), rtol=1e-12, atol=1e-13)
+    assert not np.allclose(first, base + y0)                          # and the other pairs did matter
+
+
+def test_moe_down_order_of_a_tokens_pairs_does_not_matter(oracle):
+    """Reordering the K (expert, weight, input row) triples of every token only reassociates the sum."""
+    c = down_small(115)
+    got = oracle.apply_moe_down(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, c.w, c.token_slot)
+    perm = np.array([2, 0, 1])
+    x2 = c.x.reshape(c.T, c.K, c.d_in)[:, perm].reshape(c.T * c.K, c.d_in)
+    got2 = oracle.apply_moe_down(x2, c.y0, c.A, c.B, c.rank, c.alpha, np.ascontiguousarray(c.topk[:, perm]),
+                                 np.ascontiguousarray(c.w[:, perm]), c.token_slot)
+    np.testing.assert_allclose(got2, got, rtol=1e-12, atol=1e-13)
+
+
 def test_route_sort_against_python_sorted(oracle):
     for seed, kw in [(111, {}), (112, dict(T=64, K=4, E=8, n_slots=5)), (113, dict(T=5, K=1, E=1))]:
         c = moe_small(seed, **kw)

@@ -115,6 +115,30 @@ class MoECase:
     topk: np.ndarray
 
 
+@dataclass
+class MoEDownCase:
+    """Packed MoE site on the expert down projection: x is pair-major [T*K, d_in] (an expert's
+    intermediate activation per routed pair), y0 is token-major [T, d_out], w [T, K] fp32 routing
+    weights (positive, summing to one per token)."""
+    name: str
+    T: int
+    K: int
+    E: int
+    d_in: int
+    d_out: int
+    n_slots: int
+    r_max: int
+    x: np.ndarray
+    y0: np.ndarray
+    A: np.ndarray
+    B: np.ndarray
+    rank: np.ndarray
+    alpha: np.ndarray
+    token_slot: np.ndarray
+    topk: np.ndarray
+    w: np.ndarray
+
+
 def _adapters(g, lead, r_max, d_in, d_out, ranks_per_slot, std_a, std_b):
     """lead = (S,) or (S, E).  Rows j >= rank of the slot are zero-filled."""
     A = normal_bf16(g, lead + (r_max, d_in), std_a)
@@ -178,6 +202,30 @@ def moe_case(name, seed, T, K, E, d_in, d_out, n_slots, r_max, alpha, *, ranks=N
 
 # ---- the five benchmark configurations ------------------------------------------------------
 
+def routing_weights(g: np.random.Generator, T: int, K: int) -> np.ndarray:
+    """Softmax over K N(0,1) logits per token (the weights of the selected experts renormalised
+    over the selection), fp32 [T, K]."""
+    z = g.standard_normal((T, K), dtype=np.float32).astype(np.float64)
+    e = np.exp(z - z.max(axis=1, keepdims=True))
+    return np.ascontiguousarray((e / e.sum(axis=1, keepdims=True)).astype(np.float32))
+
+
+def moe_down_case(name, seed, T, K, E, d_in, d_out, n_slots, r_max, alpha, *, ranks=None,
+                  token_slot=None, std_x=1.0, std_y=1.0, std_a=0.02, std_b=0.02) -> MoEDownCase:
+    g = rng(seed)
+    ranks = np.full(n_slots, r_max, dtype=np.int32) if ranks is None else np.asarray(ranks, dtype=np.int32)
+    x = normal_bf16(g, (T * K, d_in), std_x)
+    y0 = normal_bf16(g, (T, d_out), std_y)
+    A, B = _adapters(g, (n_slots, E), r_max, d_in, d_out, ranks, std_a, std_b)
+    if token_slot is None:
+        token_slot = g.integers(0, n_slots, size=T).astype(np.int32)
+    topk = topk_routing(g, T, E, K)
+    w = routing_weights(g, T, K)
+    alpha_arr = np.broadcast_to(np.asarray(alpha, dtype=np.float64), (n_slots,)).copy()
+    return MoEDownCase(name, T, K, E, d_in, d_out, n_slots, r_max, x, y0, A, B, ranks, alpha_arr,
+                       np.asarray(token_slot, dtype=np.int32), topk, w)
+
+
 def c1_tiny_decode() -> DenseCase:
     """64 tokens, 256->256, 8 slots rank 8 alpha 16, values ~N(0, 1/sqrt(fan_in)) (fan_in = d_in
     for x, A and y0; = r for B), slot index uniform in {-1..7}."""
@@ -219,6 +267,17 @@ def c4_moe_packed(proj: str = "gate") -> MoECase:
     i = {"gate": 0, "up": 1}[proj]
     c = moe_case(f"c4_{proj}", SEED0 + 400 + i, 2048, 8, 128, 2048, 768, 32, 8, 16.0)
     g = rng(SEED0 + 4)  # routing and slots are shared by both projections
+    c.token_slot = g.integers(0, 32, size=2048).astype(np.int32)
+    c.topk = topk_routing(g, 2048, 128, 8)
+    return c
+
+
+def c4_moe_down() -> MoEDownCase:
+    """The down projection of the c4 layer: 2048 tokens, 128 experts of intermediate 768 back to
+    hidden 2048, top-8 with routing weights, 32 slots rank 8 alpha 16; routing and slots are the
+    ones of the gate and up sites."""
+    c = moe_down_case("c4_down", SEED0 + 402, 2048, 8, 128, 768, 2048, 32, 8, 16.0)
+    g = rng(SEED0 + 4)
     c.token_slot = g.integers(0, 32, size=2048).astype(np.int32)
     c.topk = topk_routing(g, 2048, 128, 8)
     return c
