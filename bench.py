@@ -11,7 +11,7 @@ forward pass over 36 layers.  The timed loop is a HIP graph replay.
 
 Prints ONE JSON line: tokens/s of the layer step, the HBM roofline of the dominant kernel, and
 the CPU oracle timed on the same workload.  Other configurations are reported under
-"per_config".  `--workload c3|c4|c5` times a single configuration (used for profiling).
+"per_config".  `--workload c3|c4|c4d|c5|c5w` times a single configuration (used for profiling).
 """
 import argparse
 import json
@@ -202,6 +202,42 @@ def bench_c4(M, W, steps, warmup, n_sets=2):
             "bytes_per_step": 2 * moe_bytes(cg)}
 
 
+def moe_down_bytes(c):
+    """Algorithmic bytes: every pair's input row, y once in and once out, each touched (slot, expert)
+    adapter once, weights and indices.  The fp32 workspace the two-launch form writes and reads
+    (T*K*d_out*4 bytes each way) is not algorithmic."""
+    keys = set((int(c.token_slot[t]) * c.E + int(e)) for t in range(c.T) for e in c.topk[t])
+    P = c.T * c.K
+    return P * c.d_in * 2 + 2 * c.T * c.d_out * 2 + len(keys) * c.r_max * (c.d_in + c.d_out) * 2 + 2 * P * 4 + c.T * 4
+
+
+def bench_c4_down(M, W, steps, warmup, n_sets=2):
+    """Down projection of the c4 layer with the routing-weight combine; the route plan is the one
+    the gate and up sites built, so only the two launches of the apply are timed."""
+    import torch
+    c = W.c4_moe_down()
+    topk, ts = torch.from_numpy(c.topk).cuda(), torch.from_numpy(c.token_slot).cuda()
+    w = torch.from_numpy(c.w).cuda()
+    plan = M.Plan(c.T * c.K, c.n_slots * c.E)
+    M.moe_plan_route(plan, topk, ts, c.n_slots, c.E)
+    ws = torch.empty(M.moe_down_workspace_bytes(c.T, c.K, c.d_out), dtype=torch.uint8, device="cuda")
+    sets = []
+    for _ in range(n_sets):
+        site = M.Site(c.d_in, c.d_out, c.r_max, c.n_slots, n_experts=c.E)
+        upload_case(M, site, c)
+        sets.append((site, dev_bf16(c.x), dev_bf16(c.y0)))
+    torch.cuda.synchronize()
+
+    def sweep():
+        for site, x, y in sets:
+            M.moe_lora_apply_down(site, plan, x, w, ts, ws, y)
+
+    g = graph_of(sweep)
+    ms = time_region(g.replay, max(1, steps // n_sets), max(1, warmup // n_sets)) / n_sets
+    return {"ms_per_step": ms, "ms_apply_only": ms, "tokens": c.T, "launches_per_step": 2,
+            "bytes_per_step": moe_down_bytes(c)}
+
+
 def bench_c5(M, W, steps, warmup, wide=False, n_sets=3):
     import torch
     c = W.c5_segmented(wide)
@@ -290,7 +326,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="all", choices=["all", "c2", "c3", "c4", "c5", "c5w", "copy"])
+    ap.add_argument("--workload", default="all", choices=["all", "c2", "c3", "c4", "c4d", "c5", "c5w", "copy"])
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--tune", action="append", default=[], help="name=value for mlora_set_tuning")
     args = ap.parse_args()
@@ -322,6 +358,10 @@ def main():
     if args.workload in ("all", "c4"):
         log("[bench] c4 packed MoE")
         per["c4_moe_gate_up"] = summarize(bench_c4(M, W, max(20, args.steps // 10), max(4, args.warmup // 10)))
+        torch.cuda.empty_cache()
+    if args.workload in ("all", "c4d"):
+        log("[bench] c4 MoE down projection + combine")
+        per["c4_moe_down"] = summarize(bench_c4_down(M, W, max(20, args.steps // 10), max(4, args.warmup // 10)))
         torch.cuda.empty_cache()
     if args.workload in ("all", "c5"):
         log("[bench] c5 segmented prefill 7168->7168")

@@ -144,6 +144,23 @@ int32_t moe_plan_route(mlora_plan *plan, const int32_t *topk_ids, const int32_t 
 int32_t moe_lora_apply_planned(mlora_site *site, const mlora_plan *plan,
                                const void *x, int64_t ldx, void *y, int64_t ldy, void *stream);
 
+/* MoE down projection with the routing-weight combine (per-expert LoRA tensors on the expert down
+ * projection, Sections 3.4 and 4.4): pair p = t*K + k has its own input row x[p, :] (the expert's
+ * intermediate activation) and the K pairs of a token add into one output row,
+ *
+ *     y[t, :] += sum_{k = 0..K-1} pair_w[t, k] * (alpha_s / r_s) * B_{s,e(t,k)} * (A_{s,e(t,k)} * x[p, :])
+ *
+ * with k upwards in fp32 and one rounding to bf16: no atomics, the result is deterministic.
+ *   plan: from moe_plan_route on the same topk_ids / token_slot;  x: [T*K, d_in];  y: [T, d_out];
+ *   pair_w: DEVICE fp32 [T, K];  token_slot: DEVICE int32[T], the array given to moe_plan_route;
+ *   workspace: DEVICE, moe_down_workspace_bytes(T, K, d_out) bytes, 16-byte aligned, overwritten.
+ * Two launches: weighted fp32 deltas per pair into the workspace, then the per-token sum.
+ * Errors: as moe_lora_apply_planned; MLORA_E_INVALID on null pointers. */
+int32_t moe_down_workspace_bytes(int32_t T, int32_t K, int32_t d_out, size_t *bytes);
+int32_t moe_lora_apply_down(mlora_site *site, const mlora_plan *plan, const void *x, int64_t ldx,
+                            const float *pair_w, const int32_t *token_slot, void *workspace,
+                            void *y, int64_t ldy, void *stream);
+
 /* ---- the four calls of the problem statement ------------------------------------------------ */
 
 /* Decode: one token per row, gather-by-index.  Equivalent to lora_plan_decode on the site's

@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     MLoraError, Site, Plan, load_library, set_tuning,
     lora_slots_upload, lora_slots_evict, lora_apply_decode, lora_apply_segmented,
     moe_lora_apply_packed, lora_plan_decode, lora_apply_decode_planned, moe_plan_route,
-    moe_lora_apply_planned, lora_apply_decode_multi,
+    moe_lora_apply_planned, lora_apply_decode_multi, moe_down_workspace_bytes, moe_lora_apply_down,
 )

@@ -43,6 +43,8 @@ SIGNATURES = {
     "lora_apply_decode_multi": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_plan_route": (_i32, [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]),
     "moe_lora_apply_planned": (_i32, [_vp, _vp, _vp, _i64, _vp, _i64, _vp]),
+    "moe_down_workspace_bytes": (_i32, [_i32, _i32, _i32, C.POINTER(_sz)]),
+    "moe_lora_apply_down": (_i32, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _i64, _vp]),
     "lora_apply_decode": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _i32, _vp]),
     "lora_apply_segmented": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _vp, _i32, _i32, _vp]),
     "moe_lora_apply_packed": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _vp, _i32, _i32, _vp, _vp, _vp]),
@@ -255,3 +257,20 @@ def moe_lora_apply_planned(site, plan, x, y, stream=None):
     py, ldy = _rows(y)
     _check("moe_lora_apply_planned", load_library().moe_lora_apply_planned(
         site.handle, plan.handle, px, ldx, py, ldy, _stream(stream)))
+
+
+def moe_down_workspace_bytes(T, K, d_out):
+    n = _sz()
+    _check("moe_down_workspace_bytes", load_library().moe_down_workspace_bytes(T, K, d_out, C.byref(n)))
+    return n.value
+
+
+def moe_lora_apply_down(site, plan, x, pair_w, token_slot, workspace, y, stream=None):
+    """x [T*K, d_in] pair-major, pair_w fp32 [T, K], y [T, d_out]; workspace: a uint8 device tensor of
+    moe_down_workspace_bytes(T, K, d_out) bytes."""
+    px, ldx = _rows(x)
+    py, ldy = _rows(y)
+    assert pair_w.is_contiguous() and workspace.is_contiguous()
+    _check("moe_lora_apply_down", load_library().moe_lora_apply_down(
+        site.handle, plan.handle, px, ldx, _dev_ptr(pair_w, torch.float32), _dev_ptr(token_slot, torch.int32),
+        C.c_void_p(workspace.data_ptr()), py, ldy, _stream(stream)))

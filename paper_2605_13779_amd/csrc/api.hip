@@ -565,6 +565,38 @@ int32_t moe_lora_apply_planned(mlora_site *s, const mlora_plan *plan, const void
     return apply_planned_impl(s, plan, x, ldx, y, ldy, (hipStream_t)stream);
 }
 
+int32_t moe_down_workspace_bytes(int32_t T, int32_t K, int32_t d_out, size_t *bytes)
+{
+    if (!bytes || T < 0 || K <= 0 || d_out <= 0 || (d_out & 7)) return MLORA_E_INVALID;
+    *bytes = align256((size_t)T * K * d_out * sizeof(float));
+    return MLORA_OK;
+}
+
+int32_t moe_lora_apply_down(mlora_site *s, const mlora_plan *plan, const void *x, int64_t ldx,
+                            const float *pair_w, const int32_t *token_slot, void *workspace,
+                            void *y, int64_t ldy, void *stream)
+{
+    if (!s || !plan) return MLORA_E_INVALID;
+    if (s->d.n_experts <= 0 || !plan->moe) return MLORA_E_UNSUPPORTED;
+    if (plan->items == 0) return MLORA_OK;
+    if (plan->n_experts != s->d.n_experts || plan->n_slots > s->d.n_slots) return MLORA_E_SHAPE;
+    if (!pair_w || !token_slot || !workspace || !aligned16(workspace)) return MLORA_E_INVALID;
+    int32_t rc = check_xy(s, x, ldx, y, ldy);
+    if (rc) return rc;
+    DeviceGuard g(s->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    hipStream_t st = (hipStream_t)stream;
+    RowsArgs a = rows_args(s, x, ldx, y, ldy);
+    a.chunks = plan->pv.chunks;
+    a.top_k = 1;                                   // one input row per pair
+    a.grid_chunks = plan->grid_chunks;
+    a.out_f32 = (float *)workspace; a.ldo = s->d.d_out; a.row_w = pair_w;
+    if (!ok(launch_rows(a, st))) return MLORA_E_HIP;
+    const int32_t T = plan->items / plan->top_k;
+    return ok(launch_moe_combine((uint16_t *)y, ldy, (const float *)workspace, s->d.d_out, token_slot, s->rank,
+                                 s->d.n_slots, T, plan->top_k, s->d.d_out, st)) ? MLORA_OK : MLORA_E_HIP;
+}
+
 int32_t lora_apply_decode(mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy,
                           const int32_t *token_slot, int32_t T, void *stream)
 {

@@ -70,12 +70,18 @@ struct RowsArgs {
     int32_t tile_par;        // parts a chunk is cut into (one item each; 1 = one item per chunk): part p expands
     int32_t out_per_part;    // outputs [p * out_per_part, ...) and, in mode 2, shrinks k-slice p
     int32_t poll_limit;      // polls of an exchange word before a reader takes the item on its own
+    // MoE down projection: instead of adding into y, row p writes row_w[p] * delta as fp32 into
+    // out_f32[p, :] (no read); a second launch adds a token's rows in order
+    float *out_f32; int64_t ldo;
+    const float *row_w;
     uint64_t *prof;          // debug: per-workgroup phase timestamps (null in normal use)
 };
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st);
 constexpr int kMaxMulti = 4;     // sites per grouped launch
 bool rows_can_group(const RowsArgs &a);
 hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st);
+hipError_t launch_moe_combine(uint16_t *y, int64_t ldy, const float *parts, int64_t ldo, const int32_t *token_slot,
+                              const int32_t *rank, int32_t n_slots, int32_t T, int32_t K, int32_t d_out, hipStream_t st);
 
 // seg_mfma.hip: rank-64 segmented apply on the matrix cores (a shrink launch, then an expand launch)
 struct SegArgs {

@@ -245,9 +245,16 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         const bool xitem = use_x && !solo;
         // ---- one flight: every load of this item is issued here ----
         const uint16_t *Bg = a.b_tab + (int64_t)key * a.d_out * RP;
+        const bool to_parts = a.out_f32 != nullptr;               // MoE down projection: weighted fp32 deltas, no add into y
         uint16_t *yrow[kChunk];
+        float *prow[kChunk];
+        float wrow[kChunk];
 #pragma unroll
-        for (int c = 0; c < kChunk; ++c) yrow[c] = a.y + (int64_t)row[c] * a.ldy;
+        for (int c = 0; c < kChunk; ++c) {
+            yrow[c] = a.y + (int64_t)row[c] * a.ldy;
+            prow[c] = a.out_f32 + (int64_t)row[c] * a.ldo;
+            wrow[c] = to_parts ? a.row_w[row[c] + lane_zero] : 1.f;
+        }
         uint4 braw[C::DEPTH][C::EU][C::BV];
         yvec_t yraw[C::DEPTH][C::EU][kChunk];
         auto load_tile = [&](int lo, auto dconst) {
@@ -259,9 +266,11 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                 // uniform 64-bit base + 32-bit per-lane byte offset: no 64-bit address registers per lane
 #pragma unroll
                 for (int q = 0; q < C::BV; ++q) braw[d][e][q] = *(const uint4 *)((const char *)Bg + (oc * (uint32_t)(RP * 2) + (uint32_t)(q * 16)));
+                if (!to_parts) {
 #pragma unroll
-                for (int c = 0; c < kChunk; ++c)      // rows past the chunk's count repeat its first row: every load is issued
-                    yraw[d][e][c] = *(const yvec_t *)((const char *)yrow[c] + oc * 2u);
+                    for (int c = 0; c < kChunk; ++c)  // rows past the chunk's count repeat its first row: every load is issued
+                        yraw[d][e][c] = *(const yvec_t *)((const char *)yrow[c] + oc * 2u);
+                }
             }
         };
         const char *Ag = (const char *)(a.a_tab + (int64_t)key * RP * a.d_in + (int64_t)(jg * C::JPW) * a.d_in);
@@ -433,12 +442,16 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
 #pragma unroll
                                 for (int c = 0; c < kChunk; ++c) {
                                     if (c < cnt && o < out1 && rank > 0) {        // empty slot: rows stay untouched
-                                        float yf[1];
-                                        y_unpack(yraw[d][e][c], yf);
-                                        yf[0] += d0[c] + d1[c];
-                                        yvec_t out;
-                                        y_pack(yf, out);
-                                        st_quiet((char *)yrow[c] + (uint32_t)o * 2u, out);
+                                        if (to_parts) {
+                                            st_quiet((char *)prow[c] + (uint32_t)o * 4u, __float_as_uint(wrow[c] * (d0[c] + d1[c])));
+                                        } else {
+                                            float yf[1];
+                                            y_unpack(yraw[d][e][c], yf);
+                                            yf[0] += d0[c] + d1[c];
+                                            yvec_t out;
+                                            y_pack(yf, out);
+                                            st_quiet((char *)yrow[c] + (uint32_t)o * 2u, out);
+                                        }
                                     }
                                 }
                             } else {
@@ -458,7 +471,12 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                                 for (int c = 0; c < kChunk; ++c) {
                                     if (c < cnt && o < out1 && rank > 0) {        // empty slot: rows stay untouched
                                         float yf[C::OPL];
-                                        y_unpack(yraw[d][e][c], yf);
+                                        if (to_parts) {
+#pragma unroll
+                                            for (int q = 0; q < C::OPL; ++q) yf[q] = 0.f;
+                                        } else {
+                                            y_unpack(yraw[d][e][c], yf);
+                                        }
 #pragma unroll
                                         for (int q = 0; q < C::OPL; ++q) {
                                             float dlt = 0.f;
@@ -466,9 +484,14 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                                             for (int j = 0; j < RP; ++j) dlt = fmaf(hs[c][j], bf[q * RP + j], dlt);
                                             yf[q] += dlt;
                                         }
-                                        yvec_t out;
-                                        y_pack(yf, out);
-                                        st_quiet(yrow[c] + o, out);
+                                        if (to_parts) {
+#pragma unroll
+                                            for (int q = 0; q < C::OPL; ++q) st_quiet(prow[c] + o + q, __float_as_uint(wrow[c] * yf[q]));
+                                        } else {
+                                            yvec_t out;
+                                            y_pack(yf, out);
+                                            st_quiet(yrow[c] + o, out);
+                                        }
                                     }
                                 }
                             }
@@ -673,6 +696,54 @@ hipError_t launch_rows(const RowsArgs &a, hipStream_t st)
         case 64: return launch_nw<64>(a, st);
     }
     return hipErrorInvalidValue;
+}
+
+// Second launch of the MoE down projection: token t adds its K rows of weighted fp32 deltas, k
+// upwards (a fixed order: no atomics, the result is deterministic), to y[t, :] and rounds once.
+// Tokens whose slot holds no adapter are skipped; their rows of `parts` were never written.
+__global__ __launch_bounds__(256)
+void moe_combine_kernel(uint16_t *y, int64_t ldy, const float *parts, int64_t ldo, const int32_t *token_slot,
+                        const int32_t *rank, int32_t n_slots, int32_t K, int32_t d_out)
+{
+    const int t = (int)blockIdx.x;
+    const int s = token_slot[t];
+    if (s < 0 || s >= n_slots || rank[s] <= 0) return;
+    uint16_t *yr = y + (int64_t)t * ldy;
+    const float *pr = parts + (int64_t)t * K * ldo;
+    for (int o = (int)threadIdx.x * 8; o < d_out; o += 256 * 8) {
+        const uint4 yv = *(const uint4 *)(yr + o);
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int k0 = 0; k0 < K; k0 += 4) {            // four rows in flight at a time
+            float4 v[4][2];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int kk = min(k0 + k, K - 1);
+                v[k][0] = *(const float4 *)(pr + (int64_t)kk * ldo + o);
+                v[k][1] = *(const float4 *)(pr + (int64_t)kk * ldo + o + 4);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (k0 + k < K) {
+                    acc[0] += v[k][0].x; acc[1] += v[k][0].y; acc[2] += v[k][0].z; acc[3] += v[k][0].w;
+                    acc[4] += v[k][1].x; acc[5] += v[k][1].y; acc[6] += v[k][1].z; acc[7] += v[k][1].w;
+                }
+            }
+        }
+        uint4 out;
+        out.x = pack_bf2(bf_lo(yv.x) + acc[0], bf_hi(yv.x) + acc[1]);
+        out.y = pack_bf2(bf_lo(yv.y) + acc[2], bf_hi(yv.y) + acc[3]);
+        out.z = pack_bf2(bf_lo(yv.z) + acc[4], bf_hi(yv.z) + acc[5]);
+        out.w = pack_bf2(bf_lo(yv.w) + acc[6], bf_hi(yv.w) + acc[7]);
+        *(uint4 *)(yr + o) = out;
+    }
+}
+
+hipError_t launch_moe_combine(uint16_t *y, int64_t ldy, const float *parts, int64_t ldo, const int32_t *token_slot,
+                              const int32_t *rank, int32_t n_slots, int32_t T, int32_t K, int32_t d_out, hipStream_t st)
+{
+    if (T <= 0) return hipSuccess;
+    moe_combine_kernel<<<dim3((unsigned)T), dim3(256), 0, st>>>(y, ldy, parts, ldo, token_slot, rank, n_slots, K, d_out);
+    return hipGetLastError();
 }
 
 }  // namespace mlora

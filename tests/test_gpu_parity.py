@@ -441,6 +441,56 @@ def test_moe_planned_reuse(M, oracle):
         P.check_close(P.host_bits(y), ref, c.name)
 
 
+def run_moe_down(M, site, c, y0_bits):
+    x, y = P.dev_bf16(c.x), P.dev_bf16(y0_bits)
+    topk, ts = torch.from_numpy(c.topk).cuda(), torch.from_numpy(c.token_slot).cuda()
+    w = torch.from_numpy(c.w).cuda()
+    plan = M.Plan(c.T * c.K, c.n_slots * c.E)
+    M.moe_plan_route(plan, topk, ts, c.n_slots, c.E, ready_from=site)
+    ws = torch.empty(M.moe_down_workspace_bytes(c.T, c.K, c.d_out), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)                                     # NaN patterns: rows that must not be read would show
+    M.moe_lora_apply_down(site, plan, x, w, ts, ws, y)
+    torch.cuda.synchronize()
+    return P.host_bits(y)
+
+
+def check_moe_down(M, oracle, c, site, tokens=None):
+    sel = np.arange(c.T) if tokens is None else np.asarray(tokens)
+    pairs = (sel[:, None] * c.K + np.arange(c.K)[None, :]).reshape(-1)
+    args = (c.A, c.B, c.rank, c.alpha, c.topk[sel], c.w[sel], c.token_slot[sel])
+    ref = oracle.apply_moe_down(c.x[pairs], c.y0[sel], *args)
+    got = run_moe_down(M, site, c, c.y0)
+    P.check_close(got[sel], ref, c.name)
+    eff = np.array([s >= 0 and c.rank[s] > 0 for s in c.token_slot])
+    P.check_untouched(got, c.y0, ~eff, c.name)
+    zero = np.zeros_like(c.y0)
+    dref = oracle.apply_moe_down(c.x[pairs], zero[sel], *args)
+    gz = run_moe_down(M, site, c, zero)
+    P.check_delta(gz[sel], dref, c.name + " delta")
+    P.noop_must_fail(c.y0[sel], dref, np.nonzero(eff[sel])[0])
+    assert np.array_equal(got, run_moe_down(M, site, c, c.y0)), "two runs differ: the combine must be deterministic"
+
+
+@pytest.mark.parametrize("T,K,E,S,r", [(37, 2, 4, 3, 8), (200, 4, 16, 5, 4), (64, 8, 8, 2, 16), (9, 1, 1, 2, 2), (50, 3, 6, 4, 1)])
+def test_moe_down_small(M, oracle, T, K, E, S, r):
+    """Down projection with the routing-weight combine: ragged widths, tokens without adapter, an
+    empty slot, K from 1 to 8, every padded rank path of the vector kernel."""
+    ranks = [r] * S
+    if S > 2:
+        ranks[1] = 0
+    c = W.moe_down_case(f"down_{T}_{K}_{E}", 5300 + T, T, K, E, 136, 200, S, r, 2.0 * r, ranks=ranks,
+                        std_a=0.05, std_b=0.05)
+    c.token_slot[::7] = -1
+    site = moe_site(M, c)
+    check_moe_down(M, oracle, c, site)
+
+
+def test_c4_moe_down_sampled(M, oracle):
+    c = W.c4_moe_down()
+    site = moe_site(M, c)
+    check_moe_down(M, oracle, c, site, tokens=np.sort(W.rng(79).permutation(c.T)[:160]))
+
+
 def test_c4_moe_packed_sampled(M, oracle):
     c = W.c4_moe_packed("gate")
     site = moe_site(M, c)
