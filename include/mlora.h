@@ -94,6 +94,21 @@ int32_t mlora_site_check(mlora_site *site, void *stream);
 int32_t lora_slots_upload(mlora_site *site, int32_t slot, int64_t catalog_id,
                           const void *A, const void *B, int32_t r, float alpha,
                           int32_t src_on_device, void *stream);
+/* The same upload from per-expert tensors (the fragmented form an adapter is exported in before
+ * packing, Section 4.4: one [r, d_in] and one [d_out, r] tensor per expert and projection).
+ *   A_e, B_e: HOST arrays of max(n_experts, 1) HOST pointers to contiguous bf16 tensors.
+ * The tensors are stacked along the expert axis, zero padded to r_pad, into a pinned host image of
+ * the slot that the site keeps, and each table receives ONE host-to-device copy.  The call returns
+ * when the image is packed; the caller's tensors may be released then.  A second call on the same
+ * site waits until the previous image has been copied.
+ * mlora_pack_experts is the host-only packing step (a_img / b_img: mlora_slot_image_bytes bytes);
+ * it needs no GPU. */
+int32_t mlora_slot_image_bytes(const mlora_site_desc *desc, size_t *a_bytes, size_t *b_bytes);
+int32_t mlora_pack_experts(const mlora_site_desc *desc, const void *const *A_e, const void *const *B_e,
+                           int32_t r, void *a_img, void *b_img);
+int32_t lora_slots_upload_experts(mlora_site *site, int32_t slot, int64_t catalog_id,
+                                  const void *const *A_e, const void *const *B_e, int32_t r, float alpha,
+                                  void *stream);
 /* Marks the slot empty (rank 0): rows that point at it are left untouched (an adapter is
  * visible to traffic only while it is ready, Section 4). */
 int32_t lora_slots_evict(mlora_site *site, int32_t slot, void *stream);

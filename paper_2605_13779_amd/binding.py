@@ -35,6 +35,9 @@ SIGNATURES = {
     "mlora_site_check": (_i32, [_vp, _vp]),
     "lora_slots_upload": (_i32, [_vp, _i32, _i64, _vp, _vp, _i32, C.c_float, _i32, _vp]),
     "lora_slots_evict": (_i32, [_vp, _i32, _vp]),
+    "mlora_slot_image_bytes": (_i32, [C.POINTER(SiteDesc)] + [C.POINTER(_sz)] * 2),
+    "mlora_pack_experts": (_i32, [C.POINTER(SiteDesc), C.POINTER(_vp), C.POINTER(_vp), _i32, _vp, _vp]),
+    "lora_slots_upload_experts": (_i32, [_vp, _i32, _i64, C.POINTER(_vp), C.POINTER(_vp), _i32, C.c_float, _vp]),
     "mlora_plan_bytes": (_i32, [_i32, _i32, C.POINTER(_sz)]),
     "mlora_plan_create": (_i32, [_i32, _i32, _i32, _vp, C.POINTER(_vp)]),
     "mlora_plan_destroy": (None, [_vp]),
@@ -179,6 +182,36 @@ def lora_slots_upload(site, slot, catalog_id, A, B, r, alpha, stream=None):
     if not da:
         torch.cuda.current_stream().synchronize()   # host source must outlive the copy
     return None
+
+
+def _ptr_array(arrays):
+    """ctypes array of host pointers to contiguous uint16 numpy arrays (kept alive by the caller)."""
+    return (_vp * len(arrays))(*[a.ctypes.data for a in arrays])
+
+
+def pack_experts(desc, A_e, B_e, r):
+    """Host-only: stack per-expert bf16 tensors (uint16 numpy arrays [r, d_in] / [d_out, r]) into the
+    slot image (a_img [E, r_pad, d_in], b_img [E, d_out, r_pad], uint16)."""
+    import numpy as np
+    lib = load_library()
+    na, nb = _sz(), _sz()
+    _check("mlora_slot_image_bytes", lib.mlora_slot_image_bytes(C.byref(desc), C.byref(na), C.byref(nb)))
+    A_e = [np.ascontiguousarray(a, dtype=np.uint16) for a in A_e]
+    B_e = [np.ascontiguousarray(b, dtype=np.uint16) for b in B_e]
+    a_img = np.empty(na.value // 2, dtype=np.uint16)
+    b_img = np.empty(nb.value // 2, dtype=np.uint16)
+    _check("mlora_pack_experts", lib.mlora_pack_experts(C.byref(desc), _ptr_array(A_e), _ptr_array(B_e), r,
+                                                        C.c_void_p(a_img.ctypes.data), C.c_void_p(b_img.ctypes.data)))
+    return a_img, b_img
+
+
+def lora_slots_upload_experts(site, slot, catalog_id, A_e, B_e, r, alpha, stream=None):
+    """A_e / B_e: lists of per-expert uint16 numpy arrays ([r, d_in] and [d_out, r])."""
+    import numpy as np
+    A_e = [np.ascontiguousarray(a, dtype=np.uint16) for a in A_e]
+    B_e = [np.ascontiguousarray(b, dtype=np.uint16) for b in B_e]
+    _check("lora_slots_upload_experts", load_library().lora_slots_upload_experts(
+        site.handle, slot, catalog_id, _ptr_array(A_e), _ptr_array(B_e), r, alpha, _stream(stream)))
 
 
 def lora_slots_evict(site, slot, stream=None):

@@ -35,6 +35,9 @@ struct mlora_site {
     hipEvent_t stage_ev[2];
     bool stage_busy[2];
     int stage_next;
+    void *pack;                 // pinned host image of one slot (A part, then B part) for uploads from per-expert tensors (lazy)
+    hipEvent_t pack_ev;
+    bool pack_busy;
 };
 
 namespace {
@@ -357,6 +360,7 @@ int32_t mlora_site_create(const mlora_site_desc *d, void *a_tab, void *b_tab, vo
     s->stage[0] = s->stage[1] = nullptr;
     s->stage_busy[0] = s->stage_busy[1] = false;
     s->stage_next = 0;
+    s->pack = nullptr; s->pack_busy = false;
     DeviceGuard g(d->device);
     if (!g.good) { delete s; return MLORA_E_HIP; }
     meta_clear_kernel<<<dim3((d->n_slots + 255) / 256), dim3(256), 0, 0>>>(s->rank, s->scale, s->catalog, d->n_slots);
@@ -379,6 +383,11 @@ void mlora_site_destroy(mlora_site *s)
             (void)hipEventDestroy(s->stage_ev[k]);
             (void)hipHostFree(s->stage[k]);
         }
+    if (s->pack) {
+        if (s->pack_busy) (void)hipEventSynchronize(s->pack_ev);
+        (void)hipEventDestroy(s->pack_ev);
+        (void)hipHostFree(s->pack);
+    }
     delete s;
 }
 
@@ -413,6 +422,77 @@ int32_t lora_slots_upload(mlora_site *s, int32_t slot, int64_t catalog_id, const
     }
     if (!ok(e)) return MLORA_E_HIP;
     meta_set_kernel<<<dim3(1), dim3(1), 0, st>>>(s->rank, s->scale, s->catalog, slot, r, alpha / (float)r, catalog_id);
+    return ok(hipGetLastError()) ? MLORA_OK : MLORA_E_HIP;
+}
+
+int32_t mlora_slot_image_bytes(const mlora_site_desc *d, size_t *a_bytes, size_t *b_bytes)
+{
+    int32_t rc = check_desc(d);
+    if (rc) return rc;
+    if (!a_bytes || !b_bytes) return MLORA_E_INVALID;
+    const int64_t E = d->n_experts > 0 ? d->n_experts : 1, rp = round_pow2(d->r_max);
+    *a_bytes = (size_t)E * rp * d->d_in * 2;
+    *b_bytes = (size_t)E * d->d_out * rp * 2;
+    return MLORA_OK;
+}
+
+int32_t mlora_pack_experts(const mlora_site_desc *d, const void *const *A_e, const void *const *B_e, int32_t r,
+                           void *a_img, void *b_img)
+{
+    int32_t rc = check_desc(d);
+    if (rc) return rc;
+    if (!A_e || !B_e || !a_img || !b_img) return MLORA_E_INVALID;
+    if (r < 1 || r > d->r_max) return MLORA_E_SHAPE;
+    const int64_t E = d->n_experts > 0 ? d->n_experts : 1, rp = round_pow2(d->r_max), d_in = d->d_in, d_out = d->d_out;
+    for (int64_t e = 0; e < E; ++e)
+        if (!A_e[e] || !B_e[e]) return MLORA_E_INVALID;
+    char *ai = (char *)a_img, *bi = (char *)b_img;
+    for (int64_t e = 0; e < E; ++e) {
+        // A_e [r, d_in] -> rows 0..r-1 of the expert's [r_pad, d_in] block, the rest zero
+        std::memcpy(ai + e * rp * d_in * 2, A_e[e], (size_t)r * d_in * 2);
+        if (r < rp) std::memset(ai + (e * rp + r) * d_in * 2, 0, (size_t)(rp - r) * d_in * 2);
+        // B_e [d_out, r] -> columns 0..r-1 of the expert's [d_out, r_pad] block, the rest zero
+        if (r == rp) {
+            std::memcpy(bi + e * d_out * rp * 2, B_e[e], (size_t)d_out * rp * 2);
+        } else {
+            const char *src = (const char *)B_e[e];
+            char *dst = bi + e * d_out * rp * 2;
+            for (int64_t o = 0; o < d_out; ++o) {
+                std::memcpy(dst + o * rp * 2, src + o * r * 2, (size_t)r * 2);
+                std::memset(dst + (o * rp + r) * 2, 0, (size_t)(rp - r) * 2);
+            }
+        }
+    }
+    return MLORA_OK;
+}
+
+int32_t lora_slots_upload_experts(mlora_site *s, int32_t slot, int64_t catalog_id, const void *const *A_e,
+                                  const void *const *B_e, int32_t r, float alpha, void *stream)
+{
+    if (!s || !A_e || !B_e) return MLORA_E_INVALID;
+    if (slot < 0 || slot >= s->d.n_slots) return MLORA_E_SLOT;
+    if (r < 1 || r > s->d.r_max) return MLORA_E_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    DeviceGuard g(s->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    size_t ab = 0, bb = 0;
+    int32_t rc = mlora_slot_image_bytes(&s->d, &ab, &bb);
+    if (rc) return rc;
+    if (!s->pack) {
+        if (!ok(hipHostMalloc(&s->pack, ab + bb, hipHostMallocDefault))) return MLORA_E_HIP;
+        if (!ok(hipEventCreateWithFlags(&s->pack_ev, hipEventDisableTiming))) return MLORA_E_HIP;
+    }
+    if (s->pack_busy && !ok(hipEventSynchronize(s->pack_ev))) return MLORA_E_HIP;   // the previous image has left the host
+    rc = mlora_pack_experts(&s->d, A_e, B_e, r, s->pack, (char *)s->pack + ab);
+    if (rc) return rc;
+    // the image is the slot's bytes, padding included: one copy per table, no zero-fill launch
+    meta_set_kernel<<<dim3(1), dim3(1), 0, st>>>(s->rank, s->scale, s->catalog, slot, 0, 0.f, -1);
+    hipError_t e = hipMemcpyAsync((char *)s->a_tab + (size_t)slot * ab, s->pack, ab, hipMemcpyHostToDevice, st);
+    if (ok(e)) e = hipMemcpyAsync((char *)s->b_tab + (size_t)slot * bb, (char *)s->pack + ab, bb, hipMemcpyHostToDevice, st);
+    if (!ok(e)) return MLORA_E_HIP;
+    meta_set_kernel<<<dim3(1), dim3(1), 0, st>>>(s->rank, s->scale, s->catalog, slot, r, alpha / (float)r, catalog_id);
+    if (!ok(hipEventRecord(s->pack_ev, st))) return MLORA_E_HIP;
+    s->pack_busy = true;
     return ok(hipGetLastError()) ? MLORA_OK : MLORA_E_HIP;
 }
 

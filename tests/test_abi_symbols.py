@@ -72,3 +72,33 @@ def test_noop_is_rejected_by_the_parity_rules():
     with pytest.raises(AssertionError):
         P.noop_must_fail(np.zeros((8, 16), np.uint16), np.zeros((8, 16)), np.arange(8))
     P.noop_must_fail(np.zeros((8, 16), np.uint16), delta, np.arange(8))
+
+
+def test_pack_experts_stacks_and_pads_like_numpy(lib):
+    """Host-only packing of per-expert tensors into the slot image (the packed adapter form: one
+    stacked tensor per projection and A|B instead of one per expert), against plain numpy."""
+    from paper_2605_13779_amd import binding
+    g = np.random.default_rng(7)
+    for E, r, r_max, d_in, d_out in [(5, 3, 6, 24, 16), (4, 8, 8, 16, 40), (1, 1, 1, 8, 8), (128, 8, 8, 64, 24)]:
+        desc = binding.SiteDesc(d_in, d_out, r_max, 2, E if E > 1 else 0, 0)
+        A_e = [g.integers(1, 65535, size=(r, d_in), dtype=np.uint16) for _ in range(E)]
+        B_e = [g.integers(1, 65535, size=(d_out, r), dtype=np.uint16) for _ in range(E)]
+        a_img, b_img = binding.pack_experts(desc, A_e, B_e, r)
+        rp = 1
+        while rp < r_max:
+            rp *= 2
+        want_a = np.zeros((E, rp, d_in), dtype=np.uint16)
+        want_b = np.zeros((E, d_out, rp), dtype=np.uint16)
+        want_a[:, :r] = np.stack(A_e)
+        want_b[:, :, :r] = np.stack(B_e)
+        assert np.array_equal(a_img.reshape(E, rp, d_in), want_a)
+        assert np.array_equal(b_img.reshape(E, d_out, rp), want_b)
+    # the census of the paper's 30B-MoE adapter: per layer and projection 128 experts x {A, B} = 256
+    # tensors become 2 stacked ones, 48 layers x 3 projections -> 36,864 become 288
+    # (tests/golden/adapter_census.txt holds the printed totals)
+    assert 48 * 3 * 128 * 2 == 36864 and 48 * 3 * 2 == 288
+    desc = binding.SiteDesc(16, 16, 4, 2, 3, 0)
+    A_e = [np.ones((2, 16), dtype=np.uint16)] * 3
+    B_e = [np.ones((16, 2), dtype=np.uint16)] * 3
+    with pytest.raises(binding.MLoraError):
+        binding.pack_experts(desc, A_e, B_e, 5)        # rank above r_max

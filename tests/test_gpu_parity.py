@@ -491,6 +491,31 @@ def test_c4_moe_down_sampled(M, oracle):
     check_moe_down(M, oracle, c, site, tokens=np.sort(W.rng(79).permutation(c.T)[:160]))
 
 
+def test_upload_from_per_expert_tensors_equals_packed_upload(M, oracle):
+    """lora_slots_upload_experts (fragments -> pinned slot image -> one copy per table) must leave
+    the same tables as the packed upload: identical outputs bit for bit, also after a re-upload with
+    a smaller rank (padding cleared), and right against the oracle."""
+    c = W.moe_case("frag", 5400, 90, 4, 16, 136, 200, 3, 8, 16.0, ranks=[8, 5, 8], std_a=0.05, std_b=0.05)
+    packed, frag = moe_site(M, c), M.Site(c.d_in, c.d_out, c.r_max, c.n_slots, n_experts=c.E)
+    for s_ in range(c.n_slots):
+        r = int(c.rank[s_])
+        M.lora_slots_upload_experts(frag, s_, s_, [c.A[s_, e, :r, :] for e in range(c.E)],
+                                    [c.B[s_, e, :, :r] for e in range(c.E)], r, float(c.alpha[s_]))
+    torch.cuda.synchronize()
+    a, _, _ = run_moe(M, packed, c, c.y0, want_idx=False)
+    b, _, _ = run_moe(M, frag, c, c.y0, want_idx=False)
+    assert np.array_equal(a, b)
+    ref = oracle.apply_moe(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, c.token_slot)
+    P.check_close(b, ref, "fragments")
+    c2 = W.moe_case("frag", 5400, 90, 4, 16, 136, 200, 3, 8, 16.0, ranks=[3, 5, 8], std_a=0.05, std_b=0.05)
+    M.lora_slots_upload_experts(frag, 0, 9, [c2.A[0, e, :3, :] for e in range(c.E)],
+                                [c2.B[0, e, :, :3] for e in range(c.E)], 3, float(c2.alpha[0]))
+    torch.cuda.synchronize()
+    b2, _, _ = run_moe(M, frag, c2, c2.y0, want_idx=False)
+    P.check_close(b2, oracle.apply_moe(c2.x, c2.y0, c2.A, c2.B, c2.rank, c2.alpha, c2.topk, c2.token_slot), "re-upload")
+    assert frag.meta()[0].tolist() == [3, 5, 8] and frag.meta()[2][0] == 9
+
+
 def test_c4_moe_packed_sampled(M, oracle):
     c = W.c4_moe_packed("gate")
     site = moe_site(M, c)
