@@ -200,6 +200,44 @@ int32_t moe_lora_apply_packed(mlora_site *site, const void *x, int64_t ldx, void
                               int32_t T, int32_t K,
                               int32_t *out_sorted_pair, int32_t *out_group_off, void *stream);
 
+/* ---- which adapter sits in which slot (host-side state only; moves no bytes) ------------------ */
+
+/* The GPU-batch tier of the paper's serving section (Section 4: cache tiers, cold loading as
+ * scheduled service work, registered / prewarming / ready): catalog id -> slot, least-recently-used
+ * eviction among ready slots that are not pinned, one shared load per missing adapter, at most
+ * max_in_flight load jobs with at most max_queue waiting behind them, retryable rejection beyond. */
+typedef struct mlora_resident mlora_resident;
+
+enum {                          /* results of mlora_resident_request (>= 0; errors are negative)        */
+    MLORA_R_READY    = 0,       /* *slot holds the adapter; it becomes the most recently used             */
+    MLORA_R_LOAD     = 1,       /* a load job starts: upload into *slot, then mlora_resident_complete     */
+    MLORA_R_PENDING  = 2,       /* a load of the same adapter is already running or queued: wait for it   */
+    MLORA_R_QUEUED   = 3,       /* waits for a load job; mlora_resident_complete of another job starts it */
+    MLORA_R_REJECTED = 4        /* jobs and queue are full: nothing changed, retry later                  */
+};
+enum {                          /* indices into mlora_resident_stats                                      */
+    MLORA_STAT_HITS = 0, MLORA_STAT_LOADS = 1, MLORA_STAT_SHARED = 2, MLORA_STAT_REJECTS = 3,
+    MLORA_STAT_EVICTIONS = 4, MLORA_RESIDENT_STATS = 5
+};
+
+int32_t mlora_resident_create(int32_t n_slots, int32_t max_in_flight, int32_t max_queue, mlora_resident **out);
+void    mlora_resident_destroy(mlora_resident *r);
+/* Makes catalog_id (>= 0) known; it is not visible to mlora_resident_lookup before a load completes. */
+int32_t mlora_resident_register(mlora_resident *r, int64_t catalog_id);
+/* Slot of a READY adapter, else -1 (registered, queued and prewarming adapters are not exposed). */
+int32_t mlora_resident_lookup(mlora_resident *r, int64_t catalog_id);
+/* See the MLORA_R_* values.  *evicted_id = the adapter that lost *slot to this load, or -1.
+ * MLORA_E_INVALID if catalog_id was never registered. */
+int32_t mlora_resident_request(mlora_resident *r, int64_t catalog_id, int32_t *slot, int64_t *evicted_id);
+/* Ends the load job of catalog_id: ok != 0 -> READY, ok == 0 -> back to registered, its slot free.
+ * If a queued job can start now, *next_id / *next_slot name it (the caller uploads it next) and
+ * *evicted_id the adapter it displaced; otherwise they are -1. */
+int32_t mlora_resident_complete(mlora_resident *r, int64_t catalog_id, int32_t ok, int64_t *next_id,
+                                int32_t *next_slot, int64_t *evicted_id);
+/* Slots used by the batch that is being built or run are pinned: they are never evicted. */
+int32_t mlora_resident_pin(mlora_resident *r, int32_t slot, int32_t pinned);
+int32_t mlora_resident_stats(mlora_resident *r, int64_t *out /* [MLORA_RESIDENT_STATS] */);
+
 /* Tuning knobs read by the launch heuristics (0 = automatic).  Host-side, process-wide. */
 int32_t mlora_set_tuning(const char *name, int32_t value);
 

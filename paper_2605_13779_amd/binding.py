@@ -48,6 +48,14 @@ SIGNATURES = {
     "moe_lora_apply_planned": (_i32, [_vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "moe_down_workspace_bytes": (_i32, [_i32, _i32, _i32, C.POINTER(_sz)]),
     "moe_lora_apply_down": (_i32, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _i64, _vp]),
+    "mlora_resident_create": (_i32, [_i32, _i32, _i32, C.POINTER(_vp)]),
+    "mlora_resident_destroy": (None, [_vp]),
+    "mlora_resident_register": (_i32, [_vp, _i64]),
+    "mlora_resident_lookup": (_i32, [_vp, _i64]),
+    "mlora_resident_request": (_i32, [_vp, _i64, C.POINTER(_i32), C.POINTER(_i64)]),
+    "mlora_resident_complete": (_i32, [_vp, _i64, _i32, C.POINTER(_i64), C.POINTER(_i32), C.POINTER(_i64)]),
+    "mlora_resident_pin": (_i32, [_vp, _i32, _i32]),
+    "mlora_resident_stats": (_i32, [_vp, C.POINTER(_i64)]),
     "lora_apply_decode": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _i32, _vp]),
     "lora_apply_segmented": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _vp, _i32, _i32, _vp]),
     "moe_lora_apply_packed": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _vp, _i32, _i32, _vp, _vp, _vp]),
@@ -307,3 +315,54 @@ def moe_lora_apply_down(site, plan, x, pair_w, token_slot, workspace, y, stream=
     _check("moe_lora_apply_down", load_library().moe_lora_apply_down(
         site.handle, plan.handle, px, ldx, _dev_ptr(pair_w, torch.float32), _dev_ptr(token_slot, torch.int32),
         C.c_void_p(workspace.data_ptr()), py, ldy, _stream(stream)))
+
+
+class Resident:
+    """Host-side map catalog id -> GPU slot with LRU eviction and bounded, deduplicated load jobs."""
+    READY, LOAD, PENDING, QUEUED, REJECTED = range(5)
+    STATS = ("hits", "loads", "shared", "rejects", "evictions")
+
+    def __init__(self, n_slots, max_in_flight=1, max_queue=1):
+        h = _vp()
+        _check("mlora_resident_create", load_library().mlora_resident_create(n_slots, max_in_flight, max_queue, C.byref(h)))
+        self.handle = h
+
+    def close(self):
+        if self.handle:
+            load_library().mlora_resident_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def register(self, catalog_id):
+        _check("mlora_resident_register", load_library().mlora_resident_register(self.handle, catalog_id))
+
+    def lookup(self, catalog_id):
+        return load_library().mlora_resident_lookup(self.handle, catalog_id)
+
+    def request(self, catalog_id):
+        """-> (result, slot, evicted_id)"""
+        slot, ev = _i32(-1), _i64(-1)
+        rc = load_library().mlora_resident_request(self.handle, catalog_id, C.byref(slot), C.byref(ev))
+        if rc < 0:
+            _check("mlora_resident_request", rc)
+        return rc, slot.value, ev.value
+
+    def complete(self, catalog_id, ok=True):
+        """-> (next_id, next_slot, evicted_id) of the queued job that starts now, or (-1, -1, -1)"""
+        nid, ns, ev = _i64(-1), _i32(-1), _i64(-1)
+        _check("mlora_resident_complete", load_library().mlora_resident_complete(
+            self.handle, catalog_id, 1 if ok else 0, C.byref(nid), C.byref(ns), C.byref(ev)))
+        return nid.value, ns.value, ev.value
+
+    def pin(self, slot, pinned=True):
+        _check("mlora_resident_pin", load_library().mlora_resident_pin(self.handle, slot, 1 if pinned else 0))
+
+    def stats(self):
+        out = (_i64 * len(self.STATS))()
+        _check("mlora_resident_stats", load_library().mlora_resident_stats(self.handle, out))
+        return dict(zip(self.STATS, list(out)))

@@ -525,6 +525,51 @@ def test_c4_moe_packed_sampled(M, oracle):
 
 # ------------------------------------------------------------------ ABI errors on the device box
 
+def test_catalog_traffic_through_the_residency_manager(M, oracle):
+    """Tokens carry catalog ids; the host-side manager maps them to slots (loads on a miss, evicts
+    the least recently used adapter), the site tables follow, and every step's result matches the
+    oracle applied with the adapters that the requests name."""
+    n_cat, n_slots, T = 7, 3, 40
+    c = W.dense_case("catalog", 5500, T, 136, 200, n_cat, 8, 16.0, ranks=[8, 5, 8, 1, 8, 3, 8], std_a=0.05, std_b=0.05)
+    cat_ids = [1000 * (k + 1) + 7 for k in range(n_cat)]            # catalog id of adapter k
+    site = M.Site(c.d_in, c.d_out, c.r_max, n_slots)
+    res = M.Resident(n_slots, max_in_flight=1, max_queue=0)
+    for cid in cat_ids:
+        res.register(cid)
+    g = W.rng(5501)
+    for step in range(6):
+        live = g.choice(n_cat, size=n_slots, replace=False)         # a batch names at most n_slots adapters
+        want = g.choice(live, size=T).astype(np.int32)              # adapter index per token
+        want[::9] = -1
+        pinned = []
+        for k in sorted(set(want[want >= 0].tolist())):
+            r, slot, _ = res.request(cat_ids[k])
+            if r == res.LOAD:
+                rk = int(c.rank[k])
+                M.lora_slots_upload(site, slot, cat_ids[k], np.ascontiguousarray(c.A[k][:rk]),
+                                    np.ascontiguousarray(c.B[k][:, :rk]), rk, float(c.alpha[k]))
+                assert res.complete(cat_ids[k])[0] == -1
+            else:
+                assert r == res.READY
+            res.pin(slot)
+            pinned.append(slot)
+        token_slot = np.array([res.lookup(cat_ids[k]) if k >= 0 else -1 for k in want], dtype=np.int32)
+        assert (token_slot[want >= 0] >= 0).all()
+        x, y = P.dev_bf16(c.x), P.dev_bf16(c.y0)
+        M.lora_apply_decode(site, x, y, torch.from_numpy(token_slot).cuda())
+        torch.cuda.synchronize()
+        ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, want)    # by adapter, not by slot
+        P.check_close(P.host_bits(y), ref, f"step {step}")
+        P.check_untouched(P.host_bits(y), c.y0, want < 0, f"step {step}")
+        cat = site.meta()[2]
+        for k in set(want[want >= 0].tolist()):
+            assert cat[res.lookup(cat_ids[k])] == cat_ids[k]
+        for slot in pinned:
+            res.pin(slot, False)
+    st = res.stats()
+    assert st["loads"] >= n_slots and st["evictions"] >= 1 and st["rejects"] == 0
+
+
 def test_abi_error_codes(M):
     with pytest.raises(M.MLoraError) as e:
         M.Site(100, 64, 8, 2)                       # d_in not a multiple of 8
