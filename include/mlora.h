@@ -113,6 +113,14 @@ int32_t lora_slots_upload_experts(mlora_site *site, int32_t slot, int64_t catalo
  * visible to traffic only while it is ready, Section 4). */
 int32_t lora_slots_evict(mlora_site *site, int32_t slot, void *stream);
 
+/* Device-side catalog id -> slot: token_slot[t] = the lowest slot that is ready (rank > 0) and whose
+ * catalog_id equals token_catalog_id[t], else -1 (ids < 0 map to -1).  Both arrays are DEVICE memory
+ * (int64[T] in, int32[T] out).  Lets a batch carry the adapter names of the catalog (Section 4:
+ * the actor maps a revision to a local adapter id) and resolve them without a host round trip; the
+ * result feeds lora_plan_decode / lora_apply_decode / moe_plan_route. */
+int32_t lora_slot_lookup(mlora_site *site, const int64_t *token_catalog_id, int32_t T, int32_t *token_slot,
+                         void *stream);
+
 /* ---- explicit plans: group a batch once, reuse it for every site of every layer ------------ */
 
 /* Device bytes for a plan that can hold up to max_items rows (dense: tokens; MoE: token-expert

@@ -35,6 +35,7 @@ SIGNATURES = {
     "mlora_site_check": (_i32, [_vp, _vp]),
     "lora_slots_upload": (_i32, [_vp, _i32, _i64, _vp, _vp, _i32, C.c_float, _i32, _vp]),
     "lora_slots_evict": (_i32, [_vp, _i32, _vp]),
+    "lora_slot_lookup": (_i32, [_vp, _vp, _i32, _vp, _vp]),
     "mlora_slot_image_bytes": (_i32, [C.POINTER(SiteDesc)] + [C.POINTER(_sz)] * 2),
     "mlora_pack_experts": (_i32, [C.POINTER(SiteDesc), C.POINTER(_vp), C.POINTER(_vp), _i32, _vp, _vp]),
     "lora_slots_upload_experts": (_i32, [_vp, _i32, _i64, C.POINTER(_vp), C.POINTER(_vp), _i32, C.c_float, _vp]),
@@ -220,6 +221,13 @@ def lora_slots_upload_experts(site, slot, catalog_id, A_e, B_e, r, alpha, stream
     B_e = [np.ascontiguousarray(b, dtype=np.uint16) for b in B_e]
     _check("lora_slots_upload_experts", load_library().lora_slots_upload_experts(
         site.handle, slot, catalog_id, _ptr_array(A_e), _ptr_array(B_e), r, alpha, _stream(stream)))
+
+
+def lora_slot_lookup(site, token_catalog_id, token_slot_out, stream=None):
+    """token_catalog_id: int64 device tensor [T]; token_slot_out: int32 device tensor [T]."""
+    T = token_catalog_id.shape[0]
+    _check("lora_slot_lookup", load_library().lora_slot_lookup(
+        site.handle, _dev_ptr(token_catalog_id, torch.int64), T, _dev_ptr(token_slot_out, torch.int32), _stream(stream)))
 
 
 def lora_slots_evict(site, slot, stream=None):

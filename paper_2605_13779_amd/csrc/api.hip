@@ -87,6 +87,28 @@ __global__ void meta_set_kernel(int32_t *rank, float *scale, int64_t *catalog, i
     rank[slot] = r; scale[slot] = s; catalog[slot] = id;
 }
 
+// token -> slot through the catalog ids the slots hold: the lowest ready slot whose id matches, else -1.
+// One workgroup per 256 tokens; the id table (<= a few KB) is staged in LDS in pieces.
+__global__ __launch_bounds__(256)
+void slot_lookup_kernel(const int64_t *token_id, int T, const int64_t *catalog, const int32_t *rank, int n_slots,
+                        int32_t *token_slot)
+{
+    __shared__ int64_t ids[1024];
+    const int t = (int)(blockIdx.x * 256 + threadIdx.x);
+    const int64_t want = t < T ? token_id[t] : -1;
+    int found = -1;
+    for (int base = 0; base < n_slots; base += 1024) {
+        const int n = min(1024, n_slots - base);
+        __syncthreads();
+        for (int k = (int)threadIdx.x; k < n; k += 256) ids[k] = rank[base + k] > 0 ? catalog[base + k] : -1;
+        __syncthreads();
+        if (want >= 0 && found < 0)
+            for (int k = 0; k < n; ++k)
+                if (ids[k] == want) { found = base + k; break; }
+    }
+    if (t < T) token_slot[t] = found;
+}
+
 __global__ void meta_clear_kernel(int32_t *rank, float *scale, int64_t *catalog, int n)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -510,6 +532,18 @@ int32_t mlora_site_check(mlora_site *s, void *stream)
         return MLORA_E_HIP;
     }
     return MLORA_OK;
+}
+
+int32_t lora_slot_lookup(mlora_site *s, const int64_t *token_catalog_id, int32_t T, int32_t *token_slot, void *stream)
+{
+    if (!s || T < 0) return MLORA_E_INVALID;
+    if (T == 0) return MLORA_OK;
+    if (!token_catalog_id || !token_slot) return MLORA_E_INVALID;
+    DeviceGuard g(s->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    slot_lookup_kernel<<<dim3((unsigned)((T + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
+        token_catalog_id, T, s->catalog, s->rank, s->d.n_slots, token_slot);
+    return ok(hipGetLastError()) ? MLORA_OK : MLORA_E_HIP;
 }
 
 int32_t lora_slots_evict(mlora_site *s, int32_t slot, void *stream)

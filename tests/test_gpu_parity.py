@@ -570,6 +570,31 @@ def test_catalog_traffic_through_the_residency_manager(M, oracle):
     assert st["loads"] >= n_slots and st["evictions"] >= 1 and st["rejects"] == 0
 
 
+def test_device_side_catalog_id_lookup(M, oracle):
+    """Tokens name adapters by catalog id; the device maps them to slots (bit-exact against the host
+    mapping: ready slots only, unknown and negative ids -> -1) and the decode built on it is right."""
+    c = W.c3_rank1_catalog()                           # 1024 slots with distinct ids from [0, 10^6)
+    site = dense_site(M, c)
+    M.lora_slots_evict(site, 5)
+    ids = c.catalog_id.copy()
+    tok = ids[c.token_slot].astype(np.int64)
+    tok[::11] = -1
+    tok[1::13] = 999_999_999                           # not in the catalog
+    tok[2] = ids[5]                                    # evicted: not ready
+    host = {int(v): k for k, v in enumerate(ids) if k != 5}
+    want = np.array([host.get(int(v), -1) if v >= 0 else -1 for v in tok], dtype=np.int32)
+    out = torch.full((len(tok),), -7, dtype=torch.int32, device="cuda")
+    M.lora_slot_lookup(site, torch.from_numpy(tok).cuda(), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want)
+    x, y = P.dev_bf16(c.x), P.dev_bf16(c.y0)
+    M.lora_apply_decode(site, x, y, out)
+    torch.cuda.synchronize()
+    ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, want)
+    P.check_close(P.host_bits(y), ref, "by catalog id")
+    P.check_untouched(P.host_bits(y), c.y0, want < 0, "by catalog id")
+
+
 def test_abi_error_codes(M):
     with pytest.raises(M.MLoraError) as e:
         M.Site(100, 64, 8, 2)                       # d_in not a multiple of 8
