@@ -173,7 +173,8 @@ def bench_c3(M, W, steps, warmup, n_sets=24):
             "bytes_per_step": dense_bytes(c)}
 
 
-def bench_c4(M, W, steps, warmup, n_sets=2):
+def bench_c4(M, W, steps, warmup, n_sets=2, fused=True):
+    """Gate and up of the c4 layer: the route plan, then both projections (one launch when `fused`)."""
     import torch
     cg, cu = W.c4_moe_packed("gate"), W.c4_moe_packed("up")
     topk, ts = torch.from_numpy(cg.topk).cuda(), torch.from_numpy(cg.token_slot).cuda()
@@ -191,14 +192,17 @@ def bench_c4(M, W, steps, warmup, n_sets=2):
         for plan, x, pair in sets:
             if with_plan:
                 M.moe_plan_route(plan, topk, ts, cg.n_slots, cg.E)
-            for site, y in pair:
-                M.moe_lora_apply_planned(site, plan, x, y)
+            if fused:
+                M.moe_lora_apply_multi([p[0] for p in pair], plan, [x, x], [p[1] for p in pair])
+            else:
+                for site, y in pair:
+                    M.moe_lora_apply_planned(site, plan, x, y)
 
     g_full, g_apply = graph_of(sweep), graph_of(lambda: sweep(False))
     reps, wreps = max(1, steps // n_sets), max(1, warmup // n_sets)
     ms_full = time_region(g_full.replay, reps, wreps) / n_sets
     ms_apply = time_region(g_apply.replay, reps, wreps) / n_sets
-    return {"ms_per_step": ms_full, "ms_apply_only": ms_apply, "tokens": cg.T, "launches_per_step": 2,
+    return {"ms_per_step": ms_full, "ms_apply_only": ms_apply, "tokens": cg.T, "launches_per_step": 1 if fused else 2,
             "bytes_per_step": 2 * moe_bytes(cg)}
 
 

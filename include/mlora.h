@@ -166,6 +166,15 @@ int32_t moe_plan_route(mlora_plan *plan, const int32_t *topk_ids, const int32_t 
  * MoE site, using a plan from moe_plan_route.  x: [T, d_in]. */
 int32_t moe_lora_apply_planned(mlora_site *site, const mlora_plan *plan,
                                const void *x, int64_t ldx, void *y, int64_t ldy, void *stream);
+/* Several packed MoE sites that take the same route plan, applied with as few launches as possible:
+ * the gate and up projections of an expert layer read the same x with the same routing (per-expert
+ * LoRA tensors on gate, up and down, Section 3.4) and are independent of each other, so sites of
+ * rank 8 or 16 with the same rank share one launch; others get a launch of their own.  sites, xs,
+ * ldxs, ys, ldys are HOST arrays of length n_sites; each (site, x, y) triple follows the rules of
+ * moe_lora_apply_planned, and the result is bit-identical to n_sites such calls. */
+int32_t moe_lora_apply_multi(mlora_site *const *sites, int32_t n_sites, const mlora_plan *plan,
+                             const void *const *xs, const int64_t *ldxs, void *const *ys,
+                             const int64_t *ldys, void *stream);
 
 /* MoE down projection with the routing-weight combine (per-expert LoRA tensors on the expert down
  * projection, Sections 3.4 and 4.4): pair p = t*K + k has its own input row x[p, :] (the expert's

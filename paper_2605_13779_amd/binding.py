@@ -47,6 +47,7 @@ SIGNATURES = {
     "lora_apply_decode_multi": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_plan_route": (_i32, [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]),
     "moe_lora_apply_planned": (_i32, [_vp, _vp, _vp, _i64, _vp, _i64, _vp]),
+    "moe_lora_apply_multi": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_down_workspace_bytes": (_i32, [_i32, _i32, _i32, C.POINTER(_sz)]),
     "moe_lora_apply_down": (_i32, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _i64, _vp]),
     "mlora_resident_create": (_i32, [_i32, _i32, _i32, C.POINTER(_vp)]),
@@ -278,7 +279,7 @@ def lora_apply_decode_planned(site, plan, x, y, stream=None):
         site.handle, plan.handle, px, ldx, py, ldy, _stream(stream)))
 
 
-def lora_apply_decode_multi(sites, plan, xs, ys, stream=None):
+def _apply_multi(name, sites, plan, xs, ys, stream):
     n = len(sites)
     assert len(xs) == n and len(ys) == n
     rows = [(_rows(x), _rows(y)) for x, y in zip(xs, ys)]
@@ -287,8 +288,15 @@ def lora_apply_decode_multi(sites, plan, xs, ys, stream=None):
     lx = (_i64 * n)(*[r[0][1] for r in rows])
     py = (_vp * n)(*[r[1][0] for r in rows])
     ly = (_i64 * n)(*[r[1][1] for r in rows])
-    _check("lora_apply_decode_multi", load_library().lora_apply_decode_multi(
-        hs, n, plan.handle, px, lx, py, ly, _stream(stream)))
+    _check(name, getattr(load_library(), name)(hs, n, plan.handle, px, lx, py, ly, _stream(stream)))
+
+
+def lora_apply_decode_multi(sites, plan, xs, ys, stream=None):
+    _apply_multi("lora_apply_decode_multi", sites, plan, xs, ys, stream)
+
+
+def moe_lora_apply_multi(sites, plan, xs, ys, stream=None):
+    _apply_multi("moe_lora_apply_multi", sites, plan, xs, ys, stream)
 
 
 def moe_plan_route(plan, topk_ids, token_slot, n_slots, n_experts, ready_from=None,

@@ -605,6 +605,35 @@ int32_t lora_apply_decode_planned(mlora_site *s, const mlora_plan *plan, const v
     return apply_planned_impl(s, plan, x, ldx, y, ldy, (hipStream_t)stream);
 }
 
+// Neighbouring sites that can share a launch are grouped; the others get a launch of their own.
+static int32_t apply_multi_impl(mlora_site *const *sites, int32_t n_sites, const mlora_plan *plan,
+                                const void *const *xs, const int64_t *ldxs, void *const *ys, const int64_t *ldys,
+                                hipStream_t st)
+{
+    int32_t k = 0;
+    while (k < n_sites) {
+        RowsArgs grp[kMaxMulti];
+        int32_t n = 0, nw = 0;
+        while (k + n < n_sites && n < kMaxMulti) {
+            RowsArgs a = rows_args(sites[k + n], xs[k + n], ldxs[k + n], ys[k + n], ldys[k + n]);
+            a.chunks = plan->pv.chunks; a.top_k = plan->top_k; a.grid_chunks = plan->grid_chunks;
+            const int w = rows_group_waves(a);
+            if (w == 0 || (n > 0 && (a.r_pad != grp[0].r_pad || w != nw))) break;
+            nw = w;
+            grp[n++] = a;
+        }
+        if (n >= 2) {
+            if (!ok(launch_rows_multi(grp, n, st))) return MLORA_E_HIP;
+            k += n;
+        } else {
+            int32_t rc = apply_planned_impl(sites[k], plan, xs[k], ldxs[k], ys[k], ldys[k], st);
+            if (rc) return rc;
+            k += 1;
+        }
+    }
+    return MLORA_OK;
+}
+
 int32_t lora_apply_decode_multi(mlora_site *const *sites, int32_t n_sites, const mlora_plan *plan,
                                 const void *const *xs, const int64_t *ldxs, void *const *ys, const int64_t *ldys,
                                 void *stream)
@@ -622,28 +651,7 @@ int32_t lora_apply_decode_multi(mlora_site *const *sites, int32_t n_sites, const
     if (plan->items == 0) return MLORA_OK;
     DeviceGuard g(sites[0]->d.device);
     if (!g.good) return MLORA_E_HIP;
-    hipStream_t st = (hipStream_t)stream;
-    // group neighbouring sites that can share a launch; the others get a launch of their own
-    int32_t k = 0;
-    while (k < n_sites) {
-        RowsArgs grp[kMaxMulti];
-        int32_t n = 0;
-        while (k + n < n_sites && n < kMaxMulti) {
-            RowsArgs a = rows_args(sites[k + n], xs[k + n], ldxs[k + n], ys[k + n], ldys[k + n]);
-            a.chunks = plan->pv.chunks; a.top_k = plan->top_k; a.grid_chunks = plan->grid_chunks;
-            if (!rows_can_group(a) || (n > 0 && a.r_pad != grp[0].r_pad)) break;
-            grp[n++] = a;
-        }
-        if (n >= 2) {
-            if (!ok(launch_rows_multi(grp, n, st))) return MLORA_E_HIP;
-            k += n;
-        } else {
-            int32_t rc = apply_planned_impl(sites[k], plan, xs[k], ldxs[k], ys[k], ldys[k], st);
-            if (rc) return rc;
-            k += 1;
-        }
-    }
-    return MLORA_OK;
+    return apply_multi_impl(sites, n_sites, plan, xs, ldxs, ys, ldys, (hipStream_t)stream);
 }
 
 int32_t moe_plan_route(mlora_plan *plan, const int32_t *topk_ids, const int32_t *token_slot, int32_t T, int32_t K,
@@ -677,6 +685,26 @@ int32_t moe_lora_apply_planned(mlora_site *s, const mlora_plan *plan, const void
     DeviceGuard g(s->d.device);
     if (!g.good) return MLORA_E_HIP;
     return apply_planned_impl(s, plan, x, ldx, y, ldy, (hipStream_t)stream);
+}
+
+int32_t moe_lora_apply_multi(mlora_site *const *sites, int32_t n_sites, const mlora_plan *plan,
+                             const void *const *xs, const int64_t *ldxs, void *const *ys, const int64_t *ldys,
+                             void *stream)
+{
+    if (!sites || !plan || !xs || !ldxs || !ys || !ldys || n_sites < 1) return MLORA_E_INVALID;
+    if (!plan->moe) return MLORA_E_UNSUPPORTED;
+    for (int32_t k = 0; k < n_sites; ++k) {
+        if (!sites[k]) return MLORA_E_INVALID;
+        if (sites[k]->d.n_experts <= 0) return MLORA_E_UNSUPPORTED;
+        if (sites[k]->d.device != sites[0]->d.device) return MLORA_E_INVALID;
+        if (plan->items > 0 && (plan->n_experts != sites[k]->d.n_experts || plan->n_slots > sites[k]->d.n_slots)) return MLORA_E_SHAPE;
+        int32_t rc = check_xy(sites[k], xs[k], ldxs[k], ys[k], ldys[k]);
+        if (rc) return rc;
+    }
+    if (plan->items == 0) return MLORA_OK;
+    DeviceGuard g(sites[0]->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    return apply_multi_impl(sites, n_sites, plan, xs, ldxs, ys, ldys, (hipStream_t)stream);
 }
 
 int32_t moe_down_workspace_bytes(int32_t T, int32_t K, int32_t d_out, size_t *bytes)

@@ -78,7 +78,7 @@ struct RowsArgs {
 };
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st);
 constexpr int kMaxMulti = 4;     // sites per grouped launch
-bool rows_can_group(const RowsArgs &a);
+int rows_group_waves(const RowsArgs &a);
 hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st);
 hipError_t launch_moe_combine(uint16_t *y, int64_t ldy, const float *parts, int64_t ldo, const int32_t *token_slot,
                               const int32_t *rank, int32_t n_slots, int32_t T, int32_t K, int32_t d_out, hipStream_t st);

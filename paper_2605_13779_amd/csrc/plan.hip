@@ -204,7 +204,7 @@ void plan_hist_kernel(PlanView pv, const int32_t *__restrict__ topk, const int32
 __global__ __launch_bounds__(1024)
 void plan_scan_kernel(PlanView pv, int NK, int32_t *__restrict__ out_group_off)
 {
-    __shared__ int32_t s_items[1024], s_chunks[1024];
+    __shared__ int32_t wave_tot[16];
     const int tid = threadIdx.x;
     const int per = (NK + 1023) / 1024;
     const int lo = min(NK, tid * per), hi = min(NK, lo + per);
@@ -214,16 +214,9 @@ void plan_scan_kernel(PlanView pv, int NK, int32_t *__restrict__ out_group_off)
         items += c;
         chunks += (c + kChunk - 1) / kChunk;
     }
-    s_items[tid] = items; s_chunks[tid] = chunks;
-    __syncthreads();
-    for (int d = 1; d < 1024; d <<= 1) {          // Hillis-Steele inclusive scan
-        int a = 0, b = 0;
-        if (tid >= d) { a = s_items[tid - d]; b = s_chunks[tid - d]; }
-        __syncthreads();
-        s_items[tid] += a; s_chunks[tid] += b;
-        __syncthreads();
-    }
-    int run_i = s_items[tid] - items, run_c = s_chunks[tid] - chunks;
+    const int inc_i = block_scan<false>(items, tid, 16, wave_tot);
+    const int inc_c = block_scan<false>(chunks, tid, 16, wave_tot);
+    int run_i = inc_i - items, run_c = inc_c - chunks;
     for (int k = lo; k < hi; ++k) {
         int c = pv.count[k];
         pv.group_off[k] = run_i;
@@ -234,11 +227,11 @@ void plan_scan_kernel(PlanView pv, int NK, int32_t *__restrict__ out_group_off)
         run_c += (c + kChunk - 1) / kChunk;
     }
     if (tid == 1023) {
-        pv.group_off[NK] = s_items[1023];
-        if (out_group_off) out_group_off[NK] = s_items[1023];
-        pv.chunk_base[NK] = s_chunks[1023];
-        pv.hdr[0] = s_chunks[1023];
-        pv.hdr[1] = s_items[1023];
+        pv.group_off[NK] = inc_i;
+        if (out_group_off) out_group_off[NK] = inc_i;
+        pv.chunk_base[NK] = inc_c;
+        pv.hdr[0] = inc_c;
+        pv.hdr[1] = inc_i;
     }
 }
 

@@ -665,22 +665,28 @@ static hipError_t launch_multi_rp(const RowsArgs *sites, int n, hipStream_t st)
     return hipGetLastError();
 }
 
-// Dense sites of rank 8 or 16 whose d_in keeps most lanes of the shrink busy can share a launch.
-bool rows_can_group(const RowsArgs &a)
+// Waves per workgroup a site would run with in a shared launch (4 or 8), or 0 if it needs a launch
+// of its own.  Sites of rank 8 or 16 can share one; a dense site must also keep most lanes of an
+// 8-wave shrink busy, a packed MoE site takes 4 waves when 8 would be mostly idle.
+int rows_group_waves(const RowsArgs &a)
 {
-    if (a.r_pad != 8 && a.r_pad != 16) return false;
+    if ((a.r_pad != 8 && a.r_pad != 16) || a.out_f32 || tuning("rows_waves")) return 0;
     const int U = a.d_in >> 3;
     const int flu8 = a.r_pad == 8 ? RowsCfg<8, 8>::FLU : RowsCfg<16, 8>::FLU;
-    return a.n_experts == 1 && U >= flu8 * 3 / 4 && !tuning("rows_waves");
+    if (U >= flu8 * 3 / 4) return 8;
+    return a.n_experts > 1 ? 4 : 0;
 }
 
 hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st)
 {
     if (n < 1 || n > kMaxMulti) return hipErrorInvalidValue;
+    const int nw = rows_group_waves(sites[0]);
+    if (nw == 0) return hipErrorInvalidValue;
     for (int k = 0; k < n; ++k)
-        if (sites[k].r_pad != sites[0].r_pad || !rows_can_group(sites[k])) return hipErrorInvalidValue;
+        if (sites[k].r_pad != sites[0].r_pad || rows_group_waves(sites[k]) != nw) return hipErrorInvalidValue;
     if (sites[0].grid_chunks <= 0) return hipSuccess;
-    return sites[0].r_pad == 8 ? launch_multi_rp<8, 8>(sites, n, st) : launch_multi_rp<16, 8>(sites, n, st);
+    if (nw == 8) return sites[0].r_pad == 8 ? launch_multi_rp<8, 8>(sites, n, st) : launch_multi_rp<16, 8>(sites, n, st);
+    return sites[0].r_pad == 8 ? launch_multi_rp<8, 4>(sites, n, st) : launch_multi_rp<16, 4>(sites, n, st);
 }
 
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st)

@@ -424,6 +424,37 @@ def test_moe_empty_slot_and_single_adapter(M, oracle):
     check_moe(M, oracle, c, site)
 
 
+def test_moe_gate_up_in_one_launch(M, oracle):
+    """Gate and up of an expert layer share x and the route plan: moe_lora_apply_multi gives the
+    bits of separate calls and the oracle's values; a site of another rank in the list gets a
+    launch of its own."""
+    T, K, E, S = 150, 4, 8, 4
+    shapes = [(256, 136, 8), (256, 136, 8), (256, 72, 4), (2304, 264, 16), (2304, 136, 16)]
+    base = W.moe_case("route", 5400, T, K, E, 64, 64, S, 8, 16.0)
+    base.token_slot[::6] = -1
+    cases = []
+    for i, (di, do, r) in enumerate(shapes):
+        c = W.moe_case(f"mm{i}", 5401 + i, T, K, E, di, do, S, r, 2.0 * r, std_a=0.05, std_b=0.05)
+        c.topk, c.token_slot = base.topk, base.token_slot
+        cases.append(c)
+    sites = [moe_site(M, c) for c in cases]
+    plan = M.Plan(T * K, S * E)
+    M.moe_plan_route(plan, torch.from_numpy(base.topk).cuda(), torch.from_numpy(base.token_slot).cuda(), S, E)
+    xs = [P.dev_bf16(c.x) for c in cases]
+    ys = [P.dev_bf16(c.y0) for c in cases]
+    M.moe_lora_apply_multi(sites, plan, xs, ys)
+    torch.cuda.synchronize()
+    for c, site, x, y in zip(cases, sites, xs, ys):
+        ref = oracle.apply_moe(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, c.token_slot)
+        P.check_close(P.host_bits(y), ref, c.name)
+        y1 = P.dev_bf16(c.y0)
+        M.moe_lora_apply_planned(site, plan, x, y1)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y1), c.name
+    with pytest.raises(M.MLoraError):
+        M.lora_apply_decode_multi(sites[:2], plan, xs[:2], ys[:2])      # a route plan is not a decode plan
+
+
 def test_moe_planned_reuse(M, oracle):
     """One route plan shared by two sites (gate and up share the routing)."""
     ca = W.moe_case("gate", 5200, 120, 4, 8, 128, 64, 4, 8, 16.0, std_a=0.05, std_b=0.05)
