@@ -11,7 +11,7 @@ forward pass over 36 layers.  The timed loop is a HIP graph replay.
 
 Prints ONE JSON line: tokens/s of the layer step, the HBM roofline of the dominant kernel, and
 the CPU oracle timed on the same workload.  Other configurations are reported under
-"per_config".  `--workload c3|c4|c4d|c5|c5w` times a single configuration (used for profiling).
+"per_config".  `--workload c3|c4|c4d|c4m|c5|c5w` times a single configuration (used for profiling).
 """
 import argparse
 import json
@@ -242,6 +242,41 @@ def bench_c4_down(M, W, steps, warmup, n_sets=2):
             "bytes_per_step": moe_down_bytes(c)}
 
 
+def bench_c4_mixed(M, W, steps, warmup, n_sets=2):
+    """Gate site of the c4 layer whose 32 slots have ranks drawn from {2, 4, 8} in rank-8 tables:
+    the apply alone (route plan built once), with rank-bounded reads of A (the default for a launch
+    of this size) and with every padded row read."""
+    import torch
+    c = W.c4_moe_mixed_rank()
+    topk, ts = torch.from_numpy(c.topk).cuda(), torch.from_numpy(c.token_slot).cuda()
+    plan = M.Plan(c.T * c.K, c.n_slots * c.E)
+    M.moe_plan_route(plan, topk, ts, c.n_slots, c.E)
+    sets = []
+    for _ in range(n_sets):
+        site = M.Site(c.d_in, c.d_out, c.r_max, c.n_slots, n_experts=c.E)
+        upload_case(M, site, c)
+        sets.append((site, dev_bf16(c.x), dev_bf16(c.y0)))
+    torch.cuda.synchronize()
+
+    def sweep():
+        for site, x, y in sets:
+            M.moe_lora_apply_planned(site, plan, x, y)
+
+    reps, wreps = max(1, steps // n_sets), max(1, warmup // n_sets)
+    ms = time_region(graph_of(sweep).replay, reps, wreps) / n_sets
+    M.set_tuning("rows_rank_bound", -1)
+    try:
+        ms_padded = time_region(graph_of(sweep).replay, reps, wreps) / n_sets
+    finally:
+        M.set_tuning("rows_rank_bound", 0)
+    keys = set((int(c.token_slot[t]) * c.E + int(e)) for t in range(c.T) for e in c.topk[t])
+    P = c.T * c.K
+    # algorithmic: the true rank's rows of A and columns of B of every touched (slot, expert)
+    ab = sum(int(c.rank[k // c.E]) * (c.d_in + c.d_out) * 2 for k in keys)
+    return {"ms_per_step": ms, "ms_apply_only": ms, "ms_all_padded_rows_read": ms_padded, "tokens": c.T,
+            "launches_per_step": 1, "bytes_per_step": c.T * c.d_in * 2 + 2 * P * c.d_out * 2 + ab + P * 4 + c.T * 4}
+
+
 def bench_upload(M, W, reps=20):
     """Adapter load into a GPU slot of the c4 gate site (128 experts, rank 8, 2048 -> 768; 5.5 MB):
     from 256 per-expert host tensors through lora_slots_upload_experts (packed into the site's pinned
@@ -372,7 +407,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="all", choices=["all", "c2", "c3", "c4", "c4d", "c5", "c5w", "copy", "upload"])
+    ap.add_argument("--workload", default="all", choices=["all", "c2", "c3", "c4", "c4d", "c4m", "c5", "c5w", "copy", "upload"])
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--tune", action="append", default=[], help="name=value for mlora_set_tuning")
     args = ap.parse_args()
@@ -408,6 +443,12 @@ def main():
     if args.workload in ("all", "c4d"):
         log("[bench] c4 MoE down projection + combine")
         per["c4_moe_down"] = summarize(bench_c4_down(M, W, max(20, args.steps // 10), max(4, args.warmup // 10)))
+        torch.cuda.empty_cache()
+    if args.workload in ("all", "c4m"):
+        log("[bench] c4 gate site with slot ranks from {2, 4, 8}")
+        r = bench_c4_mixed(M, W, max(20, args.steps // 10), max(4, args.warmup // 10))
+        per["c4_moe_mixed_rank"] = summarize(r)
+        per["c4_moe_mixed_rank"]["us_all_padded_rows_read"] = round(r["ms_all_padded_rows_read"] * 1e3, 3)
         torch.cuda.empty_cache()
     if args.workload in ("all", "upload"):
         log("[bench] adapter load from per-expert tensors")

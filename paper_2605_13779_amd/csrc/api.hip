@@ -35,6 +35,8 @@ struct mlora_site {
     hipEvent_t stage_ev[2];
     bool stage_busy[2];
     int stage_next;
+    std::vector<int32_t> host_rank;   // what the uploads asked for, per slot (0 = empty): a hint for the launch shape only
+    int32_t n_short = 0;        // slots whose rank is below the padded rank of the tables
     void *pack;                 // pinned host image of one slot (A part, then B part) for uploads from per-expert tensors (lazy)
     hipEvent_t pack_ev;
     bool pack_busy;
@@ -57,6 +59,15 @@ constexpr int32_t kSegHpBlocks = (int32_t)((kSegXchBytes - kXchBytes - kSegCount
 
 std::mutex g_tune_mu;
 std::map<std::string, int> g_tune;
+
+// Host-side record of a slot's rank (the kernels read the device table; this only tells the launch
+// code whether any slot is padded, i.e. whether rank-bounded reads of A can save traffic).
+void note_rank(mlora_site *s, int32_t slot, int32_t r)
+{
+    int32_t &h = s->host_rank[(size_t)slot];
+    s->n_short += (int32_t)(r > 0 && r < s->r_pad) - (int32_t)(h > 0 && h < s->r_pad);
+    h = r;
+}
 
 int32_t round_pow2(int32_t r)
 {
@@ -163,6 +174,7 @@ RowsArgs rows_args(const mlora_site *s, const void *x, int64_t ldx, void *y, int
     a.d_in = s->d.d_in; a.d_out = s->d.d_out; a.r_pad = s->r_pad;
     a.n_experts = s->E; a.top_k = 1;
     a.xch = s->xch; a.ctrl = s->ctrl; a.xch_chunks = s->xch ? kXchChunks : 0;   // a rank-64 site's larger area holds these too
+    a.rank_bound = s->n_short > 0 ? 1 : 0;      // the launch code keeps it only where it pays
     a.prof = debug_prof();
     return a;
 }
@@ -366,6 +378,7 @@ int32_t mlora_site_create(const mlora_site_desc *d, void *a_tab, void *b_tab, vo
     s->d = *d;
     s->E = d->n_experts > 0 ? d->n_experts : 1;
     s->r_pad = round_pow2(d->r_max);
+    s->host_rank.assign((size_t)d->n_slots, 0);
     s->a_tab = (uint16_t *)a_tab; s->b_tab = (uint16_t *)b_tab;
     s->rank = (int32_t *)meta;
     s->scale = (float *)((char *)meta + (size_t)d->n_slots * 4);
@@ -444,6 +457,7 @@ int32_t lora_slots_upload(mlora_site *s, int32_t slot, int64_t catalog_id, const
     }
     if (!ok(e)) return MLORA_E_HIP;
     meta_set_kernel<<<dim3(1), dim3(1), 0, st>>>(s->rank, s->scale, s->catalog, slot, r, alpha / (float)r, catalog_id);
+    note_rank(s, slot, r);
     return ok(hipGetLastError()) ? MLORA_OK : MLORA_E_HIP;
 }
 
@@ -515,6 +529,7 @@ int32_t lora_slots_upload_experts(mlora_site *s, int32_t slot, int64_t catalog_i
     meta_set_kernel<<<dim3(1), dim3(1), 0, st>>>(s->rank, s->scale, s->catalog, slot, r, alpha / (float)r, catalog_id);
     if (!ok(hipEventRecord(s->pack_ev, st))) return MLORA_E_HIP;
     s->pack_busy = true;
+    note_rank(s, slot, r);
     return ok(hipGetLastError()) ? MLORA_OK : MLORA_E_HIP;
 }
 
@@ -553,6 +568,7 @@ int32_t lora_slots_evict(mlora_site *s, int32_t slot, void *stream)
     DeviceGuard g(s->d.device);
     if (!g.good) return MLORA_E_HIP;
     meta_set_kernel<<<dim3(1), dim3(1), 0, (hipStream_t)stream>>>(s->rank, s->scale, s->catalog, slot, 0, 0.f, -1);
+    note_rank(s, slot, 0);
     return ok(hipGetLastError()) ? MLORA_OK : MLORA_E_HIP;
 }
 

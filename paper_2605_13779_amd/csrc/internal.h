@@ -70,6 +70,7 @@ struct RowsArgs {
     int32_t tile_par;        // parts a chunk is cut into (one item each; 1 = one item per chunk): part p expands
     int32_t out_per_part;    // outputs [p * out_per_part, ...) and, in mode 2, shrinks k-slice p
     int32_t poll_limit;      // polls of an exchange word before a reader takes the item on its own
+    int32_t rank_bound;      // 1: read the slot's rank first and fetch only that many rows of A
     // MoE down projection: instead of adding into y, row p writes row_w[p] * delta as fp32 into
     // out_f32[p, :] (no read); a second launch adds a token's rows in order
     float *out_f32; int64_t ldo;

@@ -273,8 +273,24 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                 }
             }
         };
-        const char *Ag = (const char *)(a.a_tab + (int64_t)key * RP * a.d_in + (int64_t)(jg * C::JPW) * a.d_in);
         const uint32_t a_row_bytes = (uint32_t)a.d_in * 2u;
+        const char *Ag = (const char *)(a.a_tab + (int64_t)key * RP * a.d_in);
+        uint32_t a_row_off[C::JPW];
+        if constexpr (XCH) {
+            Ag += (int64_t)(jg * C::JPW) * a_row_bytes;
+#pragma unroll
+            for (int jj = 0; jj < C::JPW; ++jj) a_row_off[jj] = (uint32_t)jj * a_row_bytes;
+        } else {
+            // Rank-bounded reads (slots of different true rank in one padded table): rows of A past
+            // the slot's rank are not fetched.  The wave that would have read them reads the slot's
+            // last real row again (a cache hit, every load is still issued), and what it computes
+            // from that row meets the zero columns of B in the expand.
+            int a_last = RP - 1;
+            if (a.rank_bound) a_last = min(max(__builtin_amdgcn_readfirstlane(a.meta.rank[slot]), 1), RP) - 1;
+            const int a_j0 = __builtin_amdgcn_readfirstlane(jg * C::JPW);
+#pragma unroll
+            for (int jj = 0; jj < C::JPW; ++jj) a_row_off[jj] = (uint32_t)min(a_j0 + jj, a_last) * a_row_bytes;
+        }
         const uint4 *xp[kChunk];
 #pragma unroll
         for (int c = 0; c < kChunk; ++c) xp[c] = (const uint4 *)(a.x + (int64_t)(row[c] / a.top_k) * a.ldx);
@@ -283,7 +299,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
             const int u = f + ks * 64 + lane;
             const uint32_t ub = (uint32_t)(u < uh ? u : ul) * 16u;
 #pragma unroll
-            for (int jj = 0; jj < C::JPW; ++jj) av[jj] = *(const uint4 *)(Ag + (size_t)((uint32_t)jj * a_row_bytes) + ub);
+            for (int jj = 0; jj < C::JPW; ++jj) av[jj] = *(const uint4 *)(Ag + (size_t)a_row_off[jj] + ub);
 #pragma unroll
             for (int c = 0; c < kChunk; ++c) xv[c] = *(const uint4 *)((const char *)xp[c] + ub);
         };
@@ -606,6 +622,16 @@ static int fused_grid(const RowsArgs &a)
     return a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : ((a.grid_chunks + 63) & ~63);
 }
 
+// Rank-bounded reads of A cost one dependent read of the slot's rank in front of the item's loads:
+// worth it where a launch runs several rounds of items per CU (the read hides behind the other
+// items), not where the launch is one short chain.  "rows_rank_bound": 1 always, -1 never.
+static int use_rank_bound(const RowsArgs &a, int cap)
+{
+    const int t = tuning("rows_rank_bound");
+    if (t) return t > 0 ? 1 : 0;
+    return a.rank_bound && a.mode != 2 && (int64_t)a.grid_chunks * 2 >= cap;
+}
+
 static int items_target(int cap)
 {
     // the chunk count used for the division is an upper bound; live chunks are fewer, and a launch
@@ -622,6 +648,7 @@ static hipError_t launch_rp(RowsArgs a, hipStream_t st)
     if (cap <= 0) return hipErrorUnknown;
     const bool exchange = can_exchange(a) && mode == 0;
     set_parts(a, mode == 3 ? 1 : items_target(cap) / a.grid_chunks, exchange);
+    a.rank_bound = use_rank_bound(a, cap);
     if (a.mode == 2) rows_kernel<RP, NW, true><<<dim3((unsigned)fused_grid(a)), dim3(NW * 64), 0, st>>>(a);
     else rows_kernel<RP, NW, false><<<dim3((unsigned)fused_grid(a)), dim3(NW * 64), 0, st>>>(a);
     return hipGetLastError();
@@ -656,6 +683,7 @@ static hipError_t launch_multi_rp(const RowsArgs *sites, int n, hipStream_t st)
     for (int k = 0; k < n; ++k) {
         m.site[k] = sites[k];
         set_parts(m.site[k], (int)(chunk_bytes(sites[k]) / per_item + 0.5), exchange);
+        m.site[k].rank_bound = use_rank_bound(m.site[k], cap);
         any_x = any_x || m.site[k].mode == 2;
         m.first[k + 1] = m.first[k] + fused_grid(m.site[k]);
     }

@@ -455,6 +455,31 @@ def test_moe_gate_up_in_one_launch(M, oracle):
         M.lora_apply_decode_multi(sites[:2], plan, xs[:2], ys[:2])      # a route plan is not a decode plan
 
 
+def test_rank_bounded_reads_of_padded_slots(M, oracle):
+    """Slots of different true rank in one padded table: with rank-bounded reads a wave fetches
+    only the slot's real rows of A (forced on and off here; by default the launch code enables it
+    for big launches over tables that hold a padded slot, as in the last case)."""
+    ranks = [3, 16, 0, 7, 1, 12]
+    cd = W.dense_case("rb_dense", 5500, 90, 256, 520, 6, 16, 24.0, ranks=ranks, std_a=0.05, std_b=0.05)
+    cm = W.moe_case("rb_moe", 5501, 120, 4, 8, 136, 200, 4, 8, np.array([4.0, 16.0, 2.0, 10.0]),
+                    ranks=[2, 8, 1, 5], std_a=0.05, std_b=0.05)
+    c32 = W.dense_case("rb_r32", 5502, 50, 328, 264, 3, 32, 16.0, ranks=[9, 32, 17], std_a=0.05, std_b=0.05)
+    sd, sm, s32 = dense_site(M, cd), moe_site(M, cm), dense_site(M, c32)
+    for force in (1, -1):
+        M.set_tuning("rows_rank_bound", force)
+        try:
+            check_dense(M, oracle, cd, lambda y0: run_decode(M, sd, cd, y0))
+            check_dense(M, oracle, c32, lambda y0: run_decode(M, s32, c32, y0))
+            check_moe(M, oracle, cm, sm)
+        finally:
+            M.set_tuning("rows_rank_bound", 0)
+    # a launch with more chunks than the GPU runs at once turns it on by itself
+    big = W.moe_case("rb_big", 5503, 1500, 4, 64, 72, 136, 8, 8, 16.0, ranks=[2, 4, 8, 8, 1, 3, 8, 6],
+                     std_a=0.05, std_b=0.05)
+    rng = np.random.default_rng(5504)
+    check_moe(M, oracle, big, moe_site(M, big), pairs=np.sort(rng.choice(1500 * 4, 500, replace=False)))
+
+
 def test_moe_planned_reuse(M, oracle):
     """One route plan shared by two sites (gate and up share the routing)."""
     ca = W.moe_case("gate", 5200, 120, 4, 8, 128, 64, 4, 8, 16.0, std_a=0.05, std_b=0.05)

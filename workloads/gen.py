@@ -272,6 +272,20 @@ def c4_moe_packed(proj: str = "gate") -> MoECase:
     return c
 
 
+def c4_moe_mixed_rank() -> MoECase:
+    """The gate site of the c4 layer with heterogeneous adapters (ranks differ between the tenants
+    of one worker and are padded into the shape of the largest one): each of the 32 slots draws its
+    rank from {2, 4, 8} with equal probability, alpha = 2 * rank; tables of rank 8; same routing
+    and slots as c4."""
+    g = rng(SEED0 + 4)
+    token_slot = g.integers(0, 32, size=2048).astype(np.int32)
+    topk = topk_routing(g, 2048, 128, 8)
+    ranks = rng(SEED0 + 44).choice(np.array([2, 4, 8], dtype=np.int32), size=32)
+    c = moe_case("c4_mixed", SEED0 + 404, 2048, 8, 128, 2048, 768, 32, 8, 2.0 * ranks, ranks=ranks)
+    c.token_slot, c.topk = token_slot, topk
+    return c
+
+
 def c4_moe_down() -> MoEDownCase:
     """The down projection of the c4 layer: 2048 tokens, 128 experts of intermediate 768 back to
     hidden 2048, top-8 with routing weights, 32 slots rank 8 alpha 16; routing and slots are the
