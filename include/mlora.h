@@ -98,8 +98,9 @@ int32_t lora_slots_upload(mlora_site *site, int32_t slot, int64_t catalog_id,
  * packing, Section 4.4: one [r, d_in] and one [d_out, r] tensor per expert and projection).
  *   A_e, B_e: HOST arrays of max(n_experts, 1) HOST pointers to contiguous bf16 tensors.
  * The tensors are stacked along the expert axis, zero padded to r_pad, into a pinned host image of
- * the slot that the site keeps, and each table receives ONE host-to-device copy.  The call returns
- * when the image is packed; the caller's tensors may be released then.  A second call on the same
+ * the slot that the site keeps, and leave the host in a few large copies (about 2 MB each, issued
+ * while the host packs the next piece) instead of one copy per tensor.  The call returns when the
+ * image is packed and every copy is enqueued; the caller's tensors may be released then.  A second call on the same
  * site waits until the previous image has been copied.
  * mlora_pack_experts is the host-only packing step (a_img / b_img: mlora_slot_image_bytes bytes);
  * it needs no GPU. */

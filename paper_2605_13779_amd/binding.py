@@ -215,13 +215,23 @@ def pack_experts(desc, A_e, B_e, r):
     return a_img, b_img
 
 
+class ExpertTensors:
+    """The host pointer arrays of an adapter's per-expert tensors (lists of uint16 numpy arrays
+    [r, d_in] and [d_out, r]), marshalled once; keeps the arrays alive."""
+
+    def __init__(self, A_e, B_e):
+        import numpy as np
+        self.A_e = [np.ascontiguousarray(a, dtype=np.uint16) for a in A_e]
+        self.B_e = [np.ascontiguousarray(b, dtype=np.uint16) for b in B_e]
+        self.pa, self.pb = _ptr_array(self.A_e), _ptr_array(self.B_e)
+
+
 def lora_slots_upload_experts(site, slot, catalog_id, A_e, B_e, r, alpha, stream=None):
-    """A_e / B_e: lists of per-expert uint16 numpy arrays ([r, d_in] and [d_out, r])."""
-    import numpy as np
-    A_e = [np.ascontiguousarray(a, dtype=np.uint16) for a in A_e]
-    B_e = [np.ascontiguousarray(b, dtype=np.uint16) for b in B_e]
+    """A_e / B_e: lists of per-expert uint16 numpy arrays ([r, d_in] and [d_out, r]), or A_e an
+    ExpertTensors (then B_e is ignored)."""
+    t = A_e if isinstance(A_e, ExpertTensors) else ExpertTensors(A_e, B_e)
     _check("lora_slots_upload_experts", load_library().lora_slots_upload_experts(
-        site.handle, slot, catalog_id, _ptr_array(A_e), _ptr_array(B_e), r, alpha, _stream(stream)))
+        site.handle, slot, catalog_id, t.pa, t.pb, r, alpha, _stream(stream)))
 
 
 def lora_slot_lookup(site, token_catalog_id, token_slot_out, stream=None):

@@ -2,6 +2,7 @@
 // the LoRA apply runs in the kernels of rows.hip / seg_mfma.hip / plan.hip.
 #include "internal.h"
 
+#include <algorithm>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -472,6 +473,33 @@ int32_t mlora_slot_image_bytes(const mlora_site_desc *d, size_t *a_bytes, size_t
     return MLORA_OK;
 }
 
+// Experts [e0, e1) of one table of the slot image.
+// A_e [r, d_in] -> rows 0..r-1 of the expert's [r_pad, d_in] block, the rest zero
+static void pack_a_range(char *ai, const void *const *A_e, int64_t e0, int64_t e1, int64_t r, int64_t rp, int64_t d_in)
+{
+    for (int64_t e = e0; e < e1; ++e) {
+        std::memcpy(ai + e * rp * d_in * 2, A_e[e], (size_t)r * d_in * 2);
+        if (r < rp) std::memset(ai + (e * rp + r) * d_in * 2, 0, (size_t)(rp - r) * d_in * 2);
+    }
+}
+
+// B_e [d_out, r] -> columns 0..r-1 of the expert's [d_out, r_pad] block, the rest zero
+static void pack_b_range(char *bi, const void *const *B_e, int64_t e0, int64_t e1, int64_t r, int64_t rp, int64_t d_out)
+{
+    for (int64_t e = e0; e < e1; ++e) {
+        if (r == rp) {
+            std::memcpy(bi + e * d_out * rp * 2, B_e[e], (size_t)d_out * rp * 2);
+            continue;
+        }
+        const char *src = (const char *)B_e[e];
+        char *dst = bi + e * d_out * rp * 2;
+        for (int64_t o = 0; o < d_out; ++o) {
+            std::memcpy(dst + o * rp * 2, src + o * r * 2, (size_t)r * 2);
+            std::memset(dst + (o * rp + r) * 2, 0, (size_t)(rp - r) * 2);
+        }
+    }
+}
+
 int32_t mlora_pack_experts(const mlora_site_desc *d, const void *const *A_e, const void *const *B_e, int32_t r,
                            void *a_img, void *b_img)
 {
@@ -479,26 +507,11 @@ int32_t mlora_pack_experts(const mlora_site_desc *d, const void *const *A_e, con
     if (rc) return rc;
     if (!A_e || !B_e || !a_img || !b_img) return MLORA_E_INVALID;
     if (r < 1 || r > d->r_max) return MLORA_E_SHAPE;
-    const int64_t E = d->n_experts > 0 ? d->n_experts : 1, rp = round_pow2(d->r_max), d_in = d->d_in, d_out = d->d_out;
+    const int64_t E = d->n_experts > 0 ? d->n_experts : 1, rp = round_pow2(d->r_max);
     for (int64_t e = 0; e < E; ++e)
         if (!A_e[e] || !B_e[e]) return MLORA_E_INVALID;
-    char *ai = (char *)a_img, *bi = (char *)b_img;
-    for (int64_t e = 0; e < E; ++e) {
-        // A_e [r, d_in] -> rows 0..r-1 of the expert's [r_pad, d_in] block, the rest zero
-        std::memcpy(ai + e * rp * d_in * 2, A_e[e], (size_t)r * d_in * 2);
-        if (r < rp) std::memset(ai + (e * rp + r) * d_in * 2, 0, (size_t)(rp - r) * d_in * 2);
-        // B_e [d_out, r] -> columns 0..r-1 of the expert's [d_out, r_pad] block, the rest zero
-        if (r == rp) {
-            std::memcpy(bi + e * d_out * rp * 2, B_e[e], (size_t)d_out * rp * 2);
-        } else {
-            const char *src = (const char *)B_e[e];
-            char *dst = bi + e * d_out * rp * 2;
-            for (int64_t o = 0; o < d_out; ++o) {
-                std::memcpy(dst + o * rp * 2, src + o * r * 2, (size_t)r * 2);
-                std::memset(dst + (o * rp + r) * 2, 0, (size_t)(rp - r) * 2);
-            }
-        }
-    }
+    pack_a_range((char *)a_img, A_e, 0, E, r, rp, d->d_in);
+    pack_b_range((char *)b_img, B_e, 0, E, r, rp, d->d_out);
     return MLORA_OK;
 }
 
@@ -519,13 +532,30 @@ int32_t lora_slots_upload_experts(mlora_site *s, int32_t slot, int64_t catalog_i
         if (!ok(hipEventCreateWithFlags(&s->pack_ev, hipEventDisableTiming))) return MLORA_E_HIP;
     }
     if (s->pack_busy && !ok(hipEventSynchronize(s->pack_ev))) return MLORA_E_HIP;   // the previous image has left the host
-    rc = mlora_pack_experts(&s->d, A_e, B_e, r, s->pack, (char *)s->pack + ab);
-    if (rc) return rc;
-    // the image is the slot's bytes, padding included: one copy per table, no zero-fill launch
+    const int64_t E = s->E, rp = s->r_pad;
+    for (int64_t e = 0; e < E; ++e)
+        if (!A_e[e] || !B_e[e]) return MLORA_E_INVALID;
+    // The image is the slot's bytes, padding included: no zero-fill launch.  It leaves the host in
+    // pieces of about 2 MB ("upload_piece_kb"; measured best among 256 KB .. whole table), each copied
+    // as soon as it is packed, so that the copies of the earlier pieces run while the host packs the
+    // later ones.
     meta_set_kernel<<<dim3(1), dim3(1), 0, st>>>(s->rank, s->scale, s->catalog, slot, 0, 0.f, -1);
-    hipError_t e = hipMemcpyAsync((char *)s->a_tab + (size_t)slot * ab, s->pack, ab, hipMemcpyHostToDevice, st);
-    if (ok(e)) e = hipMemcpyAsync((char *)s->b_tab + (size_t)slot * bb, (char *)s->pack + ab, bb, hipMemcpyHostToDevice, st);
-    if (!ok(e)) return MLORA_E_HIP;
+    char *ai = (char *)s->pack, *bi = ai + ab;
+    // after a failed copy the earlier pieces may still be leaving the image: wait before it can be reused
+    auto drain = [&]() { (void)hipStreamSynchronize(st); return (int32_t)MLORA_E_HIP; };
+    const int64_t a_exp = rp * s->d.d_in * 2, b_exp = (int64_t)s->d.d_out * rp * 2;       // bytes per expert
+    const int64_t piece = (int64_t)(tuning("upload_piece_kb") > 0 ? tuning("upload_piece_kb") : 2048) << 10;
+    const int64_t a_step = std::max<int64_t>(1, piece / a_exp), b_step = std::max<int64_t>(1, piece / b_exp);
+    for (int64_t e0 = 0; e0 < E; e0 += a_step) {
+        const int64_t e1 = std::min(E, e0 + a_step);
+        pack_a_range(ai, A_e, e0, e1, r, rp, s->d.d_in);
+        if (!ok(hipMemcpyAsync((char *)s->a_tab + (size_t)slot * ab + e0 * a_exp, ai + e0 * a_exp, (size_t)((e1 - e0) * a_exp), hipMemcpyHostToDevice, st))) return drain();
+    }
+    for (int64_t e0 = 0; e0 < E; e0 += b_step) {
+        const int64_t e1 = std::min(E, e0 + b_step);
+        pack_b_range(bi, B_e, e0, e1, r, rp, s->d.d_out);
+        if (!ok(hipMemcpyAsync((char *)s->b_tab + (size_t)slot * bb + e0 * b_exp, bi + e0 * b_exp, (size_t)((e1 - e0) * b_exp), hipMemcpyHostToDevice, st))) return drain();
+    }
     meta_set_kernel<<<dim3(1), dim3(1), 0, st>>>(s->rank, s->scale, s->catalog, slot, r, alpha / (float)r, catalog_id);
     if (!ok(hipEventRecord(s->pack_ev, st))) return MLORA_E_HIP;
     s->pack_busy = true;
