@@ -291,9 +291,23 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
             i += n;
         }
         if ((int64_t)tab.size() > (int64_t)s->seg_cap * 3) return MLORA_E_UNSUPPORTED;
-        int32_t rc = stage_table(s, tab, st);
-        if (rc) return rc;
         SegArgs a{};
+        // a batch whose tables fit the kernel arguments needs no copy in front of its launches
+        a.inl_on = 2 * nt + 3 * n_ranges <= kSegInline && s->d.n_slots <= 0xffff && !tuning("seg_table_copy");
+        if (a.inl_on) {
+            for (int32_t i = 0; i < nt; ++i) {
+                a.inl[2 * i] = (uint32_t)tab[4 * i + 1];
+                a.inl[2 * i + 1] = (uint32_t)tab[4 * i] | (uint32_t)tab[4 * i + 2] << 16;
+            }
+            for (int32_t j = 0; j < n_ranges; ++j) {
+                const int32_t *r = tab.data() + 4 * (nt + j);
+                uint32_t *o = a.inl + 2 * nt + 3 * j;
+                o[0] = (uint32_t)r[1]; o[1] = (uint32_t)r[0] | (uint32_t)r[2] << 16; o[2] = (uint32_t)r[3];
+            }
+        } else {
+            int32_t rc = stage_table(s, tab, st);
+            if (rc) return rc;
+        }
         a.x = (const uint16_t *)x; a.ldx = ldx; a.y = (uint16_t *)y; a.ldy = ldy;
         a.a_tab = s->a_tab; a.b_tab = s->b_tab; a.meta.rank = s->rank; a.meta.scale = s->scale;
         a.tiles = s->seg_dev; a.n_tiles = nt;

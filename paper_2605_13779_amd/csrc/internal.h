@@ -85,6 +85,7 @@ hipError_t launch_moe_combine(uint16_t *y, int64_t ldy, const float *parts, int6
                               const int32_t *rank, int32_t n_slots, int32_t T, int32_t K, int32_t d_out, hipStream_t st);
 
 // seg_mfma.hip: rank-64 segmented apply on the matrix cores (a shrink launch, then an expand launch)
+constexpr int kSegInline = 832;   // words of tables inside the kernel arguments (the whole argument block stays below 4 KB)
 struct SegArgs {
     const uint16_t *x; int64_t ldx;
     uint16_t *y;       int64_t ldy;
@@ -101,6 +102,11 @@ struct SegArgs {
     int32_t upt;             // units of d_in per tile (a unit is seg_unit() elements)
     int32_t n_swg;           // workgroups of the shrink launch; n_swg * 3 <= n_tiles * upt
     int32_t n_slices;        // output slices of 512
+    // Small batches carry both tables inside the kernel arguments (no table copy in front of the
+    // launches): tile i = words 2i (first row) and 2i + 1 (slot | rows << 16), range j = words
+    // 2 * n_tiles + 3j (first row), + 1 (slot | rows << 16), + 2 (first tile).  inl_on = 0: read tiles / ranges.
+    int32_t inl_on;
+    uint32_t inl[kSegInline];
 };
 hipError_t launch_seg_mfma(const SegArgs &a, hipStream_t st);
 int seg_unit();

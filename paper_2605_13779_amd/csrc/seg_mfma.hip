@@ -65,6 +65,25 @@ __device__ __forceinline__ void static_for2(F &&f)
     f(std::integral_constant<int, 1>{});
 }
 
+// Table records, from the kernel arguments when the batch is small enough to carry them there.
+struct SegRec { int slot, row0, rows, tile0; };
+__device__ __forceinline__ SegRec seg_tile(const SegArgs &a, int i)
+{
+    if (a.inl_on) {
+        const uint32_t w0 = a.inl[2 * i], w1 = a.inl[2 * i + 1];
+        return {(int)(w1 & 0xffffu), (int)w0, (int)(w1 >> 16), 0};
+    }
+    return {a.tiles[4 * i], a.tiles[4 * i + 1], a.tiles[4 * i + 2], 0};
+}
+__device__ __forceinline__ SegRec seg_range(const SegArgs &a, int j)
+{
+    if (a.inl_on) {
+        const uint32_t *r = a.inl + 2 * a.n_tiles + 3 * j;
+        return {(int)(r[1] & 0xffffu), (int)r[0], (int)(r[1] >> 16), (int)r[2]};
+    }
+    return {a.ranges[4 * j], a.ranges[4 * j + 1], a.ranges[4 * j + 2], a.ranges[4 * j + 3]};
+}
+
 // Workgroups are dealt round-robin to the 8 XCDs; work ids are laid out so that an XCD gets a
 // contiguous range of them (neighbouring ids share adapter bytes, which then sit in that XCD's L2).
 __device__ __forceinline__ int xcd_contiguous_id()
@@ -113,7 +132,8 @@ void seg_shrink_kernel(const SegArgs a)
     const char *f_a = nullptr;
     int64_t f_x[2];
     auto f_open = [&]() {                              // addresses for the tile the fetch side is in
-        const int slot = max(a.tiles[4 * f_tile], 0), row0 = a.tiles[4 * f_tile + 1], nrows = a.tiles[4 * f_tile + 2];
+        const SegRec t = seg_tile(a, f_tile);
+        const int slot = max(t.slot, 0), row0 = t.row0, nrows = t.rows;
         f_a = (const char *)(a.a_tab + (int64_t)slot * 64 * a.d_in);
 #pragma unroll
         for (int q = 0; q < 2; ++q) f_x[q] = (int64_t)(row0 + min(srow + 32 * q, nrows - 1)) * a.ldx * 2;
@@ -136,7 +156,8 @@ void seg_shrink_kernel(const SegArgs a)
     f32x16_t acc = {0};
     // this share's piece of tile c_tile is complete; buf is the stage buffer that was multiplied last
     auto finish_tile = [&](unsigned char *buf) {
-        const int slot = a.tiles[4 * c_tile], nrows = a.tiles[4 * c_tile + 2];
+        const SegRec ct = seg_tile(a, c_tile);
+        const int slot = ct.slot, nrows = ct.rows;
         __syncthreads();                               // the staged unit has been read by every wave
         float *red = (float *)buf;                     // [k half][64 rows][64 adapter rows]
 #pragma unroll
@@ -275,8 +296,8 @@ void seg_expand_kernel(const SegArgs a)
     const int id = xcd_contiguous_id();
     if (id >= a.n_ranges * a.n_slices) return;
     const int sl = id / a.n_ranges, rg = id - sl * a.n_ranges;    // ids of one output slice are neighbours
-    const int slot = a.ranges[4 * rg], row0 = a.ranges[4 * rg + 1], nrows = a.ranges[4 * rg + 2];
-    const int tile0 = a.ranges[4 * rg + 3];
+    const SegRec rr = seg_range(a, rg);
+    const int slot = rr.slot, row0 = rr.row0, nrows = rr.rows, tile0 = rr.tile0;
     if (slot < 0 || a.meta.rank[slot] <= 0) return;
     const float scale = a.meta.scale[slot];
 

@@ -324,6 +324,13 @@ def test_segmented_small(M, oracle, r, d_in, d_out):
     ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
     P.check_close(a, ref, "seg")
     P.check_close(b, ref, "dec")
+    if r == 64:
+        # small batches carry their tile tables in the kernel arguments; the copied table must give the same bits
+        M.set_tuning("seg_table_copy", 1)
+        try:
+            assert np.array_equal(run_seg(M, site, c, c.y0), a)
+        finally:
+            M.set_tuning("seg_table_copy", 0)
 
 
 def test_segmented_many_tiles_in_batches(M, oracle):
