@@ -658,6 +658,49 @@ def test_device_side_catalog_id_lookup(M, oracle):
     P.check_untouched(P.host_bits(y), c.y0, want < 0, "by catalog id")
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_shapes_against_oracle(M, oracle, seed):
+    """Shapes nobody picked by hand: seeded draws of rank (powers of two and not), per-slot true ranks
+    (empty slots included), d_in / d_out (any multiple of 8), slot and expert counts, batch and
+    segment lengths, cycling over the four entry points."""
+    rng = np.random.default_rng(7700 + seed)
+    dim = lambda lo, hi: int(rng.integers(lo // 8, hi // 8 + 1)) * 8
+    for it in range(16):
+        kind = ("dense", "moe", "seg", "down")[it % 4]
+        r_max = int(rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64]))
+        S = int(rng.integers(1, 9))
+        ranks = [int(rng.integers(0, r_max + 1)) for _ in range(S)]
+        if max(ranks) == 0:
+            ranks[0] = r_max
+        alpha = (rng.random(S) * 30 + 1).round(2)
+        d_in, d_out = dim(16, 1400), dim(8, 1100)
+        if kind == "seg" and r_max == 64:
+            d_in = (d_in + 15) // 16 * 16
+        name, kw = f"rand{seed}_{it}_{kind}", dict(ranks=ranks, std_a=0.05, std_b=0.05)
+        print(name, "r_max", r_max, "ranks", ranks, "d_in", d_in, "d_out", d_out, flush=True)
+        if kind == "dense":
+            c = W.dense_case(name, 7800 + 16 * seed + it, int(rng.integers(1, 400)), d_in, d_out, S, r_max, alpha, **kw)
+            site = dense_site(M, c)
+            check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0, planned=bool(it & 4)))
+            continue
+        if kind == "seg":
+            lens = rng.integers(0, 300, size=int(rng.integers(1, 12)))
+            lens[0] += 5
+            seg_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+            seg_slot = rng.integers(-1, S, size=len(lens)).astype(np.int32)
+            c = W.seg_case(name, 7800 + 16 * seed + it, int(lens.sum()), len(lens), d_in, d_out, S, r_max, alpha,
+                           seg_off=seg_off, seg_slot=seg_slot, **kw)
+            site = dense_site(M, c)
+            check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0))
+            continue
+        T, E = int(rng.integers(1, 200)), int(rng.choice([1, 2, 4, 8, 16]))
+        K = int(rng.integers(1, min(E, 8) + 1))
+        make = W.moe_case if kind == "moe" else W.moe_down_case
+        c = make(name, 7800 + 16 * seed + it, T, K, E, d_in, d_out, S, r_max, alpha, **kw)
+        c.token_slot[::5] = -1
+        (check_moe if kind == "moe" else check_moe_down)(M, oracle, c, moe_site(M, c))
+
+
 def test_abi_error_codes(M):
     with pytest.raises(M.MLoraError) as e:
         M.Site(100, 64, 8, 2)                       # d_in not a multiple of 8
