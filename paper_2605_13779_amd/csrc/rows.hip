@@ -187,6 +187,13 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
     bool solo_next = false;
 
     for (int item = wg; item < n_items; item += n_wg) {
+        // Per-item copies of the thread's coordinates: what is derived from them (LDS addresses, lane
+        // masks) is recomputed in each item instead of being kept, and spilled, across the whole loop;
+        // a reload of such a spill would wait for every load of the item that is still in flight.
+        int tid_item = (int)threadIdx.x;
+        asm volatile("" : "+v"(tid_item));
+        const int tid = tid_item, w = tid >> 6, lane = tid & 63;
+        const int jg = w % C::JG, ks = w / C::JG;
         // ---- which chunk, which part of it ----
         int chunk, kslice = 0, out0 = 0, out1 = a.d_out;
         bool do_shrink = true, do_expand = true;
