@@ -35,6 +35,7 @@ constexpr int KU = 128;           // elements of d_in per unit of the shrink (8 
 constexpr int UROW = KU * 2 + 16; // padded byte stride of a staged row (x or A)
 constexpr int STAGE_BYTES = (TM + 64) * UROW;
 constexpr int RED_BYTES = 2 * TM * 64 * 4;                // the two k halves of a unit
+constexpr int kWaitVm0 = 0x0F70; // s_waitcnt vmcnt(0) with the other counters left alone (gfx9 encoding)
 constexpr int ES = 512;           // outputs per expand slice (64 per wave)
 constexpr int H_LD = 72;          // padded row stride of the bf16 h tiles, in elements
 constexpr int ST_LD = 68;         // padded row stride of a wave's 16 x 64 staging tile, in floats
@@ -191,7 +192,7 @@ void seg_shrink_kernel(const SegArgs a)
             // count.  (Release and acquire fences would do the same by writing back and invalidating
             // the whole L2, which holds the adapter rows everybody is reading.)  The wait also drains
             // the units in flight; it happens once or twice per workgroup.
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(kWaitVm0);
             __syncthreads();
             if (tid == 0) {
                 const int old = __hip_atomic_fetch_add(a.hcount + c_tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -240,6 +241,10 @@ void seg_shrink_kernel(const SegArgs a)
                 *(uint2 *)(hf + row * 128 + 64 + c4 * 4) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
             }
         }
+        // Every path through here ends with nothing in flight, and the compiler is told so (a wait it
+        // can see, not inline assembly): otherwise it assumes that loads of this block may still be
+        // pending where the paths join again and drains the prefetched units in front of every fetch.
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __syncthreads();                               // the partials' LDS is staged into again
     };
     int c_left = n;
