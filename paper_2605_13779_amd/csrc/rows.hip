@@ -226,6 +226,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         int row[kChunk];
         row[0] = __builtin_amdgcn_readfirstlane(r1.x); row[1] = __builtin_amdgcn_readfirstlane(r1.y);
         row[2] = __builtin_amdgcn_readfirstlane(r1.z); row[3] = __builtin_amdgcn_readfirstlane(r1.w);
+        if (prof && tid == 0 && first_item) prof[5] = wall_clock64();      // the chunk record has arrived
         if (XCH && first_item) {
             if (tid == 0) {
                 s_tag = tag;
@@ -234,6 +235,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
             __syncthreads();
             tag = s_tag;
         }
+        if (prof && tid == 0 && first_item) prof[6] = wall_clock64();      // ... and the launch tag
         if (cnt <= 0) { first_item = false; continue; }            // record past the live chunks of this batch
 #pragma unroll
         for (int c = 1; c < kChunk; ++c) row[c] = c < cnt ? row[c] : row[0];
@@ -305,6 +307,18 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         auto load_flight = [&](int f, int ul, int uh) {
             const int u = f + ks * 64 + lane;
             const uint32_t ub = (uint32_t)(u < uh ? u : ul) * 16u;
+            if constexpr (XCH) {
+                // A k-slice of an exchange item is often narrower than the workgroup (64 units = one
+                // wave): the waves past its end issue nothing.  A CU accepts one 64-lane 16-byte load
+                // per 16 cycles, and their clamped loads took more of that than the item's real bytes.
+                if (__builtin_amdgcn_readfirstlane(f + ks * 64) >= uh) {
+#pragma unroll
+                    for (int jj = 0; jj < C::JPW; ++jj) av[jj] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+                    for (int c = 0; c < kChunk; ++c) xv[c] = make_uint4(0, 0, 0, 0);
+                    return;
+                }
+            }
 #pragma unroll
             for (int jj = 0; jj < C::JPW; ++jj) av[jj] = *(const uint4 *)(Ag + (size_t)a_row_off[jj] + ub);
 #pragma unroll
