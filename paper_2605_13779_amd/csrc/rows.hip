@@ -264,8 +264,17 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
             prow[c] = a.out_f32 + (int64_t)row[c] * a.ldo;
             wrow[c] = to_parts ? a.row_w[row[c] + lane_zero] : 1.f;
         }
+        // Matrix-core expand: the result comes out with lane l holding row l%4 of the chunk and the four
+        // outputs of its block (see below), so a lane reads and writes 8 contiguous bytes of its own row:
+        // one 64-lane access covers 128 contiguous bytes of each of the four rows.
+        const int r4 = lane & 3;
+        const int my_row = r4 == 0 ? row[0] : (r4 == 1 ? row[1] : (r4 == 2 ? row[2] : row[3]));
+        char *const y_lane = (char *)(a.y + (int64_t)my_row * a.ldy);
+        char *const p_lane = (char *)(a.out_f32 + (int64_t)my_row * a.ldo);
+        const float w_lane = (C::MX && to_parts) ? a.row_w[my_row] : 1.f;
         uint4 braw[C::DEPTH][C::EU][C::BV];
-        yvec_t yraw[C::DEPTH][C::EU][kChunk];
+        yvec_t yraw[C::DEPTH][C::EU][C::MX ? 1 : kChunk];
+        uint2 yq[C::DEPTH][C::EU];
         auto load_tile = [&](int lo, auto dconst) {
             constexpr int d = decltype(dconst)::value;
 #pragma unroll
@@ -276,9 +285,13 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
 #pragma unroll
                 for (int q = 0; q < C::BV; ++q) braw[d][e][q] = *(const uint4 *)((const char *)Bg + (oc * (uint32_t)(RP * 2) + (uint32_t)(q * 16)));
                 if (!to_parts) {
+                    if constexpr (C::MX) {
+                        yq[d][e] = *(const uint2 *)(y_lane + (oc & ~3u) * 2u);
+                    } else {
 #pragma unroll
-                    for (int c = 0; c < kChunk; ++c)  // rows past the chunk's count repeat its first row: every load is issued
-                        yraw[d][e][c] = *(const yvec_t *)((const char *)yrow[c] + oc * 2u);
+                        for (int c = 0; c < kChunk; ++c)  // rows past the chunk's count repeat its first row: every load is issued
+                            yraw[d][e][c] = *(const yvec_t *)((const char *)yrow[c] + oc * 2u);
+                    }
                 }
             }
         };
@@ -468,27 +481,28 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                         for (int e = 0; e < C::EU; ++e) {
                             const int o = lo + (e * C::NT + tid) * C::OPL;
                             if constexpr (C::MX) {
+                                // Operand order: the adapter's B rows are the "row" operand (lane l supplies
+                                // output l of the wave's 64), h the "column" operand (lane l supplies chunk row
+                                // l%4), so accumulator register i of lane l is output 4*(l/4) + i of row l%4.
                                 f32x4_t d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                                 for (int s4 = 0; s4 < RP / 4; ++s4) {
                                     const uint4 bq = braw[d][e][s4 / 2];
                                     const s16x4_t bop = __builtin_bit_cast(s16x4_t, (s4 & 1) ? make_uint2(bq.z, bq.w) : make_uint2(bq.x, bq.y));
-                                    d0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ahi[s4], bop, d0, 0, 0, 0);
-                                    d1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(alo[s4], bop, d1, 0, 0, 0);
+                                    d0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(bop, ahi[s4], d0, 0, 0, 0);
+                                    d1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(bop, alo[s4], d1, 0, 0, 0);
                                 }
-#pragma unroll
-                                for (int c = 0; c < kChunk; ++c) {
-                                    if (c < cnt && o < out1 && rank > 0) {        // empty slot: rows stay untouched
-                                        if (to_parts) {
-                                            st_quiet((char *)prow[c] + (uint32_t)o * 4u, __float_as_uint(wrow[c] * (d0[c] + d1[c])));
-                                        } else {
-                                            float yf[1];
-                                            y_unpack(yraw[d][e][c], yf);
-                                            yf[0] += d0[c] + d1[c];
-                                            yvec_t out;
-                                            y_pack(yf, out);
-                                            st_quiet((char *)yrow[c] + (uint32_t)o * 2u, out);
-                                        }
+                                const int ob = o & ~3;                            // first output of this lane's block
+                                if (r4 < cnt && ob < out1 && rank > 0) {          // empty slot: rows stay untouched
+                                    if (to_parts) {
+                                        st_quiet(p_lane + (uint32_t)ob * 4u,
+                                                 make_uint4(__float_as_uint(w_lane * (d0[0] + d1[0])), __float_as_uint(w_lane * (d0[1] + d1[1])),
+                                                            __float_as_uint(w_lane * (d0[2] + d1[2])), __float_as_uint(w_lane * (d0[3] + d1[3]))));
+                                    } else {
+                                        const uint2 yv = yq[d][e];
+                                        st_quiet(y_lane + (uint32_t)ob * 2u,
+                                                 make_uint2(pack_bf2(bf_lo(yv.x) + (d0[0] + d1[0]), bf_hi(yv.x) + (d0[1] + d1[1])),
+                                                            pack_bf2(bf_lo(yv.y) + (d0[2] + d1[2]), bf_hi(yv.y) + (d0[3] + d1[3]))));
                                     }
                                 }
                             } else {
