@@ -45,6 +45,9 @@ struct RowsCfg {
     // works on 16 independent 4x4 blocks, lane l = (block l/4, column l%4), so lane l's result
     // column is its own output and its four accumulator registers are the chunk's four rows.
     static constexpr bool MX = (RP == 8 || RP == 16) && kChunk == 4;
+    // Every row of x (and y) of a chunk is loaded whatever its count: fewer, emptier loads lost time in
+    // the 8-wave decode kernels of rank 8 / 16 and won it everywhere else (load issue is what they save).
+    static constexpr bool ALLROWS = MX && NW == 8;
     static_assert(JG * KS == NW && EU >= 1, "wave layout");
 };
 
@@ -289,8 +292,8 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                         yq[d][e] = *(const uint2 *)(y_lane + (oc & ~3u) * 2u);
                     } else {
 #pragma unroll
-                        for (int c = 0; c < kChunk; ++c)  // rows past the chunk's count repeat its first row: every load is issued
-                            yraw[d][e][c] = *(const yvec_t *)((const char *)yrow[c] + oc * 2u);
+                        for (int c = 0; c < kChunk; ++c)  // rows past the chunk's count are not fetched
+                            if (C::ALLROWS || c == 0 || c < cnt) yraw[d][e][c] = *(const yvec_t *)((const char *)yrow[c] + oc * 2u);
                     }
                 }
             }
@@ -334,8 +337,12 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
             }
 #pragma unroll
             for (int jj = 0; jj < C::JPW; ++jj) av[jj] = *(const uint4 *)(Ag + (size_t)a_row_off[jj] + ub);
+            // Rows past the chunk's count are not fetched, except in the 8-wave matrix-core kernels (ALLROWS;
+            // measured).  The count is wave-uniform and the tile loads that follow are unconditional, so
+            // the waits for these loads keep a known number in flight.
 #pragma unroll
-            for (int c = 0; c < kChunk; ++c) xv[c] = *(const uint4 *)((const char *)xp[c] + ub);
+            for (int c = 0; c < kChunk; ++c)
+                if (C::ALLROWS || c == 0 || c < cnt) xv[c] = *(const uint4 *)((const char *)xp[c] + ub);
         };
         // Tiles 1 .. DEPTH-1 of the expand are requested once the shrink's operands have been consumed
         // (their registers are free then) and travel while the partial sums are reduced and traded.
