@@ -586,6 +586,25 @@ def test_c4_moe_packed_sampled(M, oracle):
     check_moe(M, oracle, c, site, pairs=pairs)
 
 
+def test_c4_gate_up_one_launch_sampled(M, oracle):
+    """The benchmark's launch configuration of c4: gate and up in one launch over one route plan, at
+    full size, sampled pairs against the oracle."""
+    cg, cu = W.c4_moe_packed("gate"), W.c4_moe_packed("up")
+    sites = [moe_site(M, cg), moe_site(M, cu)]
+    plan = M.Plan(cg.T * cg.K, cg.n_slots * cg.E)
+    M.moe_plan_route(plan, torch.from_numpy(cg.topk).cuda(), torch.from_numpy(cg.token_slot).cuda(), cg.n_slots, cg.E)
+    x = P.dev_bf16(cg.x)
+    ys = [P.dev_bf16(cg.y0), P.dev_bf16(cu.y0)]
+    M.moe_lora_apply_multi(sites, plan, [x, x], ys)
+    torch.cuda.synchronize()
+    sel = np.sort(W.rng(7).permutation(cg.T * cg.K)[:384])
+    tok = sel // cg.K
+    for c, y in zip((cg, cu), ys):
+        sub_topk = c.topk.reshape(-1)[sel].reshape(-1, 1)
+        ref = oracle.apply_moe(cg.x[tok], c.y0[sel], c.A, c.B, c.rank, c.alpha, sub_topk, c.token_slot[tok])
+        P.check_close(P.host_bits(y)[sel], ref, c.name)
+
+
 # ------------------------------------------------------------------ ABI errors on the device box
 
 def test_catalog_traffic_through_the_residency_manager(M, oracle):
