@@ -1,11 +1,11 @@
-// Vector-ALU LoRA apply over plan chunks: decode (gather by slot index), packed MoE pairs and
-// small-rank segments.  A chunk is up to MLORA_CHUNK rows that share one adapter (and expert):
+// LoRA apply over plan chunks: decode (gather by slot index), packed MoE pairs and small-rank
+// segments.  Vector ALU, with the expand of padded ranks 8 and 16 on 4x4x4 matrix-core blocks.  A chunk is up to MLORA_CHUNK rows that share one adapter (and expert):
 //   shrink  h[c][j] = sum_i x[row_c, i] * A[j, i]   -- wavefront reduction, packed-bf16 dot2,
 //                                                      fp32 accumulate
 //   scale   h *= alpha / r
 //   expand  y[row_c, o] = bf16_rne(float(y[row_c, o]) + sum_j h[c][j] * B[o, j])   in place
 // Adapter rows beyond the slot's true rank are zero in the tables (padded slots), so the loops
-// run to the padded rank.
+// run to the padded rank; big launches over tables with padded slots skip the reads of those rows of A.
 //
 // These launches last microseconds, so what matters is how few dependent memory round trips a
 // workgroup makes: every work item issues its loads in one flight.  Two shapes of launch:

@@ -1,7 +1,8 @@
 // Rank-64 segmented (prefill) LoRA apply on the gfx950 matrix cores, as two launches.
 //
 // All rows of a segment use one adapter (a request's prompt is one contiguous run), so both halves
-// are dense contractions with v_mfma_f32_32x32x16_bf16:
+// are dense contractions on the matrix cores (v_mfma_f32_32x32x16_bf16 in the shrink,
+// v_mfma_f32_16x16x32_bf16 in the expand):
 //
 //   shrink  hp[j][64 rows x 64]  = X[64 rows x k-slice j] * A_s^T[k-slice j x 64]
 //           A workgroup owns a tile of up to 64 consecutive rows of one segment and one k-slice of
