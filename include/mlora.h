@@ -21,8 +21,10 @@
  *     ldx / ldy are row strides in elements (multiples of 8).
  *   - A slot index of -1, an index outside [0, n_slots), or a slot that holds no adapter
  *     (never uploaded, or evicted) leaves the row bit-identical.
- *   - A site's tables may be read by applies on one stream at a time; uploading into a slot
- *     that an unfinished apply on another stream reads is a caller error.
+ *   - A site serves applies on one stream at a time: its scratch (private plan, exchange words,
+ *     prefill partial sums) is shared by all of its calls, so two applies of one site that overlap
+ *     on different streams race; uploading into a slot that an unfinished apply on another stream
+ *     reads is a caller error.  Different sites are independent.
  */
 #ifndef MLORA_H
 #define MLORA_H
