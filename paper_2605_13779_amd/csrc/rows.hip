@@ -323,10 +323,12 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         auto load_flight = [&](int f, int ul, int uh) {
             const int u = f + ks * 64 + lane;
             const uint32_t ub = (uint32_t)(u < uh ? u : ul) * 16u;
-            if constexpr (XCH) {
-                // A k-slice of an exchange item is often narrower than the workgroup (64 units = one
-                // wave): the waves past its end issue nothing.  A CU accepts one 64-lane 16-byte load
-                // per 16 cycles, and their clamped loads took more of that than the item's real bytes.
+            // The waves past the end of the range issue nothing (a k-slice of an exchange item is often
+            // one wave wide, and the last flight of a long shrink is partial).  A CU accepts one 64-lane
+            // 16-byte load per 16 cycles whatever the lanes fetch, and clamped loads took more of that
+            // than the item's real bytes.  (Not in the 4-wave kernels: their ranges fill the workgroup,
+            // and the branch alone measured slower there.)
+            if constexpr (XCH || NW == 8) {
                 if (__builtin_amdgcn_readfirstlane(f + ks * 64) >= uh) {
 #pragma unroll
                     for (int jj = 0; jj < C::JPW; ++jj) av[jj] = make_uint4(0, 0, 0, 0);
