@@ -3,8 +3,9 @@
 
 A "step" is one pass of the whole hot path over one batch of the headline workload: the
 4B-dense-like decode layer (256 tokens, q/k/v/o/gate/up/down, 64 resident rank-16 slots, Zipf
-slot popularity): one batch plan + the seven fused shrink->expand->add applies, issued as four
-launches (q|k|v and gate|up are independent of each other and share a launch).  Inputs are
+slot popularity): the batch plan + the seven fused shrink->expand->add applies, issued as four
+launches (q|k|v and gate|up are independent of each other and share a launch; the q|k|v launch
+builds the plan inside itself and leaves it for the others).  Inputs are
 resident in HBM before the timed region.  Steps cycle over several distinct "layers" (own slot
 tables, x and y) so that no step finds its operands in the 256 MB last-level cache, as in a real
 forward pass over 36 layers.  The timed loop is a HIP graph replay.
@@ -106,10 +107,13 @@ def bench_c2(M, W, steps, warmup, n_layers=8, eager=True):
 
     def layer_step(i, with_plan=True, only_grouped=False):
         plan, sites = layers[i % n_layers]
-        if with_plan:
-            M.lora_plan_decode(plan, ts, 64)
-        for grp in groups:
+        for gi, grp in enumerate(groups):
             if only_grouped and len(grp) == 1:
+                continue
+            if with_plan and gi == 0:
+                # the step's first launch groups the batch by slot itself and leaves the plan for the others
+                M.lora_plan_apply_decode_multi([sites[k][0] for k in grp], plan, ts, 64,
+                                               [sites[k][1] for k in grp], [sites[k][2] for k in grp])
                 continue
             if len(grp) == 1:
                 site, x, y = sites[grp[0]]

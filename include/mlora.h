@@ -153,6 +153,19 @@ int32_t lora_apply_decode_planned(mlora_site *site, const mlora_plan *plan,
 int32_t lora_apply_decode_multi(mlora_site *const *sites, int32_t n_sites, const mlora_plan *plan,
                                 const void *const *xs, const int64_t *ldxs,
                                 void *const *ys, const int64_t *ldys, void *stream);
+/* lora_plan_decode followed by lora_apply_decode_multi, for the first sites of a decode step (q/k/v
+ * of the first layer): the batch is grouped by slot (Section 4: the requests of one decoding step
+ * name at most 64 distinct resident adapters) and the plan is left in `plan` for every later
+ * planned apply of the step.  For batches of up to 256 rows the leading sites that can share a
+ * launch build the plan inside that launch (every workgroup sorts the batch's keys itself instead
+ * of waiting for a planner launch; workgroup 0 writes the plan out), which saves the planner
+ * launch; otherwise this is exactly the two calls.  Plan and results are those of the two calls,
+ * bit for bit.  Arguments and errors as for those two calls. */
+int32_t lora_plan_apply_decode_multi(mlora_site *const *sites, int32_t n_sites, mlora_plan *plan,
+                                     const int32_t *token_slot, int32_t T, int32_t n_slots,
+                                     const mlora_site *ready_from,
+                                     const void *const *xs, const int64_t *ldxs,
+                                     void *const *ys, const int64_t *ldys, void *stream);
 
 /* Route index build for packed MoE LoRA (per-expert LoRA tensors are keyed by expert id,
  * Section 3.4): pair p = t*K + k has key = token_slot[t] * n_experts + topk_ids[t, k]; pairs

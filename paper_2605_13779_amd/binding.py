@@ -45,6 +45,7 @@ SIGNATURES = {
     "lora_plan_decode": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
     "lora_apply_decode_planned": (_i32, [_vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "lora_apply_decode_multi": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "lora_plan_apply_decode_multi": (_i32, [_vp, _i32, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_plan_route": (_i32, [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]),
     "moe_lora_apply_planned": (_i32, [_vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "moe_lora_apply_multi": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -303,6 +304,20 @@ def _apply_multi(name, sites, plan, xs, ys, stream):
 
 def lora_apply_decode_multi(sites, plan, xs, ys, stream=None):
     _apply_multi("lora_apply_decode_multi", sites, plan, xs, ys, stream)
+
+
+def lora_plan_apply_decode_multi(sites, plan, token_slot, n_slots, xs, ys, ready_from=None, stream=None):
+    n = len(sites)
+    assert len(xs) == n and len(ys) == n
+    rows = [(_rows(x), _rows(y)) for x, y in zip(xs, ys)]
+    hs = (_vp * n)(*[s.handle for s in sites])
+    px = (_vp * n)(*[r[0][0] for r in rows])
+    lx = (_i64 * n)(*[r[0][1] for r in rows])
+    py = (_vp * n)(*[r[1][0] for r in rows])
+    ly = (_i64 * n)(*[r[1][1] for r in rows])
+    _check("lora_plan_apply_decode_multi", load_library().lora_plan_apply_decode_multi(
+        hs, n, plan.handle, _dev_ptr(token_slot, torch.int32), token_slot.shape[0], n_slots,
+        ready_from.handle if ready_from is not None else None, px, lx, py, ly, _stream(stream)))
 
 
 def moe_lora_apply_multi(sites, plan, xs, ys, stream=None):

@@ -714,6 +714,57 @@ int32_t lora_apply_decode_multi(mlora_site *const *sites, int32_t n_sites, const
     return apply_multi_impl(sites, n_sites, plan, xs, ldxs, ys, ldys, (hipStream_t)stream);
 }
 
+int32_t lora_plan_apply_decode_multi(mlora_site *const *sites, int32_t n_sites, mlora_plan *plan,
+                                     const int32_t *token_slot, int32_t T, int32_t n_slots, const mlora_site *ready_from,
+                                     const void *const *xs, const int64_t *ldxs, void *const *ys, const int64_t *ldys,
+                                     void *stream)
+{
+    if (!sites || !plan || !xs || !ldxs || !ys || !ldys || n_sites < 1 || T < 0 || n_slots <= 0) return MLORA_E_INVALID;
+    if (T > 0 && !token_slot) return MLORA_E_INVALID;
+    if (ready_from && ready_from->d.n_slots < n_slots) return MLORA_E_SLOT;
+    if (T > plan->max_items || n_slots > plan->n_keys) return MLORA_E_UNSUPPORTED;
+    for (int32_t k = 0; k < n_sites; ++k) {
+        if (!sites[k]) return MLORA_E_INVALID;
+        if (sites[k]->d.n_experts > 0) return MLORA_E_UNSUPPORTED;
+        if (sites[k]->d.device != sites[0]->d.device || sites[k]->d.device != plan->device) return MLORA_E_INVALID;
+        if (n_slots > sites[k]->d.n_slots) return MLORA_E_SLOT;
+        int32_t rc = check_xy(sites[k], xs[k], ldxs[k], ys[k], ldys[k]);
+        if (rc) return rc;
+    }
+    DeviceGuard g(plan->device);
+    if (!g.good) return MLORA_E_HIP;
+    hipStream_t st = (hipStream_t)stream;
+    if (T == 0) { plan->items = 0; plan->grid_chunks = 0; plan->moe = false; return MLORA_OK; }
+    const int32_t *ready_rank = ready_from ? ready_from->rank : nullptr;
+    // the leading sites that can share a launch plan inside it; everything else as two calls would do
+    RowsArgs grp[kMaxMulti];
+    int32_t n = 0;
+    if (T <= rows_local_plan_rows() && n_slots <= rows_local_plan_slots() && max_chunks(T, n_slots) <= rows_local_plan_rows() &&
+        !tuning("plan_general") &&
+        !tuning("plan_separate")) {
+        while (n < n_sites && n < kMaxMulti) {
+            RowsArgs a = rows_args(sites[n], xs[n], ldxs[n], ys[n], ldys[n]);
+            a.chunks = plan->pv.chunks; a.top_k = 1; a.grid_chunks = (int32_t)max_chunks(T, n_slots);
+            if (rows_group_waves(a) != 8 || (n > 0 && a.r_pad != grp[0].r_pad)) {
+                if (n == 0 && rows_plans_alone(a)) grp[n++] = a;       // a launch of its own, planned inside
+                break;
+            }
+            grp[n++] = a;
+        }
+        if (n == 1 && !rows_plans_alone(grp[0])) n = 0;
+    }
+    if (n == 0) {
+        int32_t rc = plan_decode_impl(plan, token_slot, T, n_slots, ready_rank, st);
+        if (rc) return rc;
+        return apply_multi_impl(sites, n_sites, plan, xs, ldxs, ys, ldys, st);
+    }
+    plan->items = T; plan->top_k = 1; plan->n_experts = 1; plan->n_slots = n_slots; plan->moe = false;
+    plan->grid_chunks = (int32_t)max_chunks(T, n_slots);
+    if (!ok(launch_rows_multi_plan(grp, n, plan->pv, token_slot, T, n_slots, ready_rank, st))) return MLORA_E_HIP;
+    if (n == n_sites) return MLORA_OK;
+    return apply_multi_impl(sites + n, n_sites - n, plan, xs + n, ldxs + n, ys + n, ldys + n, st);
+}
+
 int32_t moe_plan_route(mlora_plan *plan, const int32_t *topk_ids, const int32_t *token_slot, int32_t T, int32_t K,
                        int32_t n_slots, int32_t n_experts, const mlora_site *ready_from,
                        int32_t *out_sorted_pair, int32_t *out_group_off, void *stream)

@@ -80,6 +80,11 @@ struct RowsArgs {
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st);
 constexpr int kMaxMulti = 4;     // sites per grouped launch
 int rows_group_waves(const RowsArgs &a);
+bool rows_plans_alone(const RowsArgs &a);
+int rows_local_plan_rows();
+int rows_local_plan_slots();
+hipError_t launch_rows_multi_plan(const RowsArgs *sites, int n, const PlanView &pv, const int32_t *token_slot, int T,
+                                  int n_slots, const int32_t *ready_rank, hipStream_t st);
 hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st);
 hipError_t launch_moe_combine(uint16_t *y, int64_t ldy, const float *parts, int64_t ldo, const int32_t *token_slot,
                               const int32_t *rank, int32_t n_slots, int32_t T, int32_t K, int32_t d_out, hipStream_t st);

@@ -3,7 +3,7 @@
 // Dense decode (at most 64 distinct adapters share one decoding step, Section 4 cache-tier
 // table) and the packed-MoE route index build (per-expert LoRA tensors keyed by expert id,
 // Section 3.4).  All integer work; every output is uniquely determined by the inputs.
-#include "internal.h"
+#include "plan_device.h"
 
 namespace mlora {
 
@@ -47,81 +47,6 @@ hipError_t launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t st)
 // at distance < 64 stay inside a wave (DPP / swizzle), only the few longer ones go through LDS.
 // Group starts and chunk numbers then come from two scans, and the chunk records are written.
 // ---------------------------------------------------------------------------------------------
-constexpr int kSortMax = 1024;
-
-template <int D>
-__device__ __forceinline__ uint32_t lane_xor_u32(uint32_t x)
-{
-    int r;
-    if constexpr (D == 1) r = __builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xf, 0xf, true);
-    else if constexpr (D == 2) r = __builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xf, 0xf, true);
-    else if constexpr (D == 4) {
-        r = __builtin_amdgcn_update_dpp(0, (int)x, 0x104, 0xf, 0x5, false);
-        r = __builtin_amdgcn_update_dpp(r, (int)x, 0x114, 0xf, 0xa, false);
-    } else if constexpr (D == 8) r = __builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xf, 0xf, true);
-    else if constexpr (D == 16) r = __builtin_amdgcn_ds_swizzle((int)x, 0x401F);
-    else r = __shfl_xor((int)x, 32, 64);
-    return (uint32_t)r;
-}
-
-// One compare-exchange step of the network for the key held by thread i (partner i ^ J, merge size K).
-template <int K, int J>
-__device__ __forceinline__ void bitonic_step(uint32_t &ks, uint32_t &kt, int i, uint2 *xch)
-{
-    uint32_t ps, pt;
-    if constexpr (J < 64) {
-        ps = lane_xor_u32<J>(ks);
-        pt = lane_xor_u32<J>(kt);
-    } else {
-        xch[i] = make_uint2(ks, kt);
-        __syncthreads();
-        const uint2 p = xch[i ^ J];
-        __syncthreads();
-        ps = p.x; pt = p.y;
-    }
-    const bool self_less = ks < ps || (ks == ps && kt < pt);
-    const bool up = (i & K) == 0, lower = (i & J) == 0;
-    const bool keep_self = (lower == up) == self_less;      // lower lane of an ascending pair keeps the smaller key
-    if (!keep_self) { ks = ps; kt = pt; }
-}
-
-template <int K, int J>
-struct BitonicMerge {
-    static __device__ __forceinline__ void run(uint32_t &ks, uint32_t &kt, int i, uint2 *xch)
-    {
-        bitonic_step<K, J>(ks, kt, i, xch);
-        if constexpr (J > 1) BitonicMerge<K, J / 2>::run(ks, kt, i, xch);
-    }
-};
-
-template <int K>
-struct BitonicSort {
-    static __device__ __forceinline__ void run(uint32_t &ks, uint32_t &kt, int i, int N, uint2 *xch)
-    {
-        if constexpr (K > 2) BitonicSort<K / 2>::run(ks, kt, i, N, xch);
-        if (K <= N) BitonicMerge<K, K / 2>::run(ks, kt, i, xch);      // N is uniform over the workgroup
-    }
-};
-
-// Inclusive scan over the workgroup (one value per thread); IS_MAX selects max instead of plus.
-template <bool IS_MAX>
-__device__ __forceinline__ int block_scan(int v, int tid, int nw, int32_t *wave_tot)
-{
-    const int lane = tid & 63, w = tid >> 6;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int o = __shfl_up(v, d, 64);
-        if (lane >= d) v = IS_MAX ? max(v, o) : v + o;
-    }
-    if (lane == 63) wave_tot[w] = v;
-    __syncthreads();
-    int base = 0;
-    for (int k = 0; k < w; ++k) base = IS_MAX ? max(base, wave_tot[k]) : base + wave_tot[k];
-    __syncthreads();
-    (void)nw;
-    return IS_MAX ? max(v, base) : v + base;
-}
-
 __global__ __launch_bounds__(1024)
 void plan_dense_small_kernel(PlanView pv, const int32_t *__restrict__ token_slot, int T, int n_slots,
                              const int32_t *__restrict__ ready_rank, int rec_bound, int N)

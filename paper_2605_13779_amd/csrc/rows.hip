@@ -20,7 +20,7 @@
 //                        exchange carries value and launch tag in one 64-bit store, so no fences
 //                        are needed; a part whose partners have not published after a bounded
 //                        number of polls takes its item again on its own, with the whole shrink.
-#include "internal.h"
+#include "plan_device.h"
 
 namespace mlora {
 
@@ -154,7 +154,7 @@ __device__ __forceinline__ void y_pack(const float *f, uint4 &r)
 // Work of workgroup `wg` out of `n_wg` on one site (one launch may cover several sites).
 // XCH: the kernel can pass partial shrink results between workgroups (a.mode 2).
 template <int RP, int NW, bool XCH>
-__device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const int n_wg)
+__device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const int n_wg, const int32_t *lrec = nullptr)
 {
     using C = RowsCfg<RP, NW>;
     typedef typename YVec<C::OPL>::T yvec_t;
@@ -222,7 +222,8 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
             if (chunk >= a.grid_chunks) continue;
         }
         // The whole record is fetched before its count is looked at (one round trip, not two).
-        const int4 *rec = (const int4 *)(a.chunks + (int64_t)chunk * kRec);
+        // (a launch that planned for itself has the records in LDS)
+        const int4 *rec = lrec ? (const int4 *)(lrec + chunk * kRec) : (const int4 *)(a.chunks + (int64_t)chunk * kRec);
         int4 r0 = rec[0], r1 = rec[1];
         asm volatile("" : "+v"(r0.x), "+v"(r0.y), "+v"(r1.x), "+v"(r1.y), "+v"(r1.z), "+v"(r1.w));
         const int key = __builtin_amdgcn_readfirstlane(r0.x), cnt = __builtin_amdgcn_readfirstlane(r0.y);
@@ -603,6 +604,34 @@ void rows_multi_kernel(const MultiArgs m)
     rows_body<RP, NW, XCH>(m.site[s], b - m.first[s], m.first[s + 1] - m.first[s]);
 }
 
+// The first launch of a decode step can plan for itself: every workgroup sorts the batch's
+// (slot, row) keys in LDS (what the one-workgroup planner kernel does, a microsecond of work) instead
+// of waiting for a planner launch and then fetching its chunk record; workgroup 0 also leaves the
+// plan in global memory for the launches that follow.  Batches of up to kLocalPlanRows rows over up
+// to kLocalPlanSlots slots.
+constexpr int kLocalPlanRows = 256;   // more rows mean more distinct slots per wave, and every workgroup pays for them
+struct PlanLocalArgs {
+    const int32_t *token_slot;
+    const int32_t *ready_rank;
+    int32_t T, n_slots, rec_bound;
+    PlanView pv;
+};
+
+template <int RP, int NW, bool XCH>
+__global__ __launch_bounds__(NW * 64, (NW >= 8 && RP <= 16) ? 4 : 1)
+void rows_multi_plan_kernel(const MultiArgs m, const PlanLocalArgs pl)
+{
+    __shared__ PlanLocalLds p_lds;
+    __shared__ __attribute__((aligned(16))) int32_t p_rec[kLocalPlanRows * kRec];
+    const int b = (int)blockIdx.x;
+    plan_dense_local(pl.token_slot, pl.T, pl.n_slots, pl.ready_rank, pl.rec_bound, (int)threadIdx.x, NW * 64,
+                     p_lds, p_rec, b == 0, pl.pv);
+    int s = 0;
+#pragma unroll
+    for (int k = 1; k < kMaxMulti; ++k) s += (k < m.n && b >= m.first[k]) ? 1 : 0;
+    rows_body<RP, NW, XCH>(m.site[s], b - m.first[s], m.first[s + 1] - m.first[s], p_rec);
+}
+
 template <int RP, int NW, bool XCH>
 static int rows_capacity()
 {
@@ -711,7 +740,7 @@ static hipError_t launch_nw(const RowsArgs &a, hipStream_t st)
 }
 
 template <int RP, int NW>
-static hipError_t launch_multi_rp(const RowsArgs *sites, int n, hipStream_t st)
+static hipError_t launch_multi_rp(const RowsArgs *sites, int n, hipStream_t st, const PlanLocalArgs *pl = nullptr)
 {
     const int cap = rows_capacity<RP, NW, true>();
     if (cap <= 0) return hipErrorUnknown;
@@ -726,12 +755,21 @@ static hipError_t launch_multi_rp(const RowsArgs *sites, int n, hipStream_t st)
     bool any_x = false;
     for (int k = 0; k < n; ++k) {
         m.site[k] = sites[k];
-        set_parts(m.site[k], (int)(chunk_bytes(sites[k]) / per_item + 0.5), exchange);
+        // (one site alone gets the parts its own launch would get, so that the results are the same bits)
+        set_parts(m.site[k], n == 1 ? items_target(cap) / sites[0].grid_chunks : (int)(chunk_bytes(sites[k]) / per_item + 0.5), exchange);
         m.site[k].rank_bound = use_rank_bound(m.site[k], cap);
         any_x = any_x || m.site[k].mode == 2;
         m.first[k + 1] = m.first[k] + fused_grid(m.site[k]);
     }
     for (int k = n; k < kMaxMulti; ++k) { m.site[k] = m.site[0]; m.first[k + 1] = m.first[n]; }
+    if constexpr (NW == 8) {
+        if (pl) {
+            if (any_x) rows_multi_plan_kernel<RP, NW, true><<<dim3((unsigned)m.first[n]), dim3(NW * 64), 0, st>>>(m, *pl);
+            else rows_multi_plan_kernel<RP, NW, false><<<dim3((unsigned)m.first[n]), dim3(NW * 64), 0, st>>>(m, *pl);
+            return hipGetLastError();
+        }
+    }
+    if (pl) return hipErrorInvalidValue;
     if (any_x) rows_multi_kernel<RP, NW, true><<<dim3((unsigned)m.first[n]), dim3(NW * 64), 0, st>>>(m);
     else rows_multi_kernel<RP, NW, false><<<dim3((unsigned)m.first[n]), dim3(NW * 64), 0, st>>>(m);
     return hipGetLastError();
@@ -759,6 +797,44 @@ hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st)
     if (sites[0].grid_chunks <= 0) return hipSuccess;
     if (nw == 8) return sites[0].r_pad == 8 ? launch_multi_rp<8, 8>(sites, n, st) : launch_multi_rp<16, 8>(sites, n, st);
     return sites[0].r_pad == 8 ? launch_multi_rp<8, 4>(sites, n, st) : launch_multi_rp<16, 4>(sites, n, st);
+}
+
+// A dense site whose own launch would run the 8-wave kernel of rank 1, 8 or 16 (the instantiated
+// self-planning kernels) can plan inside that launch.
+bool rows_plans_alone(const RowsArgs &a)
+{
+    if ((a.r_pad != 1 && a.r_pad != 8 && a.r_pad != 16) || a.n_experts != 1 || a.out_f32 || tuning("rows_waves")) return false;
+    const int U = a.d_in >> 3;
+    const int flu = a.r_pad == 1 ? RowsCfg<1, 8>::FLU : (a.r_pad == 8 ? RowsCfg<8, 8>::FLU : RowsCfg<16, 8>::FLU);
+    return U >= flu * 3 / 4;
+}
+
+// Plans the dense batch inside the launch of `sites` (8-wave sites of one rank, see rows_group_waves)
+// and leaves the plan in pv.  T <= rows_local_plan_rows().
+int rows_local_plan_rows() { return kLocalPlanRows; }
+int rows_local_plan_slots() { return kLocalPlanSlots; }
+
+hipError_t launch_rows_multi_plan(const RowsArgs *sites, int n, const PlanView &pv, const int32_t *token_slot, int T,
+                                  int n_slots, const int32_t *ready_rank, hipStream_t st)
+{
+    if (n < 1 || n > kMaxMulti || T < 1 || T > kLocalPlanRows || n_slots > kLocalPlanSlots) return hipErrorInvalidValue;
+    if (n == 1) {
+        if (!rows_plans_alone(sites[0])) return hipErrorInvalidValue;
+    } else {
+        for (int k = 0; k < n; ++k)
+            if (sites[k].r_pad != sites[0].r_pad || rows_group_waves(sites[k]) != 8) return hipErrorInvalidValue;
+    }
+    PlanLocalArgs pl;
+    pl.token_slot = token_slot; pl.ready_rank = ready_rank; pl.T = T; pl.n_slots = n_slots;
+    pl.rec_bound = (int)max_chunks(T, n_slots);
+    if (pl.rec_bound > kLocalPlanRows) return hipErrorInvalidValue;
+    pl.pv = pv;
+    switch (sites[0].r_pad) {
+        case 1:  return launch_multi_rp<1, 8>(sites, n, st, &pl);
+        case 8:  return launch_multi_rp<8, 8>(sites, n, st, &pl);
+        case 16: return launch_multi_rp<16, 8>(sites, n, st, &pl);
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st)

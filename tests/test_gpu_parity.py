@@ -219,6 +219,87 @@ def test_decode_parts_when_partners_never_answer(M, oracle):
         M.set_tuning("rows_poll_limit", 0)
 
 
+def _plan_words(plan, max_items, n_keys):
+    """hdr, sorted and chunk records of a plan buffer (layout: 8 header words, three tables of
+    n_keys + 1, four of max_items, then the records)."""
+    w = plan.buf.view(torch.int32).cpu().numpy()
+    off_sorted = 8 + 3 * (n_keys + 1) + 3 * max_items
+    return w[:2].copy(), w[off_sorted:off_sorted + max_items].copy(), w[off_sorted + max_items:].copy()
+
+
+@pytest.mark.parametrize("T,S", [(61, 5), (256, 64), (1, 3), (200, 64), (300, 7)])
+def test_decode_step_that_plans_inside_its_first_launch(M, oracle, T, S):
+    """lora_plan_apply_decode_multi = lora_plan_decode + lora_apply_decode_multi, bit for bit, in the
+    results and in the plan it leaves behind (which a later planned apply uses); 300 rows are more
+    than a launch plans for itself and take the two-call path, as does a first site that cannot
+    share a launch."""
+    shapes = [(2304, 264, 16), (2304, 1032, 16), (2304, 520, 16), (128, 72, 16)]
+    slots = W.rng(90 + T).integers(-1, S, size=T).astype(np.int32)
+    cases = [W.dense_case(f"pl{i}", 3200 + i, T, di, do, S, r, 32.0, token_slot=slots, ranks=[16 if k % 5 else 0 for k in range(S)] if S > 3 else None,
+                          std_a=0.05, std_b=0.05) for i, (di, do, r) in enumerate(shapes)]
+    sites = [dense_site(M, c) for c in cases]
+    ts = torch.from_numpy(slots).cuda()
+    for order in ([0, 1, 2, 3], [3, 0, 1]):
+        cs, ss = [cases[k] for k in order], [sites[k] for k in order]
+        xs = [P.dev_bf16(c.x) for c in cs]
+        ya, yb = [P.dev_bf16(c.y0) for c in cs], [P.dev_bf16(c.y0) for c in cs]
+        pa, pb = M.Plan(max(T, 1), S), M.Plan(max(T, 1), S)
+        pa.buf.zero_(); pb.buf.zero_()
+        M.lora_plan_decode(pa, ts, S, ready_from=ss[0])
+        M.lora_apply_decode_multi(ss, pa, xs, ya)
+        M.lora_plan_apply_decode_multi(ss, pb, ts, S, xs, yb, ready_from=ss[0])
+        torch.cuda.synchronize()
+        for c, a, b in zip(cs, ya, yb):
+            assert torch.equal(a, b), c.name
+            ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+            P.check_close(P.host_bits(b), ref, c.name)
+        (ha, sa, ra), (hb, sb, rb) = _plan_words(pa, max(T, 1), S), _plan_words(pb, max(T, 1), S)
+        assert np.array_equal(ha, hb), (ha, hb)
+        n_chunks, n_rows = int(ha[0]), int(ha[1])
+        assert np.array_equal(sa[:n_rows], sb[:n_rows])
+        ra, rb = ra[:8 * ((T + 3 * min(S, T)) // 4)].reshape(-1, 8), rb[:8 * ((T + 3 * min(S, T)) // 4)].reshape(-1, 8)
+        assert np.array_equal(ra[:, 1], rb[:, 1]) and np.all(ra[n_chunks:, 1] == 0)
+        for k in range(n_chunks):
+            assert np.array_equal(ra[k, :3], rb[k, :3]) and np.array_equal(ra[k, 4:4 + ra[k, 1]], rb[k, 4:4 + rb[k, 1]])
+        # the plan that the fused launch left behind drives a later planned apply
+        y2 = P.dev_bf16(cs[0].y0)
+        M.lora_apply_decode_planned(ss[0], pb, xs[0], y2)
+        torch.cuda.synchronize()
+        ref = oracle.apply_decode(cs[0].x, cs[0].y0, cs[0].A, cs[0].B, cs[0].rank, cs[0].alpha, cs[0].token_slot)
+        P.check_close(P.host_bits(y2), ref, "later apply")
+
+
+def test_single_site_plans_inside_its_launch(M, oracle):
+    """A rank-1 catalog site (every row its own slot, 1024 slots) and a rank-16 site on their own:
+    the launch plans for itself up to 256 rows and 1024 slots (more rows take the two calls); same
+    bits as plan + planned apply."""
+    for name, T, S, d_in, d_out, r in (("cat", 256, 1024, 4096, 264, 1), ("cat_ragged", 199, 700, 4096, 136, 1),
+                                       ("cat_two_calls", 333, 700, 4096, 136, 1), ("one16", 200, 40, 2304, 264, 16)):
+        slots = W.rng(95 + T).permutation(S)[:T].astype(np.int32) if r == 1 else W.rng(95 + T).integers(-1, S, size=T).astype(np.int32)
+        slots[::11] = -1
+        c = W.dense_case(name, 3300 + T, T, d_in, d_out, S, r, 2.0 * r, token_slot=slots, std_a=0.05, std_b=0.05)
+        site = dense_site(M, c)
+        ts = torch.from_numpy(slots).cuda()
+        x = P.dev_bf16(c.x)
+        ya, yb = P.dev_bf16(c.y0), P.dev_bf16(c.y0)
+        pa, pb = M.Plan(T, S), M.Plan(T, S)
+        pa.buf.zero_(); pb.buf.zero_()
+        M.lora_plan_decode(pa, ts, S)
+        M.lora_apply_decode_planned(site, pa, x, ya)
+        M.lora_plan_apply_decode_multi([site], pb, ts, S, [x], [yb])
+        torch.cuda.synchronize()
+        assert torch.equal(ya, yb), name
+        ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+        P.check_close(P.host_bits(yb), ref, name)
+        (ha, sa, ra), (hb, sb, rb) = _plan_words(pa, T, S), _plan_words(pb, T, S)
+        assert np.array_equal(ha, hb) and np.array_equal(sa[:ha[1]], sb[:hb[1]]), name
+        nrec = (T + 3 * min(S, T)) // 4
+        ra, rb = ra[:8 * nrec].reshape(-1, 8), rb[:8 * nrec].reshape(-1, 8)
+        assert np.array_equal(ra[:, 1], rb[:, 1]) and np.array_equal(ra[:ha[0], :3], rb[:hb[0], :3]), name
+        live = np.arange(4)[None, :] < ra[:ha[0], 1:2]
+        assert np.array_equal(ra[:ha[0], 4:][live], rb[:hb[0], 4:][live]), name
+
+
 def test_graph_replay_keeps_results_right(M, oracle):
     """A captured graph replays the same kernel arguments; the launches that exchange partial
     results between workgroups must still tell one replay from the next.  Inputs change between
