@@ -128,7 +128,7 @@ def bench_c2(M, W, steps, warmup, n_layers=8, eager=True):
 
     g_full = graph_of(all_layers)
     g_apply = graph_of(lambda: all_layers(False))
-    g_dom = graph_of(lambda: all_layers(False, True))      # the dominant kernel alone: the two grouped launches
+    g_dom = graph_of(lambda: all_layers(True, True))       # the dominant kernel alone: the two grouped launches, as in the step
     reps, wreps = max(1, steps // n_layers), max(1, warmup // n_layers)
     ms_full = time_region(g_full.replay, reps, wreps) / n_layers
     ms_apply = time_region(g_apply.replay, reps, wreps) / n_layers
@@ -489,9 +489,10 @@ def main():
     s = per["c2_layer"]
     achieved = head["dom_bytes_per_launch"] / (head["dom_us_per_launch"] * 1e-6) / 1e9
     roofline = {"bound": "hbm",
-                "kernel": "rows_multi_kernel<16,8,*> (the two grouped decode launches of a layer, averaged: shrink -> "
-                          "scale -> expand -> add; q|k|v with one item per chunk, gate|up with chunks cut into parts "
-                          "that trade k-slice sums)",
+                "kernel": "rows_multi_plan_kernel<16,8,false> + rows_multi_kernel<16,8,true> (the two grouped decode "
+                          "launches of a layer, averaged: shrink -> scale -> expand -> add; q|k|v with one item per "
+                          "chunk, building the batch plan inside the launch; gate|up with chunks cut into parts that "
+                          "trade k-slice sums)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(),
                 "alg_bytes_per_launch": head["dom_bytes_per_launch"],
