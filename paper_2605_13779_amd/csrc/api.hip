@@ -865,10 +865,25 @@ int32_t lora_apply_decode(mlora_site *s, const void *x, int64_t ldx, void *y, in
     // batches beyond the private plan are processed in slices; rows are independent
     for (int32_t t0 = 0; t0 < T; t0 += s->priv.max_items) {
         const int32_t n = T - t0 < s->priv.max_items ? T - t0 : s->priv.max_items;
+        const uint16_t *xs = (const uint16_t *)x + (int64_t)t0 * ldx;
+        uint16_t *ys = (uint16_t *)y + (int64_t)t0 * ldy;
+        // a small batch on a site whose launch can plan for itself needs no planner launch (same plan,
+        // same bits; see lora_plan_apply_decode_multi)
+        if (n <= rows_local_plan_rows() && s->d.n_slots <= rows_local_plan_slots() &&
+            max_chunks(n, s->d.n_slots) <= rows_local_plan_rows() && !tuning("plan_general") && !tuning("plan_separate")) {
+            mlora_plan *plan = &s->priv;
+            RowsArgs a = rows_args(s, xs, ldx, ys, ldy);
+            a.chunks = plan->pv.chunks; a.top_k = 1; a.grid_chunks = (int32_t)max_chunks(n, s->d.n_slots);
+            if (rows_plans_alone(a)) {
+                plan->items = n; plan->top_k = 1; plan->n_experts = 1; plan->n_slots = s->d.n_slots; plan->moe = false;
+                plan->grid_chunks = a.grid_chunks;
+                if (!ok(launch_rows_multi_plan(&a, 1, plan->pv, token_slot + t0, n, s->d.n_slots, s->rank, st))) return MLORA_E_HIP;
+                continue;
+            }
+        }
         rc = plan_decode_impl(&s->priv, token_slot + t0, n, s->d.n_slots, s->rank, st);
         if (rc) return rc;
-        rc = apply_planned_impl(s, &s->priv, (const uint16_t *)x + (int64_t)t0 * ldx, ldx,
-                                (uint16_t *)y + (int64_t)t0 * ldy, ldy, st);
+        rc = apply_planned_impl(s, &s->priv, xs, ldx, ys, ldy, st);
         if (rc) return rc;
     }
     return MLORA_OK;

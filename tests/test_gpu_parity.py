@@ -287,8 +287,10 @@ def test_single_site_plans_inside_its_launch(M, oracle):
         M.lora_plan_decode(pa, ts, S)
         M.lora_apply_decode_planned(site, pa, x, ya)
         M.lora_plan_apply_decode_multi([site], pb, ts, S, [x], [yb])
+        yc = P.dev_bf16(c.y0)
+        M.lora_apply_decode(site, x, yc, ts)               # the one-call form takes the same path on its private plan
         torch.cuda.synchronize()
-        assert torch.equal(ya, yb), name
+        assert torch.equal(ya, yb) and torch.equal(ya, yc), name
         ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
         P.check_close(P.host_bits(yb), ref, name)
         (ha, sa, ra), (hb, sb, rb) = _plan_words(pa, T, S), _plan_words(pb, T, S)
