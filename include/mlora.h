@@ -212,9 +212,9 @@ int32_t moe_lora_apply_down(mlora_site *site, const mlora_plan *plan, const void
 /* ---- the four calls of the problem statement ------------------------------------------------ */
 
 /* Decode: one token per row, gather-by-index.  Equivalent to lora_plan_decode on the site's
- * private scratch followed by lora_apply_decode_planned (for batches of up to 256 rows on sites of
- * rank 1, 8 or 16 with a wide d_in the plan is built inside the apply launch: same plan, same bits,
- * one launch).  T = 0 is MLORA_OK and launches nothing.
+ * private scratch followed by lora_apply_decode_planned (for batches of up to 256 rows on sites
+ * whose d_in is wide enough for the 8-wave kernel the plan is built inside the apply launch: same
+ * plan, same bits, one launch).  T = 0 is MLORA_OK and launches nothing.
  * Errors: MLORA_E_UNSUPPORTED on a MoE site, MLORA_E_SHAPE on bad strides. */
 int32_t lora_apply_decode(mlora_site *site, const void *x, int64_t ldx, void *y, int64_t ldy,
                           const int32_t *token_slot, int32_t T, void *stream);

@@ -799,14 +799,24 @@ hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st)
     return sites[0].r_pad == 8 ? launch_multi_rp<8, 4>(sites, n, st) : launch_multi_rp<16, 4>(sites, n, st);
 }
 
-// A dense site whose own launch would run the 8-wave kernel of rank 1, 8 or 16 (the instantiated
-// self-planning kernels) can plan inside that launch.
+// A dense site whose own launch would run the 8-wave kernel can plan inside that launch.
+template <int RP>
+static bool wide_enough_for_8_waves(int U) { return RP >= 64 || U >= RowsCfg<RP, 8>::FLU * 3 / 4; }
+
 bool rows_plans_alone(const RowsArgs &a)
 {
-    if ((a.r_pad != 1 && a.r_pad != 8 && a.r_pad != 16) || a.n_experts != 1 || a.out_f32 || tuning("rows_waves")) return false;
+    if (a.n_experts != 1 || a.out_f32 || tuning("rows_waves")) return false;
     const int U = a.d_in >> 3;
-    const int flu = a.r_pad == 1 ? RowsCfg<1, 8>::FLU : (a.r_pad == 8 ? RowsCfg<8, 8>::FLU : RowsCfg<16, 8>::FLU);
-    return U >= flu * 3 / 4;
+    switch (a.r_pad) {
+        case 1:  return wide_enough_for_8_waves<1>(U);
+        case 2:  return wide_enough_for_8_waves<2>(U);
+        case 4:  return wide_enough_for_8_waves<4>(U);
+        case 8:  return wide_enough_for_8_waves<8>(U);
+        case 16: return wide_enough_for_8_waves<16>(U);
+        case 32: return wide_enough_for_8_waves<32>(U);
+        case 64: return true;
+    }
+    return false;
 }
 
 // Plans the dense batch inside the launch of `sites` (8-wave sites of one rank, see rows_group_waves)
@@ -831,8 +841,12 @@ hipError_t launch_rows_multi_plan(const RowsArgs *sites, int n, const PlanView &
     pl.pv = pv;
     switch (sites[0].r_pad) {
         case 1:  return launch_multi_rp<1, 8>(sites, n, st, &pl);
+        case 2:  return launch_multi_rp<2, 8>(sites, n, st, &pl);
+        case 4:  return launch_multi_rp<4, 8>(sites, n, st, &pl);
         case 8:  return launch_multi_rp<8, 8>(sites, n, st, &pl);
         case 16: return launch_multi_rp<16, 8>(sites, n, st, &pl);
+        case 32: return launch_multi_rp<32, 8>(sites, n, st, &pl);
+        case 64: return launch_multi_rp<64, 8>(sites, n, st, &pl);
     }
     return hipErrorInvalidValue;
 }

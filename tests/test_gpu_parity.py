@@ -270,11 +270,13 @@ def test_decode_step_that_plans_inside_its_first_launch(M, oracle, T, S):
 
 
 def test_single_site_plans_inside_its_launch(M, oracle):
-    """A rank-1 catalog site (every row its own slot, 1024 slots) and a rank-16 site on their own:
+    """A rank-1 catalog site (every row its own slot, 1024 slots) and sites of the other ranks on their own:
     the launch plans for itself up to 256 rows and 1024 slots (more rows take the two calls); same
     bits as plan + planned apply."""
     for name, T, S, d_in, d_out, r in (("cat", 256, 1024, 4096, 264, 1), ("cat_ragged", 199, 700, 4096, 136, 1),
-                                       ("cat_two_calls", 333, 700, 4096, 136, 1), ("one16", 200, 40, 2304, 264, 16)):
+                                       ("cat_two_calls", 333, 700, 4096, 136, 1), ("one16", 200, 40, 2304, 264, 16),
+                                       ("one2", 100, 9, 4096, 72, 2), ("one4", 130, 20, 4096, 136, 4),
+                                       ("one32", 90, 12, 1024, 200, 32), ("one64", 70, 6, 520, 136, 64)):
         slots = W.rng(95 + T).permutation(S)[:T].astype(np.int32) if r == 1 else W.rng(95 + T).integers(-1, S, size=T).astype(np.int32)
         slots[::11] = -1
         c = W.dense_case(name, 3300 + T, T, d_in, d_out, S, r, 2.0 * r, token_slot=slots, std_a=0.05, std_b=0.05)
