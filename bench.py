@@ -153,6 +153,8 @@ def bench_c2(M, W, steps, warmup, n_layers=8, eager=True):
 
 
 def bench_c3(M, W, steps, warmup, n_sets=24):
+    """Rank-1 catalog: one lora_apply_decode call per step.  For rank-1 and rank-2 sites the call
+    applies the rows one by one without a plan (one launch)."""
     import torch
     c = W.c3_rank1_catalog()
     ts = torch.from_numpy(c.token_slot).cuda()
@@ -160,20 +162,17 @@ def bench_c3(M, W, steps, warmup, n_sets=24):
     for _ in range(n_sets):
         site = M.Site(c.d_in, c.d_out, c.r_max, c.n_slots)
         upload_case(M, site, c)
-        sets.append((site, M.Plan(c.T, c.n_slots), dev_bf16(c.x), dev_bf16(c.y0)))
+        sets.append((site, dev_bf16(c.x), dev_bf16(c.y0)))
     torch.cuda.synchronize()
 
-    def sweep(with_plan=True):
-        for site, plan, x, y in sets:
-            if with_plan:
-                M.lora_plan_decode(plan, ts, c.n_slots)
-            M.lora_apply_decode_planned(site, plan, x, y)
+    def sweep():
+        for site, x, y in sets:
+            M.lora_apply_decode(site, x, y, ts)
 
-    g_full, g_apply = graph_of(sweep), graph_of(lambda: sweep(False))
+    g_full = graph_of(sweep)
     reps, wreps = max(1, steps // n_sets), max(1, warmup // n_sets)
     ms_full = time_region(g_full.replay, reps, wreps) / n_sets
-    ms_apply = time_region(g_apply.replay, reps, wreps) / n_sets
-    return {"ms_per_step": ms_full, "ms_apply_only": ms_apply, "tokens": c.T, "launches_per_step": 1,
+    return {"ms_per_step": ms_full, "ms_apply_only": ms_full, "tokens": c.T, "launches_per_step": 1,
             "bytes_per_step": dense_bytes(c)}
 
 

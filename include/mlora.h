@@ -214,7 +214,10 @@ int32_t moe_lora_apply_down(mlora_site *site, const mlora_plan *plan, const void
 /* Decode: one token per row, gather-by-index.  Equivalent to lora_plan_decode on the site's
  * private scratch followed by lora_apply_decode_planned (for batches of up to 256 rows on sites
  * whose d_in is wide enough for the 8-wave kernel the plan is built inside the apply launch: same
- * plan, same bits, one launch).  T = 0 is MLORA_OK and launches nothing.
+ * plan, same bits, one launch).  Sites of rank 1 and 2 (compact catalogs of tiny adapters, Section 4)
+ * are applied row by row without any plan: grouping rows by slot would save at most two adapter
+ * rows per row, less than a planner launch costs; the result equals the planned one up to the order
+ * in which the fp32 partial sums of the shrink are added.  T = 0 is MLORA_OK and launches nothing.
  * Errors: MLORA_E_UNSUPPORTED on a MoE site, MLORA_E_SHAPE on bad strides. */
 int32_t lora_apply_decode(mlora_site *site, const void *x, int64_t ldx, void *y, int64_t ldy,
                           const int32_t *token_slot, int32_t T, void *stream);

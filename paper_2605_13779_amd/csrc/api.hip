@@ -862,6 +862,13 @@ int32_t lora_apply_decode(mlora_site *s, const void *x, int64_t ldx, void *y, in
     DeviceGuard g(s->d.device);
     if (!g.good) return MLORA_E_HIP;
     hipStream_t st = (hipStream_t)stream;
+    if (s->r_pad <= 2 && !tuning("plan_general") && !tuning("plan_separate")) {
+        // Tiny adapters (the compact rank-1 catalog of Section 4): rows are applied one by one, without
+        // a plan -- grouping would save at most two adapter rows per row, a planner launch costs more.
+        RowsArgs a = rows_args(s, x, ldx, y, ldy);
+        a.row_slot = token_slot; a.row_slots = s->d.n_slots; a.top_k = 1; a.grid_chunks = T;
+        return ok(launch_rows(a, st)) ? MLORA_OK : MLORA_E_HIP;
+    }
     // batches beyond the private plan are processed in slices; rows are independent
     for (int32_t t0 = 0; t0 < T; t0 += s->priv.max_items) {
         const int32_t n = T - t0 < s->priv.max_items ? T - t0 : s->priv.max_items;

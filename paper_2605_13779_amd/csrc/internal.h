@@ -71,6 +71,9 @@ struct RowsArgs {
     int32_t out_per_part;    // outputs [p * out_per_part, ...) and, in mode 2, shrinks k-slice p
     int32_t poll_limit;      // polls of an exchange word before a reader takes the item on its own
     int32_t rank_bound;      // 1: read the slot's rank first and fetch only that many rows of A
+    // ungrouped launch (ranks 1 and 2 only): item i is row i with slot row_slot[i]; `chunks` is not read
+    const int32_t *row_slot;
+    int32_t row_slots;       // slots the site holds (indices outside [0, row_slots) leave the row untouched)
     // MoE down projection: instead of adding into y, row p writes row_w[p] * delta as fp32 into
     // out_f32[p, :] (no read); a second launch adds a token's rows in order
     float *out_f32; int64_t ldo;

@@ -223,8 +223,19 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         }
         // The whole record is fetched before its count is looked at (one round trip, not two).
         // (a launch that planned for itself has the records in LDS)
-        const int4 *rec = lrec ? (const int4 *)(lrec + chunk * kRec) : (const int4 *)(a.chunks + (int64_t)chunk * kRec);
-        int4 r0 = rec[0], r1 = rec[1];
+        int4 r0, r1;
+        bool row_item = false;
+        if constexpr (!XCH && RP <= 2) row_item = a.row_slot != nullptr;
+        if (row_item) {
+            // Ungrouped launch of a rank-1 / rank-2 site: item = row, no plan.  Grouping rows by slot
+            // saves at most one or two adapter rows per row there, less than a planner launch costs.
+            const int sl = a.row_slot[chunk];
+            r0 = make_int4(sl, (sl >= 0 && sl < a.row_slots) ? 1 : 0, 0, 0);
+            r1 = make_int4(chunk, chunk, chunk, chunk);
+        } else {
+            const int4 *rec = lrec ? (const int4 *)(lrec + chunk * kRec) : (const int4 *)(a.chunks + (int64_t)chunk * kRec);
+            r0 = rec[0]; r1 = rec[1];
+        }
         asm volatile("" : "+v"(r0.x), "+v"(r0.y), "+v"(r1.x), "+v"(r1.y), "+v"(r1.z), "+v"(r1.w));
         const int key = __builtin_amdgcn_readfirstlane(r0.x), cnt = __builtin_amdgcn_readfirstlane(r0.y);
         int row[kChunk];
@@ -719,7 +730,7 @@ static hipError_t launch_rp(RowsArgs a, hipStream_t st)
     const int mode = tuning("rows_mode");     // 0 auto, 1 parts that redo the shrink, 3 one item per chunk
     const int cap = rows_capacity<RP, NW, true>();
     if (cap <= 0) return hipErrorUnknown;
-    const bool exchange = can_exchange(a) && mode == 0;
+    const bool exchange = can_exchange(a) && mode == 0 && !a.row_slot;
     set_parts(a, mode == 3 ? 1 : items_target(cap) / a.grid_chunks, exchange);
     a.rank_bound = use_rank_bound(a, cap);
     if (a.mode == 2) rows_kernel<RP, NW, true><<<dim3((unsigned)fused_grid(a)), dim3(NW * 64), 0, st>>>(a);
