@@ -89,7 +89,7 @@ __device__ __forceinline__ int block_scan(int v, int tid, int nw, int32_t *wave_
 //
 // No sort here: a row's place is (rows of smaller slots) + (earlier rows of its own slot).  Inside a
 // wave the second term comes from ballots, one per distinct slot of the wave; across waves from a
-// small table of per-wave counts; the first term from one scan over the slots.  Six barriers,
+// small table of per-wave counts; the first term from one scan over the slots.  Five barriers,
 // against fifteen of the sorting network, which is what a 512-thread workgroup feels.
 constexpr int kLocalPlanSlots = 1024;
 struct PlanLocalLds {
@@ -111,9 +111,9 @@ __device__ __forceinline__ void plan_dense_local(const int32_t *__restrict__ tok
         const int v = token_slot[i];
         if (v >= 0 && v < n_slots && !(ready_rank && ready_rank[v] <= 0)) s = v;
     }
-    for (int k = i; k < n_slots; k += nthreads)
-        for (int v = 0; v < kRowWaves; ++v) L.cntw[v][k] = 0;
-    __syncthreads();
+    // every row wave clears and fills its own line of the table (LDS operations of a wave stay in order)
+    if (w < kRowWaves)
+        for (int k = lane; k < n_slots; k += 64) L.cntw[w][k] = 0;
     // earlier rows of the same slot inside the wave, and the wave's count per slot
     int rank = 0;
     uint64_t todo = __ballot(s >= 0);
