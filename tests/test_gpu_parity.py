@@ -142,6 +142,51 @@ def test_decode_strided_rows(M, oracle):
     assert torch.equal(yb[:, :16], guard[:, :16]) and torch.equal(yb[:, 272:], guard[:, 272:])
 
 
+def _far_rows(bits, ld):
+    """The rows of `bits` as a view into a buffer whose rows lie `ld` elements apart."""
+    buf = torch.empty((bits.shape[0], ld), dtype=torch.bfloat16, device="cuda")
+    view = buf[:, :bits.shape[1]]
+    view.copy_(P.dev_bf16(bits))
+    return view
+
+
+def test_rows_more_than_4_gib_apart(M, oracle):
+    """Row strides of 64 MiB: the last rows of x and y start beyond 4 GiB from the first, so any
+    32-bit row offset in a kernel would land in the wrong row.  Decode (planned in the launch and
+    the row-by-row form of rank 1), the matrix-core prefill pair and the packed MoE call."""
+    ld = (1 << 25) + 8
+    for r in (8, 1):
+        c = W.dense_case(f"far_r{r}", 3090 + r, 72, 128, 192, 3, r, 2.0 * r, std_a=0.05, std_b=0.05)
+        c.token_slot[5] = -1
+        site = dense_site(M, c)
+        x, y = _far_rows(c.x, ld), _far_rows(c.y0, ld)
+        M.lora_apply_decode(site, x, y, torch.from_numpy(c.token_slot).cuda())
+        torch.cuda.synchronize()
+        ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+        P.check_close(P.host_bits(y.contiguous()), ref, c.name)
+        del x, y
+    c = W.seg_case("far_seg", 3093, 72, 3, 256, 192, 2, 64, 128.0, seg_off=[0, 30, 31, 72], seg_slot=[1, -1, 0],
+                   std_a=0.05, std_b=0.05)
+    site = dense_site(M, c)
+    x, y = _far_rows(c.x, ld), _far_rows(c.y0, ld)
+    M.lora_apply_segmented(site, x, y, c.seg_off, c.seg_slot)
+    torch.cuda.synchronize()
+    ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+    got = P.host_bits(y.contiguous())
+    P.check_close(got, ref, c.name)
+    P.check_untouched(got, c.y0, c.token_slot < 0, c.name)
+    del x, y
+    c = W.moe_case("far_moe", 3094, 36, 2, 4, 136, 200, 3, 8, 16.0, std_a=0.05, std_b=0.05)
+    site = moe_site(M, c)
+    x, y = _far_rows(c.x, 2 * ld), _far_rows(c.y0, ld)
+    M.moe_lora_apply_packed(site, x, y, torch.from_numpy(c.topk).cuda(), torch.from_numpy(c.token_slot).cuda(), None, None)
+    torch.cuda.synchronize()
+    ref = oracle.apply_moe(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, c.token_slot)
+    P.check_close(P.host_bits(y.contiguous()), ref, c.name)
+    del x, y
+    torch.cuda.empty_cache()
+
+
 def test_decode_large_batch_general_planner(M, oracle):
     """More rows than the one-workgroup planner takes: the histogram/scan/scatter pipeline."""
     c = W.dense_case("big", 3004, 2500, 64, 96, 37, 4, 8.0, std_a=0.1, std_b=0.1)
