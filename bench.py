@@ -42,19 +42,30 @@ def upload_case(M, site, c):
                                 np.ascontiguousarray(c.B[s][..., :, :r]), r, float(c.alpha[s]))
 
 
-def time_region(fn, iters, warmup):
-    """Mean milliseconds per call of fn() over `iters` calls, HIP events on the current stream."""
+def time_region(fn, iters, warmup, stats=None):
+    """Mean milliseconds per call of fn() over `iters` back-to-back calls, HIP events on the current
+    stream.  With `stats` (a dict) the same calls are also read as five consecutive batches (events
+    recorded between them, nothing else changes) and the median and the minimum of the batch means
+    are stored there."""
     import torch
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(iters):
-        fn()
-    e1.record()
+    n_b = 5 if stats is not None and iters >= 5 else 1
+    cuts = [iters * b // n_b for b in range(n_b + 1)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_b + 1)]
+    ev[0].record()
+    for b in range(n_b):
+        for _ in range(cuts[b + 1] - cuts[b]):
+            fn()
+        ev[b + 1].record()
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / iters
+    if stats is not None:
+        per = sorted(ev[b].elapsed_time(ev[b + 1]) / (cuts[b + 1] - cuts[b]) for b in range(n_b))
+        stats["batches"] = n_b
+        stats["median"] = per[n_b // 2]
+        stats["min"] = per[0]
+    return ev[0].elapsed_time(ev[n_b]) / iters
 
 
 def graph_of(fn):
@@ -130,12 +141,17 @@ def bench_c2(M, W, steps, warmup, n_layers=8, eager=True):
     g_apply = graph_of(lambda: all_layers(False))
     g_dom = graph_of(lambda: all_layers(True, True))       # the dominant kernel alone: the two grouped launches, as in the step
     reps, wreps = max(1, steps // n_layers), max(1, warmup // n_layers)
-    ms_full = time_region(g_full.replay, reps, wreps) / n_layers
+    st = {}
+    ms_full = time_region(g_full.replay, reps, wreps, st) / n_layers
     ms_apply = time_region(g_apply.replay, reps, wreps) / n_layers
     ms_dom = time_region(g_dom.replay, reps, wreps) / n_layers
+    # the same step on one layer's tables over and over: they stay in the last-level cache
+    g_warm = graph_of(lambda: [layer_step(0) for _ in range(n_layers)])
+    ms_warm = time_region(g_warm.replay, reps, wreps) / n_layers
     n_dom = sum(1 for g in groups if len(g) > 1)
     out = {"ms_per_step": ms_full, "steps_timed": reps * n_layers, "tokens": T,
-           "ms_apply_only": ms_apply, "launches_per_step": len(groups),
+           "ms_apply_only": ms_apply, "launches_per_step": len(groups), "ms_cache_warm": ms_warm,
+           "batch_stats": {k: (v / n_layers if k != "batches" else v) for k, v in st.items()},
            "dom_us_per_launch": ms_dom * 1e3 / n_dom,
            "dom_bytes_per_launch": sum(dense_bytes(cases[k]) for g in groups if len(g) > 1 for k in g) / n_dom}
     if eager:
@@ -171,9 +187,14 @@ def bench_c3(M, W, steps, warmup, n_sets=24):
 
     g_full = graph_of(sweep)
     reps, wreps = max(1, steps // n_sets), max(1, warmup // n_sets)
-    ms_full = time_region(g_full.replay, reps, wreps) / n_sets
+    st = {}
+    ms_full = time_region(g_full.replay, reps, wreps, st) / n_sets
+    site, x, y = sets[0]
+    g_warm = graph_of(lambda: [M.lora_apply_decode(site, x, y, ts) for _ in range(n_sets)])
+    ms_warm = time_region(g_warm.replay, reps, wreps) / n_sets
     return {"ms_per_step": ms_full, "ms_apply_only": ms_full, "tokens": c.T, "launches_per_step": 1,
-            "bytes_per_step": dense_bytes(c)}
+            "bytes_per_step": dense_bytes(c), "ms_cache_warm": ms_warm,
+            "batch_stats": {k: (v / n_sets if k != "batches" else v) for k, v in st.items()}}
 
 
 def bench_c4(M, W, steps, warmup, n_sets=2, fused=True):
@@ -203,10 +224,12 @@ def bench_c4(M, W, steps, warmup, n_sets=2, fused=True):
 
     g_full, g_apply = graph_of(sweep), graph_of(lambda: sweep(False))
     reps, wreps = max(1, steps // n_sets), max(1, warmup // n_sets)
-    ms_full = time_region(g_full.replay, reps, wreps) / n_sets
+    st = {}
+    ms_full = time_region(g_full.replay, reps, wreps, st) / n_sets
     ms_apply = time_region(g_apply.replay, reps, wreps) / n_sets
     return {"ms_per_step": ms_full, "ms_apply_only": ms_apply, "tokens": cg.T, "launches_per_step": 1 if fused else 2,
-            "bytes_per_step": 2 * moe_bytes(cg)}
+            "bytes_per_step": 2 * moe_bytes(cg),
+            "batch_stats": {k: (v / n_sets if k != "batches" else v) for k, v in st.items()}}
 
 
 def moe_down_bytes(c):
@@ -240,9 +263,11 @@ def bench_c4_down(M, W, steps, warmup, n_sets=2):
             M.moe_lora_apply_down(site, plan, x, w, ts, ws, y)
 
     g = graph_of(sweep)
-    ms = time_region(g.replay, max(1, steps // n_sets), max(1, warmup // n_sets)) / n_sets
+    st = {}
+    ms = time_region(g.replay, max(1, steps // n_sets), max(1, warmup // n_sets), st) / n_sets
     return {"ms_per_step": ms, "ms_apply_only": ms, "tokens": c.T, "launches_per_step": 2,
-            "bytes_per_step": moe_down_bytes(c)}
+            "bytes_per_step": moe_down_bytes(c),
+            "batch_stats": {k: (v / n_sets if k != "batches" else v) for k, v in st.items()}}
 
 
 def bench_c4_mixed(M, W, steps, warmup, n_sets=2):
@@ -339,10 +364,13 @@ def bench_c5(M, W, steps, warmup, wide=False, n_sets=3):
         k[0] += 1
         M.lora_apply_segmented(site, x, y, c.seg_off, c.seg_slot)
 
-    ms = time_region(one, steps, warmup)
+    st = {}
+    ms = time_region(one, steps, warmup, st)
+    x0, y0 = sets[0]
+    ms_warm = time_region(lambda: M.lora_apply_segmented(site, x0, y0, c.seg_off, c.seg_slot), steps, warmup)
     flops = 2.0 * c.T * c.r_max * (c.d_in + c.d_out)
     return {"ms_per_step": ms, "ms_apply_only": ms, "tokens": c.T, "launches_per_step": 1,
-            "bytes_per_step": dense_bytes(c), "flops_per_step": flops}
+            "bytes_per_step": dense_bytes(c), "flops_per_step": flops, "ms_cache_warm": ms_warm, "batch_stats": st}
 
 
 def bench_copy(steps, warmup, mib=256):
@@ -368,6 +396,11 @@ def summarize(r):
            "us_per_launch": round(r["ms_apply_only"] * 1e3 / r["launches_per_step"], 3),
            "alg_GBps": round(gbs, 1), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4),
            "alg_MB_per_step": round(r["bytes_per_step"] / 1e6, 2)}
+    if "batch_stats" in r and r["batch_stats"]:
+        b = r["batch_stats"]
+        out["batches"] = {"n": b["batches"], "median_us": round(b["median"] * 1e3, 3), "min_us": round(b["min"] * 1e3, 3)}
+    if "ms_cache_warm" in r:
+        out["us_per_step_cache_warm"] = round(r["ms_cache_warm"] * 1e3, 3)     # one buffer set over and over (labelled, not the metric)
     if "flops_per_step" in r:
         tf = r["flops_per_step"] / t / 1e12
         out["TFLOPs"] = round(tf, 1)
@@ -396,16 +429,31 @@ def cpu_baseline(W, cases, budget_s=12.0):
     def step():
         for c in cases:
             ref.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
-    step()
-    t0, n = time.perf_counter(), 0
-    while True:
+    def timed(budget):
         step()
-        n += 1
-        dt = time.perf_counter() - t0
-        if dt >= budget_s or n >= 200:
-            break
-    return {"value": cases[0].T * n / dt, "unit": "tokens/s", "cores": ref.num_threads(), "kind": "oracle",
-            "sample": f"{n} full layer steps (256 tokens x 7 projections), fp64 C loops, OpenMP over rows, {dt:.1f} s"}
+        t0, n = time.perf_counter(), 0
+        while True:
+            step()
+            n += 1
+            dt = time.perf_counter() - t0
+            if dt >= budget or n >= 200:
+                return n, dt
+    n, dt = timed(budget_s)
+    out = {"value": cases[0].T * n / dt, "unit": "tokens/s", "cores": ref.num_threads(), "kind": "oracle",
+           "sample": f"{n} full layer steps (256 tokens x 7 projections), fp64 C loops, OpenMP over rows, {dt:.1f} s"}
+    try:                                   # the same oracle on one thread, through the OpenMP runtime it already uses
+        import ctypes
+        gomp = ctypes.CDLL("libgomp.so.1")
+        many = ref.num_threads()
+        gomp.omp_set_num_threads(1)
+        try:
+            n1, dt1 = timed(3.0)
+        finally:
+            gomp.omp_set_num_threads(many)
+        out["one_thread_value"] = cases[0].T * n1 / dt1
+    except OSError:
+        pass
+    return out
 
 
 def main():
