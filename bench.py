@@ -97,7 +97,7 @@ def moe_bytes(c):
 
 # ---------------------------------------------------------------- workloads
 
-def bench_c2(M, W, steps, warmup, n_layers=8, eager=True):
+def bench_c2(M, W, steps, warmup, n_layers=8, eager=True, cache_warm=False):
     import torch
     cases = W.c2_dense_decode()
     T = cases[0].T
@@ -146,8 +146,10 @@ def bench_c2(M, W, steps, warmup, n_layers=8, eager=True):
     ms_apply = time_region(g_apply.replay, reps, wreps) / n_layers
     ms_dom = time_region(g_dom.replay, reps, wreps) / n_layers
     # the same step on one layer's tables over and over: they stay in the last-level cache
-    g_warm = graph_of(lambda: [layer_step(0) for _ in range(n_layers)])
-    ms_warm = time_region(g_warm.replay, reps, wreps) / n_layers
+    ms_warm = None
+    if cache_warm:
+        g_warm = graph_of(lambda: [layer_step(0) for _ in range(n_layers)])
+        ms_warm = time_region(g_warm.replay, reps, wreps) / n_layers
     n_dom = sum(1 for g in groups if len(g) > 1)
     out = {"ms_per_step": ms_full, "steps_timed": reps * n_layers, "tokens": T,
            "ms_apply_only": ms_apply, "launches_per_step": len(groups), "ms_cache_warm": ms_warm,
@@ -168,7 +170,7 @@ def bench_c2(M, W, steps, warmup, n_layers=8, eager=True):
     return out, cases
 
 
-def bench_c3(M, W, steps, warmup, n_sets=24):
+def bench_c3(M, W, steps, warmup, n_sets=24, cache_warm=False):
     """Rank-1 catalog: one lora_apply_decode call per step.  For rank-1 and rank-2 sites the call
     applies the rows one by one without a plan (one launch)."""
     import torch
@@ -189,9 +191,11 @@ def bench_c3(M, W, steps, warmup, n_sets=24):
     reps, wreps = max(1, steps // n_sets), max(1, warmup // n_sets)
     st = {}
     ms_full = time_region(g_full.replay, reps, wreps, st) / n_sets
-    site, x, y = sets[0]
-    g_warm = graph_of(lambda: [M.lora_apply_decode(site, x, y, ts) for _ in range(n_sets)])
-    ms_warm = time_region(g_warm.replay, reps, wreps) / n_sets
+    ms_warm = None
+    if cache_warm:
+        site, x, y = sets[0]
+        g_warm = graph_of(lambda: [M.lora_apply_decode(site, x, y, ts) for _ in range(n_sets)])
+        ms_warm = time_region(g_warm.replay, reps, wreps) / n_sets
     return {"ms_per_step": ms_full, "ms_apply_only": ms_full, "tokens": c.T, "launches_per_step": 1,
             "bytes_per_step": dense_bytes(c), "ms_cache_warm": ms_warm,
             "batch_stats": {k: (v / n_sets if k != "batches" else v) for k, v in st.items()}}
@@ -350,7 +354,7 @@ def bench_upload(M, W, reps=20):
     return out
 
 
-def bench_c5(M, W, steps, warmup, wide=False, n_sets=3):
+def bench_c5(M, W, steps, warmup, wide=False, n_sets=3, cache_warm=False):
     import torch
     c = W.c5_segmented(wide)
     site = M.Site(c.d_in, c.d_out, c.r_max, c.n_slots)
@@ -366,8 +370,10 @@ def bench_c5(M, W, steps, warmup, wide=False, n_sets=3):
 
     st = {}
     ms = time_region(one, steps, warmup, st)
-    x0, y0 = sets[0]
-    ms_warm = time_region(lambda: M.lora_apply_segmented(site, x0, y0, c.seg_off, c.seg_slot), steps, warmup)
+    ms_warm = None
+    if cache_warm:
+        x0, y0 = sets[0]
+        ms_warm = time_region(lambda: M.lora_apply_segmented(site, x0, y0, c.seg_off, c.seg_slot), steps, warmup)
     flops = 2.0 * c.T * c.r_max * (c.d_in + c.d_out)
     return {"ms_per_step": ms, "ms_apply_only": ms, "tokens": c.T, "launches_per_step": 1,
             "bytes_per_step": dense_bytes(c), "flops_per_step": flops, "ms_cache_warm": ms_warm, "batch_stats": st}
@@ -399,7 +405,7 @@ def summarize(r):
     if "batch_stats" in r and r["batch_stats"]:
         b = r["batch_stats"]
         out["batches"] = {"n": b["batches"], "median_us": round(b["median"] * 1e3, 3), "min_us": round(b["min"] * 1e3, 3)}
-    if "ms_cache_warm" in r:
+    if r.get("ms_cache_warm") is not None:
         out["us_per_step_cache_warm"] = round(r["ms_cache_warm"] * 1e3, 3)     # one buffer set over and over (labelled, not the metric)
     if "flops_per_step" in r:
         tf = r["flops_per_step"] / t / 1e12
@@ -463,6 +469,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="all", choices=["all", "c2", "c3", "c4", "c4d", "c4m", "c5", "c5w", "copy", "upload"])
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--cache-warm", action="store_true",
+                    help="also time each configuration on one buffer set over and over (labelled us_per_step_cache_warm)")
     ap.add_argument("--tune", action="append", default=[], help="name=value for mlora_set_tuning")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -481,14 +489,14 @@ def main():
     head = None
     if args.workload in ("all", "c2"):
         log("[bench] c2 dense decode layer")
-        r, cases = bench_c2(M, W, args.steps, args.warmup)
+        r, cases = bench_c2(M, W, args.steps, args.warmup, cache_warm=args.cache_warm)
         head = r
         per["c2_layer"] = summarize(r)
         per["c2_layer"]["ms_per_step_eager"] = round(r["ms_per_step_eager"], 6)
         per["c2_layer"]["distinct_slots"] = r["distinct_slots"]
     if args.workload in ("all", "c3"):
         log("[bench] c3 rank-1 catalog")
-        per["c3_rank1"] = summarize(bench_c3(M, W, args.steps, args.warmup))
+        per["c3_rank1"] = summarize(bench_c3(M, W, args.steps, args.warmup, cache_warm=args.cache_warm))
         torch.cuda.empty_cache()
     if args.workload in ("all", "c4"):
         log("[bench] c4 packed MoE")
@@ -510,11 +518,11 @@ def main():
         torch.cuda.empty_cache()
     if args.workload in ("all", "c5"):
         log("[bench] c5 segmented prefill 7168->7168")
-        per["c5_seg"] = summarize(bench_c5(M, W, max(10, args.steps // 40), max(3, args.warmup // 40)))
+        per["c5_seg"] = summarize(bench_c5(M, W, max(10, args.steps // 40), max(3, args.warmup // 40), cache_warm=args.cache_warm))
         torch.cuda.empty_cache()
     if args.workload in ("all", "c5w"):
         log("[bench] c5 segmented prefill 7168->18432")
-        per["c5_seg_wide"] = summarize(bench_c5(M, W, max(10, args.steps // 40), max(3, args.warmup // 40), wide=True))
+        per["c5_seg_wide"] = summarize(bench_c5(M, W, max(10, args.steps // 40), max(3, args.warmup // 40), wide=True, cache_warm=args.cache_warm))
         torch.cuda.empty_cache()
 
     if args.workload == "copy":

@@ -193,11 +193,156 @@ void plan_fix_kernel(PlanView pv, int P, int32_t *__restrict__ out_sorted, int r
     if (r % kChunk == 0) { rec[0] = key; rec[1] = min(kChunk, n - r); rec[2] = off + r; rec[3] = 0; }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same result in one launch, for batches of moderate size (MoE decode / prefill steps of a
+// few thousand tokens).  Every workgroup owns kOneRange consecutive pairs and builds, in LDS, the
+// histogram of ALL pairs and the histogram of the pairs in front of its range; a scan of the first
+// gives the group starts and chunk numbers, the second is the stable rank of the range's first
+// member of each group.  Position of pair p = group start + pairs of its key in front of the
+// range + pairs of its key in front of it inside the range.  Every workgroup reads all keys
+// (P * 4 bytes from L2 each), which is what replaces the three dependent launches and the global
+// atomics of the pipeline above; the result is the unique stable counting sort either way.
+// ---------------------------------------------------------------------------------------------
+constexpr int kOneRange = 256;     // pairs owned by a workgroup
+constexpr int kOneKeys = 4096;     // largest key space (LDS: three int32 tables of this size)
+constexpr int kOnePairs = 32768;   // largest batch (each workgroup walks all of it)
+constexpr int kOneThreads = 1024;
+
+// k_magic = ceil(2^32 / K) (0 for K = 1): p / K is then the high word of p * k_magic, exact while
+// p * K < 2^32.  A wave instruction takes four cycles on the 16-lane SIMDs, every workgroup walks
+// all pairs, and the general division is some forty instructions per pair.
+__device__ __forceinline__ int route_key(const int32_t *__restrict__ topk, const int32_t *__restrict__ token_slot,
+                                         const int32_t *__restrict__ ready_rank, int p, uint32_t k_magic, int E, int n_slots)
+{
+    const int s = token_slot[k_magic ? (int)__umulhi((uint32_t)p, k_magic) : p];
+    const int e = topk ? topk[p] : 0;
+    if (s >= 0 && s < n_slots && e >= 0 && e < E && !(ready_rank && ready_rank[s] <= 0)) return s * E + e;
+    return -1;
+}
+
+__global__ __launch_bounds__(kOneThreads)
+void plan_route_one_kernel(PlanView pv, const int32_t *__restrict__ topk, const int32_t *__restrict__ token_slot,
+                           int P, uint32_t k_magic, int E, int n_slots, const int32_t *__restrict__ ready_rank,
+                           int32_t *__restrict__ out_sorted, int32_t *__restrict__ out_group_off, int rec_bound)
+{
+    __shared__ int32_t goff[kOneKeys + 1];       // histogram of all pairs, then exclusive group starts
+    __shared__ int32_t pre[kOneKeys];            // histogram of the pairs in front of this range
+    __shared__ int32_t cbase[kOneKeys + 1];      // first chunk of each group
+    __shared__ __attribute__((aligned(16))) int32_t lkey[kOneRange];
+    __shared__ int32_t lrank[kOneRange];
+    __shared__ int32_t wave_tot[16];
+    static_assert(kOneThreads == 4 * kOneRange, "four threads per pair in the in-range rank");
+    const int tid = threadIdx.x, NK = n_slots * E;
+    const int p0 = (int)blockIdx.x * kOneRange;
+    for (int k = tid; k < NK; k += kOneThreads) { goff[k] = 0; pre[k] = 0; }
+    if (tid < kOneRange) lkey[tid] = -1;         // positions past the batch
+    __syncthreads();
+    constexpr int kU = 16;                                      // keys per thread in flight
+    for (int q0 = 0; q0 < P; q0 += kU * kOneThreads) {
+        int key[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int q = q0 + u * kOneThreads + tid;
+            key[u] = q < P ? route_key(topk, token_slot, ready_rank, q, k_magic, E, n_slots) : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int q = q0 + u * kOneThreads + tid;
+            if (key[u] >= 0) {
+                atomicAdd(&goff[key[u]], 1);
+                if (q < p0) atomicAdd(&pre[key[u]], 1);
+            }
+            if (q >= p0 && q < p0 + kOneRange) lkey[q - p0] = key[u];
+        }
+    }
+    if (tid < kOneRange) lrank[tid] = 0;
+    __syncthreads();
+    // Members of the same group in front of a pair inside the range: pair i = tid % 256 against the
+    // quarter tid / 256 of the range, four keys per LDS read; the quarters' counts meet in lrank.
+    {
+        const int i = tid & (kOneRange - 1), m0 = (tid / kOneRange) * (kOneRange / 4);
+        const int key = lkey[i];
+        int r = 0;
+        if (key >= 0) {
+#pragma unroll 4
+            for (int m = m0; m < m0 + kOneRange / 4; m += 4) {
+                const int4 k4 = *(const int4 *)(lkey + m);
+                r += (m < i && k4.x == key) + (m + 1 < i && k4.y == key) + (m + 2 < i && k4.z == key) + (m + 3 < i && k4.w == key);
+            }
+            if (r) atomicAdd(&lrank[i], r);
+        }
+    }
+    // exclusive scans of the group sizes and of the groups' chunk counts, in place
+    const int per = (NK + kOneThreads - 1) / kOneThreads;       // <= 4
+    const int lo = min(NK, tid * per), hi = min(NK, lo + per);
+    int cnt[kOneKeys / kOneThreads], items = 0, chunks = 0;
+#pragma unroll
+    for (int u = 0; u < kOneKeys / kOneThreads; ++u) {
+        cnt[u] = lo + u < hi ? goff[lo + u] : 0;
+        items += cnt[u];
+        chunks += (cnt[u] + kChunk - 1) / kChunk;
+    }
+    const int inc_i = block_scan<false>(items, tid, 16, wave_tot);
+    const int inc_c = block_scan<false>(chunks, tid, 16, wave_tot);
+    int run_i = inc_i - items, run_c = inc_c - chunks;
+#pragma unroll
+    for (int u = 0; u < kOneKeys / kOneThreads; ++u) {
+        if (lo + u < hi) {
+            goff[lo + u] = run_i;
+            cbase[lo + u] = run_c;
+            run_i += cnt[u];
+            run_c += (cnt[u] + kChunk - 1) / kChunk;
+        }
+    }
+    if (tid == kOneThreads - 1) { goff[NK] = inc_i; cbase[NK] = inc_c; }
+    __syncthreads();
+    const int n_rows = goff[NK], n_chunks = cbase[NK];
+    if (blockIdx.x == 0) {
+        for (int k = tid; k <= NK; k += kOneThreads) {
+            pv.group_off[k] = goff[k];
+            if (out_group_off) out_group_off[k] = goff[k];
+            pv.chunk_base[k] = cbase[k];
+        }
+        if (tid == 0) { pv.hdr[0] = n_chunks; pv.hdr[1] = n_rows; }
+    }
+    if (tid < kOneRange) {
+        const int j = p0 + tid;                  // this range also owns positions / records [p0, p0 + kOneRange)
+        if (j < P) {
+            if (j >= n_chunks && j < rec_bound) pv.chunks[(int64_t)j * kRec + 1] = 0;   // empty record past the live chunks
+            if (j >= n_rows) {
+                pv.sorted[j] = -1;
+                if (out_sorted) out_sorted[j] = -1;
+            }
+            const int key = lkey[tid];
+            if (key >= 0) {
+                const int r = pre[key] + lrank[tid];
+                const int off = goff[key], n = goff[key + 1] - off;
+                pv.sorted[off + r] = j;
+                if (out_sorted) out_sorted[off + r] = j;
+                int32_t *rec = pv.chunks + (int64_t)(cbase[key] + r / kChunk) * kRec;
+                rec[4 + (r % kChunk)] = j;
+                if (r % kChunk == 0) { rec[0] = key; rec[1] = min(kChunk, n - r); rec[2] = off + r; rec[3] = 0; }
+            }
+        }
+    }
+}
+
+bool plan_route_in_one_launch(int64_t P, int64_t NK)
+{
+    return P <= kOnePairs && NK <= kOneKeys && !tuning("plan_pipeline");
+}
+
 hipError_t launch_plan_general(const PlanView &pv, const int32_t *topk, const int32_t *token_slot,
                                int T, int K, int E, int n_slots, const int32_t *ready_rank,
                                int32_t *out_sorted, int32_t *out_group_off, hipStream_t st)
 {
     const int P = T * K, NK = n_slots * E;
+    if (plan_route_in_one_launch(P, NK)) {
+        plan_route_one_kernel<<<dim3((unsigned)((P + kOneRange - 1) / kOneRange)), dim3(kOneThreads), 0, st>>>(
+            pv, topk, token_slot, P, K > 1 ? (uint32_t)((0x100000000ull + (uint64_t)K - 1) / (uint64_t)K) : 0u, E, n_slots,
+            ready_rank, out_sorted, out_group_off, (int)max_chunks(P, NK));
+        return hipGetLastError();
+    }
     const unsigned nb = (unsigned)((P + 255) / 256);
     plan_hist_kernel<<<dim3(nb), dim3(256), 0, st>>>(pv, topk, token_slot, P, K, E, n_slots, ready_rank);
     plan_scan_kernel<<<dim3(1), dim3(1024), 0, st>>>(pv, NK, out_group_off);

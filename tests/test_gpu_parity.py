@@ -191,11 +191,14 @@ def test_decode_large_batch_general_planner(M, oracle):
     """More rows than the one-workgroup planner takes: the histogram/scan/scatter pipeline."""
     c = W.dense_case("big", 3004, 2500, 64, 96, 37, 4, 8.0, std_a=0.1, std_b=0.1)
     site = dense_site(M, c)
-    M.set_tuning("plan_general", 1)
-    try:
-        check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0))
-    finally:
-        M.set_tuning("plan_general", 0)
+    for pipeline in (0, 1):                               # the one-launch form and the four-launch pipeline
+        M.set_tuning("plan_general", 1)
+        M.set_tuning("plan_pipeline", pipeline)
+        try:
+            check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0))
+        finally:
+            M.set_tuning("plan_general", 0)
+            M.set_tuning("plan_pipeline", 0)
     check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0))
 
 
@@ -653,6 +656,50 @@ def test_moe_planned_reuse(M, oracle):
         torch.cuda.synchronize()
         ref = oracle.apply_moe(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, c.token_slot)
         P.check_close(P.host_bits(y), ref, c.name)
+
+
+@pytest.mark.parametrize("T,K,E,S", [(37, 2, 4, 3), (1000, 3, 7, 5), (300, 1, 1, 9), (2048, 8, 128, 32), (4096, 8, 64, 64),
+                                     (4097, 8, 64, 64), (640, 4, 160, 32)])
+def test_route_index_build_paths_agree(M, oracle, T, K, E, S):
+    """The route index build has a one-launch form (every workgroup histograms all pairs in LDS) for
+    up to 32768 pairs and 4096 (slot, expert) keys, and a four-launch pipeline for everything else:
+    both must give the oracle's stable counting sort bit for bit (sorted pairs, group offsets) and
+    leave the same chunk records.  Repeated experts inside a token, rows without adapter, sizes
+    that are not multiples of a workgroup's range, one pair more than the one-launch form takes,
+    and one key space larger than it takes."""
+    g = W.rng(7700 + T + K)
+    topk = g.integers(0, E, size=(T, K)).astype(np.int32)
+    slots = g.integers(-1, S, size=T).astype(np.int32)
+    if T > 100:
+        slots[10:90] = 2                              # one crowded group: many members in one range
+        topk[10:90, 0] = E - 1
+    ref_sp, ref_go = oracle.route_sort(topk, slots, np.ones(S, dtype=np.int32), E)
+    tk, ts = torch.from_numpy(topk).cuda(), torch.from_numpy(slots).cuda()
+    outs = []
+    for pipeline in (0, 1):
+        M.set_tuning("plan_pipeline", pipeline)
+        try:
+            plan = M.Plan(T * K, S * E)
+            sp = torch.full((T * K,), -7, dtype=torch.int32, device="cuda")
+            go = torch.full((S * E + 1,), -7, dtype=torch.int32, device="cuda")
+            for _ in range(2):                         # a plan buffer is used again and again
+                M.moe_plan_route(plan, tk, ts, S, E, out_sorted_pair=sp, out_group_off=go)
+            torch.cuda.synchronize()
+        finally:
+            M.set_tuning("plan_pipeline", 0)
+        assert np.array_equal(go.cpu().numpy(), ref_go), f"group offsets differ (pipeline={pipeline})"
+        assert np.array_equal(sp.cpu().numpy(), ref_sp), f"sorted pairs differ (pipeline={pipeline})"
+        hdr, srt, rec = _plan_words(plan, T * K, S * E)
+        n_chunks = int(hdr[0])
+        assert int(hdr[1]) == int(ref_go[-1])
+        assert np.array_equal(srt, ref_sp)
+        bound = (T * K + 3 * min(S * E, T * K)) // 4              # records a launch may read: sum of ceil(n_g / 4) <= this
+        rec = rec[:8 * bound].reshape(-1, 8)[:, :4].copy()         # key, count, first position, flag (members: through the apply tests)
+        rec[n_chunks:, [0, 2, 3]] = 0                             # past the live records only the count (0) is defined
+        outs.append((n_chunks, rec))
+    assert outs[0][0] == outs[1][0]
+    assert np.array_equal(outs[0][1], outs[1][1]), "chunk records differ between the two forms"
+    assert np.all(outs[0][1][outs[0][0]:, 1] == 0)
 
 
 def run_moe_down(M, site, c, y0_bits):
