@@ -52,7 +52,7 @@ void plan_dense_small_kernel(PlanView pv, const int32_t *__restrict__ token_slot
                              const int32_t *__restrict__ ready_rank, int rec_bound, int N)
 {
     __shared__ uint2 xch[kSortMax];              // long-distance exchanges, then sorted slots / chunk starts
-    __shared__ int32_t wave_tot[16];
+    __shared__ __attribute__((aligned(16))) int32_t wave_tot[16];
     __shared__ int32_t s_rows, s_chunks;
     const int i = threadIdx.x;                   // blockDim.x == N, a power of two in [64, 1024]
     const uint32_t kNone = 0xffffffffu;
@@ -129,7 +129,7 @@ void plan_hist_kernel(PlanView pv, const int32_t *__restrict__ topk, const int32
 __global__ __launch_bounds__(1024)
 void plan_scan_kernel(PlanView pv, int NK, int32_t *__restrict__ out_group_off)
 {
-    __shared__ int32_t wave_tot[16];
+    __shared__ __attribute__((aligned(16))) int32_t wave_tot[16];
     const int tid = threadIdx.x;
     const int per = (NK + 1023) / 1024;
     const int lo = min(NK, tid * per), hi = min(NK, lo + per);
@@ -230,7 +230,7 @@ void plan_route_one_kernel(PlanView pv, const int32_t *__restrict__ topk, const 
     __shared__ int32_t cbase[kOneKeys + 1];      // first chunk of each group
     __shared__ __attribute__((aligned(16))) int32_t lkey[kOneRange];
     __shared__ int32_t lrank[kOneRange];
-    __shared__ int32_t wave_tot[16];
+    __shared__ __attribute__((aligned(16))) int32_t wave_tot[16];
     static_assert(kOneThreads == 4 * kOneRange, "four threads per pair in the in-range rank");
     const int tid = threadIdx.x, NK = n_slots * E;
     const int p0 = (int)blockIdx.x * kOneRange;

@@ -61,20 +61,44 @@ struct BitonicSort {
     }
 };
 
+// Inclusive scan over the 64 lanes of a wave with data-parallel-primitive moves (values >= 0, so 0
+// is the identity of both operations): shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the
+// last lane of row 0 / 2 is broadcast into row 1 / 3 and the last lane of the lower half into the
+// upper half.  Lanes without a source keep the identity.
+template <bool IS_MAX>
+__device__ __forceinline__ int wave_scan(int v)
+{
+    auto op = [](int a, int b) { return IS_MAX ? max(a, b) : a + b; };
+    v = op(v, __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false));     // row_shr:1
+    v = op(v, __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false));     // row_shr:2
+    v = op(v, __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false));     // row_shr:4
+    v = op(v, __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false));     // row_shr:8
+    v = op(v, __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false));     // row_bcast:15 into rows 1 and 3
+    v = op(v, __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false));     // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 // Inclusive scan over the workgroup (one value per thread); IS_MAX selects max instead of plus.
 template <bool IS_MAX>
 __device__ __forceinline__ int block_scan(int v, int tid, int nw, int32_t *wave_tot)
 {
     const int lane = tid & 63, w = tid >> 6;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int o = __shfl_up(v, d, 64);
-        if (lane >= d) v = IS_MAX ? max(v, o) : v + o;
-    }
+    v = wave_scan<IS_MAX>(v);
     if (lane == 63) wave_tot[w] = v;
     __syncthreads();
+    // the totals of the waves in front of this one: all sixteen words in four reads (a loop over
+    // k < w is a chain of dependent LDS reads); words of waves that do not exist are never selected
     int base = 0;
-    for (int k = 0; k < w; ++k) base = IS_MAX ? max(base, wave_tot[k]) : base + wave_tot[k];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int4 t = ((const int4 *)wave_tot)[q];
+        const int e[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int v = 4 * q + k < w ? e[k] : 0;
+            base = IS_MAX ? max(base, v) : base + v;
+        }
+    }
     __syncthreads();
     (void)nw;
     return IS_MAX ? max(v, base) : v + base;
@@ -94,9 +118,11 @@ __device__ __forceinline__ int block_scan(int v, int tid, int nw, int32_t *wave_
 constexpr int kLocalPlanSlots = 1024;
 struct PlanLocalLds {
     int32_t cntw[4][kLocalPlanSlots];      // rows of slot s in wave w (the rows sit in the first 4 waves)
+    __attribute__((aligned(16))) int32_t srow[2][256];   // usable slot of each row (-1: none), one copy per half
+    int32_t prt[256];                      // the upper half's counts for each row (same << 16 | earlier)
     int32_t off[kLocalPlanSlots + 1];      // rows of smaller slots
     int32_t cbase[kLocalPlanSlots + 1];    // chunks of smaller slots
-    int32_t wave_tot[16];
+    __attribute__((aligned(16))) int32_t wave_tot[16];
 };
 
 __device__ __forceinline__ void plan_dense_local(const int32_t *__restrict__ token_slot, int T, int n_slots,
@@ -106,25 +132,44 @@ __device__ __forceinline__ void plan_dense_local(const int32_t *__restrict__ tok
 {
     const int lane = i & 63, w = i >> 6, nw = nthreads >> 6;
     constexpr int kRowWaves = 4;
-    int s = -1;
-    if (i < T) {
-        const int v = token_slot[i];
-        if (v >= 0 && v < n_slots && !(ready_rank && ready_rank[v] <= 0)) s = v;
+    // The rows sit in waves 0..3.  A workgroup of eight waves lets wave w + 4 do the upper half of
+    // wave w's compares (below): it fetches the same 64 slots and hands its counts over through LDS.
+    const bool split = nw >= 2 * kRowWaves;
+    const int hw = split ? (w & (kRowWaves - 1)) : w, half = split ? w / kRowWaves : 0;
+    const int hrow = hw * 64 + lane;
+    int sh = -1;
+    if (hw < kRowWaves && hrow < T) {
+        const int v = token_slot[hrow];
+        if (v >= 0 && v < n_slots && !(ready_rank && ready_rank[v] <= 0)) sh = v;
     }
-    // every row wave clears and fills its own line of the table (LDS operations of a wave stay in order)
-    if (w < kRowWaves)
-        for (int k = lane; k < n_slots; k += 64) L.cntw[w][k] = 0;
-    // earlier rows of the same slot inside the wave, and the wave's count per slot
-    int rank = 0;
-    uint64_t todo = __ballot(s >= 0);
-    while (todo) {
-        const int leader = __ffsll((long long)todo) - 1;
-        const int sl = __builtin_amdgcn_readlane(s, leader);
-        const uint64_t m = __ballot(s == sl);
-        if (s == sl) rank = __popcll(m & (((uint64_t)1 << lane) - 1));
-        if (lane == leader) L.cntw[w][sl] = __popcll(m);
-        todo &= ~m;
+    const int s = w < kRowWaves ? sh : -1;       // a row's own thread: i == hrow
+    // Earlier rows of the same slot inside the wave, and the wave's count per slot: every lane
+    // compares its slot with the wave's 64 slots, read back from LDS four at a time (all lanes read
+    // the same address: a broadcast).  A loop over the distinct slots with ballots is shorter on
+    // paper, but each of its 30 to 40 rounds (64 slots, Zipf popularity) is a chain of scalar /
+    // vector hand-overs and took 1.9 us.  Every row wave clears and fills its own line of the count
+    // table (LDS operations of a wave stay in order).
+    int rank = 0, same = 0;
+    if (hw < kRowWaves) {
+        if (w < kRowWaves)
+            for (int k = lane; k < n_slots; k += 64) L.cntw[w][k] = 0;
+        int32_t *mine = L.srow[half] + 64 * hw;   // this wave's own copy of the 64 slots
+        mine[lane] = sh;
+        const int j_lo = split ? 32 * half : 0, n4 = split ? 8 : 16;
+#pragma unroll 4
+        for (int q = 0; q < n4; ++q) {
+            const int j = j_lo + 4 * q;
+            const int4 v = *(const int4 *)(mine + j);
+            same += (v.x == sh) + (v.y == sh) + (v.z == sh) + (v.w == sh);
+            rank += (v.x == sh && j < lane) + (v.y == sh && j + 1 < lane) + (v.z == sh && j + 2 < lane) + (v.w == sh && j + 3 < lane);
+        }
+        if (w >= kRowWaves) L.prt[hrow] = same << 16 | rank;
     }
+    if (split) {
+        __syncthreads();
+        if (w < kRowWaves) { const int p = L.prt[i]; rank += p & 0xffff; same += p >> 16; }
+    }
+    if (s >= 0 && rank == 0) L.cntw[w][s] = same;
     __syncthreads();
     // per slot: size and chunks, a run of slots per thread; one scan carries both sums (each total is
     // at most 256)

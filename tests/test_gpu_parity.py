@@ -277,7 +277,7 @@ def _plan_words(plan, max_items, n_keys):
     return w[:2].copy(), w[off_sorted:off_sorted + max_items].copy(), w[off_sorted + max_items:].copy()
 
 
-@pytest.mark.parametrize("T,S", [(61, 5), (256, 64), (1, 3), (200, 64), (300, 7)])
+@pytest.mark.parametrize("T,S", [(61, 5), (256, 64), (1, 3), (200, 64), (300, 7), (256, 65), (250, 300), (256, 1000)])
 def test_decode_step_that_plans_inside_its_first_launch(M, oracle, T, S):
     """lora_plan_apply_decode_multi = lora_plan_decode + lora_apply_decode_multi, bit for bit, in the
     results and in the plan it leaves behind (which a later planned apply uses); 300 rows are more
