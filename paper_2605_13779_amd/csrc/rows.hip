@@ -153,9 +153,11 @@ __device__ __forceinline__ void y_pack(const float *f, uint4 &r)
 
 // Work of workgroup `wg` out of `n_wg` on one site (one launch may cover several sites).
 // XCH: the kernel can pass partial shrink results between workgroups (a.mode 2).
-template <int RP, int NW, bool XCH>
+// RI: the launch has no plan; item i is row i and its slot is a.row_slot[i] (rank 1 and 2 only).
+template <int RP, int NW, bool XCH, bool RI = false>
 __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const int n_wg, const int32_t *lrec = nullptr)
 {
+    static_assert(!RI || (!XCH && RP <= 2), "row items: small ranks, nothing traded");
     using C = RowsCfg<RP, NW>;
     typedef typename YVec<C::OPL>::T yvec_t;
     __shared__ __attribute__((aligned(16))) float hs[kChunk][RP];
@@ -224,12 +226,20 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         // The whole record is fetched before its count is looked at (one round trip, not two).
         // (a launch that planned for itself has the records in LDS)
         int4 r0, r1;
-        bool row_item = false;
-        if constexpr (!XCH && RP <= 2) row_item = a.row_slot != nullptr;
-        if (row_item) {
+        uint4 x_early = make_uint4(0, 0, 0, 0);
+        yvec_t y_early = {};
+        if constexpr (RI) {
             // Ungrouped launch of a rank-1 / rank-2 site: item = row, no plan.  Grouping rows by slot
             // saves at most one or two adapter rows per row there, less than a planner launch costs.
             const int sl = a.row_slot[chunk];
+            // The row's x and y do not depend on its slot: they are requested behind the slot read,
+            // before its value is looked at, and travel while it is awaited (half of the item's bytes;
+            // the launch is one flight per row, and after the slot has arrived all rows' flights share
+            // the memory system at once).
+            const int u = ks * 64 + lane;                    // this lane's unit of the first shrink flight
+            x_early = *(const uint4 *)((const char *)(a.x + (int64_t)chunk * a.ldx) + (uint32_t)(u < U ? u : 0) * 16u);
+            const int o = out0 + tid * C::OPL;               // ... and its outputs of the first expand tile
+            y_early = *(const yvec_t *)((const char *)(a.y + (int64_t)chunk * a.ldy) + (uint32_t)(o < out1 ? o : 0) * 2u);
             r0 = make_int4(sl, (sl >= 0 && sl < a.row_slots) ? 1 : 0, 0, 0);
             r1 = make_int4(chunk, chunk, chunk, chunk);
         } else {
@@ -290,8 +300,9 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         uint4 braw[C::DEPTH][C::EU][C::BV];
         yvec_t yraw[C::DEPTH][C::EU][C::MX ? 1 : kChunk];
         uint2 yq[C::DEPTH][C::EU];
-        auto load_tile = [&](int lo, auto dconst) {
+        auto load_tile = [&](int lo, auto dconst, auto first_c) {      // first_c: the item's first tile (row items have its y already)
             constexpr int d = decltype(dconst)::value;
+            constexpr bool early = RI && decltype(first_c)::value != 0;
 #pragma unroll
             for (int e = 0; e < C::EU; ++e) {
                 const int o = lo + (e * C::NT + tid) * C::OPL;
@@ -304,8 +315,10 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                         yq[d][e] = *(const uint2 *)(y_lane + (oc & ~3u) * 2u);
                     } else {
 #pragma unroll
-                        for (int c = 0; c < kChunk; ++c)  // rows past the chunk's count are not fetched
-                            if (C::ALLROWS || c == 0 || c < cnt) yraw[d][e][c] = *(const yvec_t *)((const char *)yrow[c] + oc * 2u);
+                        for (int c = 0; c < kChunk; ++c) {  // rows past the chunk's count are not fetched
+                            if (early && c == 0 && e == 0) yraw[d][e][c] = y_early;
+                            else if (C::ALLROWS || c == 0 || c < cnt) yraw[d][e][c] = *(const yvec_t *)((const char *)yrow[c] + oc * 2u);
+                        }
                     }
                 }
             }
@@ -332,7 +345,8 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
 #pragma unroll
         for (int c = 0; c < kChunk; ++c) xp[c] = (const uint4 *)(a.x + (int64_t)(row[c] / a.top_k) * a.ldx);
         uint4 av[C::JPW], xv[kChunk];
-        auto load_flight = [&](int f, int ul, int uh) {
+        auto load_flight = [&](int f, int ul, int uh, auto first_c) {  // first_c: the item's first flight (row items have its x already)
+            constexpr bool early = RI && decltype(first_c)::value != 0;
             const int u = f + ks * 64 + lane;
             const uint32_t ub = (uint32_t)(u < uh ? u : ul) * 16u;
             // The waves past the end of the range issue nothing (a k-slice of an exchange item is often
@@ -355,14 +369,16 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
             // measured).  The count is wave-uniform and the tile loads that follow are unconditional, so
             // the waits for these loads keep a known number in flight.
 #pragma unroll
-            for (int c = 0; c < kChunk; ++c)
-                if (C::ALLROWS || c == 0 || c < cnt) xv[c] = *(const uint4 *)((const char *)xp[c] + ub);
+            for (int c = 0; c < kChunk; ++c) {
+                if (early && c == 0) xv[c] = x_early;
+                else if (C::ALLROWS || c == 0 || c < cnt) xv[c] = *(const uint4 *)((const char *)xp[c] + ub);
+            }
         };
         // Tiles 1 .. DEPTH-1 of the expand are requested once the shrink's operands have been consumed
         // (their registers are free then) and travel while the partial sums are reduced and traded.
         auto load_more_tiles = [&]() {
             static_for<C::DEPTH>([&](auto dc) {
-                if constexpr (decltype(dc)::value >= 1) { if (out0 + dc.value * C::TILE < out1) load_tile(out0 + dc.value * C::TILE, dc); }
+                if constexpr (decltype(dc)::value >= 1) { if (out0 + dc.value * C::TILE < out1) load_tile(out0 + dc.value * C::TILE, dc, IntC<0>{}); }
             });
         };
         // Shrink over the units [ul, uh) of d_in.  Returns, in thread c * RP + j, the sum for row c
@@ -370,7 +386,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         auto shrink_units = [&](int ul, int uh, bool then_tiles) -> float {
             bool first = true;
             for (int f = ul; f < uh; f += C::FLU) {
-                if (f > ul) load_flight(f, ul, uh);
+                if (f > ul) load_flight(f, ul, uh, IntC<0>{});
                 const bool in = f + ks * 64 + lane < uh;
 #pragma unroll
                 for (int c0 = 0; c0 < kChunk; c0 += C::CS) {
@@ -406,9 +422,9 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
             return s;
         };
         const int u_lo = solo ? 0 : kslice * a.kslice_units, u_hi = solo ? U : min(U, u_lo + a.kslice_units);
-        if (do_shrink) load_flight(u_lo, u_lo, u_hi);
+        if (do_shrink) load_flight(u_lo, u_lo, u_hi, IntC<1>{});
         if (do_expand) {                          // the first tile travels with the shrink operands
-            load_tile(out0, IntC<0>{});
+            load_tile(out0, IntC<0>{}, IntC<1>{});
             if (!do_shrink) load_more_tiles();
         }
         if (prof && tid == 0 && first_item) { prof[1] = wall_clock64(); prof[7] = cnt + 100 * (do_shrink ? 1 : 0) + 1000 * (do_expand ? 1 : 0); }
@@ -568,7 +584,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                                 }
                             }
                         }
-                        if (lo + C::DEPTH * C::TILE < out1) load_tile(lo + C::DEPTH * C::TILE, dc);
+                        if (lo + C::DEPTH * C::TILE < out1) load_tile(lo + C::DEPTH * C::TILE, dc, IntC<0>{});
                     }
                 });
             }
@@ -594,6 +610,14 @@ __global__ __launch_bounds__(NW * 64, (NW >= 8 && RP <= 16) ? 4 : 1)
 void rows_kernel(const RowsArgs a)
 {
     rows_body<RP, NW, XCH>(a, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// The launch without a plan: item i is row i (rank 1 and 2).
+template <int RP, int NW>
+__global__ __launch_bounds__(NW * 64, NW >= 8 ? 4 : 1)
+void rows_items_kernel(const RowsArgs a)
+{
+    rows_body<RP, NW, false, true>(a, (int)blockIdx.x, (int)gridDim.x);
 }
 
 // Several sites that share a batch plan in one launch (q/k/v of one layer, or gate/up): site s owns
@@ -733,7 +757,10 @@ static hipError_t launch_rp(RowsArgs a, hipStream_t st)
     const bool exchange = can_exchange(a) && mode == 0 && !a.row_slot;
     set_parts(a, mode == 3 ? 1 : items_target(cap) / a.grid_chunks, exchange);
     a.rank_bound = use_rank_bound(a, cap);
-    if (a.mode == 2) rows_kernel<RP, NW, true><<<dim3((unsigned)fused_grid(a)), dim3(NW * 64), 0, st>>>(a);
+    if (a.row_slot) {
+        if constexpr (RP <= 2) rows_items_kernel<RP, NW><<<dim3((unsigned)fused_grid(a)), dim3(NW * 64), 0, st>>>(a);
+        else return hipErrorInvalidValue;
+    } else if (a.mode == 2) rows_kernel<RP, NW, true><<<dim3((unsigned)fused_grid(a)), dim3(NW * 64), 0, st>>>(a);
     else rows_kernel<RP, NW, false><<<dim3((unsigned)fused_grid(a)), dim3(NW * 64), 0, st>>>(a);
     return hipGetLastError();
 }
