@@ -395,6 +395,27 @@ def bench_copy(steps, warmup, mib=256):
     return {"ms_per_step": ms, "ms_apply_only": ms, "tokens": 0, "launches_per_step": 1, "bytes_per_step": 2 * n}
 
 
+def bench_ceilings(steps=30, warmup=5, mib=256):
+    """Yardsticks measured on the same GPU with library kernels (not this package's): a plain
+    device-to-device copy and an in-place elementwise read-modify-write, each over three 256 MiB
+    buffers in turn (768 MiB, beyond the last-level cache)."""
+    import torch
+    n = (mib << 20) // 2
+    src = [torch.zeros(n, dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+    dst = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+    k = [0]
+
+    def nxt():
+        k[0] += 1
+        return k[0] % 3
+    out = {}
+    for name, fn, nbytes in (("copy", lambda: dst[nxt()].copy_(src[k[0] % 3]), 4 * n),
+                             ("read_modify_write", lambda: src[nxt()].add_(1.0), 4 * n)):
+        ms = time_region(fn, steps, warmup)
+        out[name + "_GBps"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+    return out
+
+
 def summarize(r):
     t = r["ms_apply_only"] * 1e-3
     gbs = r["bytes_per_step"] / t / 1e9
@@ -525,6 +546,10 @@ def main():
         per["c5_seg_wide"] = summarize(bench_c5(M, W, max(10, args.steps // 40), max(3, args.warmup // 40), wide=True, cache_warm=args.cache_warm))
         torch.cuda.empty_cache()
 
+    if args.workload == "all":
+        log("[bench] measured streaming ceilings (library kernels)")
+        per["measured_ceilings"] = bench_ceilings()
+        torch.cuda.empty_cache()
     if args.workload == "copy":
         per["copy_256MiB"] = summarize(bench_copy(max(10, args.steps // 40), max(3, args.warmup // 40)))
     if head is None:      # single non-headline workload: still one JSON line, clearly labelled
@@ -561,6 +586,9 @@ def main():
                                    "projections in 4 launches (q|k|v, o, gate|up, down), HIP-graph replay "
                                    "over 8 distinct layers"},
             "roofline": roofline, "per_config": per}
+    if "measured_ceilings" in per:
+        # the same achieved rate against what library kernels reach on this GPU (context, not the roofline's peak)
+        roofline["frac_of_measured_rmw_stream"] = round(achieved / per["measured_ceilings"]["read_modify_write_GBps"], 4)
     if not args.no_cpu:
         log("[bench] cpu oracle baseline")
         line["cpu_baseline"] = cpu_baseline(W, cases)
