@@ -269,6 +269,39 @@ def test_decode_parts_when_partners_never_answer(M, oracle):
         M.set_tuning("rows_poll_limit", 0)
 
 
+@pytest.mark.parametrize("mode", [1, 3])
+def test_decode_launch_shapes_forced(M, oracle, mode):
+    """The launch shapes a dense site does not get by default at these sizes: parts that each redo
+    the whole shrink (1) and one item per chunk whatever the chunk count (3); alone and grouped."""
+    shapes = [(2304, 1032, 16), (4096, 520, 8), (2304, 2056, 16), (1024, 264, 4)]
+    slots = W.rng(38).integers(-1, 6, size=77).astype(np.int32)
+    cases = [W.dense_case(f"shape{mode}_{i}", 3350 + i, 77, di, do, 6, r, 32.0, token_slot=slots, std_a=0.05, std_b=0.05)
+             for i, (di, do, r) in enumerate(shapes)]
+    sites = [dense_site(M, c) for c in cases]
+    plan = M.Plan(77, 6)
+    M.lora_plan_decode(plan, torch.from_numpy(slots).cuda(), 6)
+    M.set_tuning("rows_mode", mode)
+    try:
+        for c, site in zip(cases, sites):
+            y = P.dev_bf16(c.y0)
+            M.lora_apply_decode_planned(site, plan, P.dev_bf16(c.x), y)
+            torch.cuda.synchronize()
+            ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+            P.check_close(P.host_bits(y), ref, c.name)
+            P.check_untouched(P.host_bits(y), c.y0, c.token_slot < 0, c.name)
+        grp = [0, 2]
+        xs = [P.dev_bf16(cases[k].x) for k in grp]
+        ys = [P.dev_bf16(cases[k].y0) for k in grp]
+        M.lora_apply_decode_multi([sites[k] for k in grp], plan, xs, ys)
+        torch.cuda.synchronize()
+        for k, y in zip(grp, ys):
+            c = cases[k]
+            ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+            P.check_close(P.host_bits(y), ref, c.name + " (grouped)")
+    finally:
+        M.set_tuning("rows_mode", 0)
+
+
 def _plan_words(plan, max_items, n_keys):
     """hdr, sorted and chunk records of a plan buffer (layout: 8 header words, three tables of
     n_keys + 1, four of max_items, then the records)."""
