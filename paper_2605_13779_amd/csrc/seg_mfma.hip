@@ -301,7 +301,11 @@ void seg_expand_kernel(const SegArgs a)
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, kh = lane >> 5;
     const int id = xcd_contiguous_id();
     if (id >= a.n_ranges * a.n_slices) return;
-    const int sl = id / a.n_ranges, rg = id - sl * a.n_ranges;    // ids of one output slice are neighbours
+    // The output slices of one row range are neighbours (same XCD, started together): between them
+    // they sweep whole rows of y, which the memory side serves better than the same slice of many
+    // ranges (1 KB pieces 14 KB apart per workgroup either way; measured 1 % on the call), and they
+    // share the range's h.
+    const int rg = id / a.n_slices, sl = id - rg * a.n_slices;
     const SegRec rr = seg_range(a, rg);
     const int slot = rr.slot, row0 = rr.row0, nrows = rr.rows, tile0 = rr.tile0;
     if (slot < 0 || a.meta.rank[slot] <= 0) return;
