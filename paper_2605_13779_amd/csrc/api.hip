@@ -242,8 +242,9 @@ int32_t stage_table(mlora_site *s, const std::vector<int32_t> &tab, hipStream_t 
     return MLORA_OK;
 }
 
-// Rank-64 prefill: cut the segments into tiles of 64 rows (shrink items) and runs of whole tiles
-// (expand items), in batches that fit the partial-result buffer, and launch shrink + expand per batch.
+// Rank-64 prefill: cut the segments into tiles of 64 rows (shrink items) and into equal groups of
+// 32-row blocks (expand items), in batches that fit the partial-result buffer, and launch shrink +
+// expand per batch.
 int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy,
                        const int32_t *seg_off, const int32_t *seg_slot, int32_t S, hipStream_t st)
 {
@@ -265,14 +266,15 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
     int64_t batch_tiles = kSegMaxTiles;
     if (batch_tiles > kSegHpBlocks - cap) batch_tiles = kSegHpBlocks - cap;
     if (batch_tiles < 1) return MLORA_E_UNSUPPORTED;
-    // tiles per expand run: a run re-reads its 64 KB slice of B_s, so longer runs cost fewer adapter
-    // bytes; shorter runs give more items to balance.  Aim at about four items per CU.
-    int32_t rt = tuning("seg_range_tiles");
-    if (rt < 1) {
-        rt = (int32_t)(n_all * n_slices / 1024);
-        if (rt < 2) rt = 2;
-        if (rt > 8) rt = 8;
-    }
+    // The expand's workgroups come in groups of n_slices (one per output slice) that own the same
+    // rows.  Every group gets the same number of 32-row blocks (+-1), cut out of the batch's block
+    // list wherever that falls -- also inside a segment or across segments (a workgroup then fetches
+    // the next adapter's B rows and goes on).  With whole tile runs of single segments as items, the
+    // launch ran in two to three rounds of uneven items and its time moved by 15 % with the run length.
+    const int32_t cap_e = seg_expand_capacity();
+    if (cap_e <= 0) return MLORA_E_HIP;
+    int32_t groups_wanted = tuning("seg_expand_groups");
+    if (groups_wanted < 1) groups_wanted = cap_e / n_slices > 0 ? cap_e / n_slices : 1;
     for (int64_t t0 = 0; t0 < n_all; t0 += batch_tiles) {
         const int32_t nt = (int32_t)(n_all - t0 < batch_tiles ? n_all - t0 : batch_tiles);
         std::vector<int32_t> tab;
@@ -281,19 +283,47 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
             const Tile &t = tiles[t0 + i];
             tab.push_back(t.slot); tab.push_back(t.row0); tab.push_back(t.rows); tab.push_back(0);
         }
+        // pieces of the groups: walk the batch's 32-row blocks (tile i has one or two)
+        int64_t n_blocks = 0;
+        for (int32_t i = 0; i < nt; ++i) n_blocks += tiles[t0 + i].rows > 32 ? 2 : 1;
+        const int32_t n_groups = (int32_t)(n_blocks < groups_wanted ? n_blocks : groups_wanted);
+        std::vector<int32_t> group_off;
+        group_off.reserve((size_t)n_groups + 1);
         int32_t n_ranges = 0;
-        for (int32_t i = 0; i < nt;) {
-            const Tile &f = tiles[t0 + i];
-            int32_t n = 1, rows = f.rows;
-            while (n < rt && i + n < nt && tiles[t0 + i + n].seg == f.seg) { rows += tiles[t0 + i + n].rows; ++n; }
-            tab.push_back(f.slot); tab.push_back(f.row0); tab.push_back(rows); tab.push_back(i);
-            ++n_ranges;
-            i += n;
+        {
+            int32_t ti = 0, half = 0;                  // next block: half `half` of tile ti
+            int64_t b = 0;
+            for (int32_t g = 0; g < n_groups; ++g) {
+                const int64_t b_end = (int64_t)(g + 1) * n_blocks / n_groups;
+                group_off.push_back(n_ranges);
+                int32_t cur_seg = -1;
+                while (b < b_end) {
+                    const Tile &t = tiles[t0 + ti];
+                    const int32_t r_off = half * 32;
+                    const int32_t rows = (t.rows - r_off) < 32 ? (t.rows - r_off) : 32;
+                    const size_t last = tab.size();
+                    if (t.seg == cur_seg && tab[last - 3] + tab[last - 2] == t.row0 + r_off) {
+                        tab[last - 2] += rows;         // the piece goes on
+                    } else {
+                        tab.push_back(t.slot); tab.push_back(t.row0 + r_off); tab.push_back(rows); tab.push_back(ti * 64 + r_off);
+                        ++n_ranges;
+                        cur_seg = t.seg;
+                    }
+                    ++b;
+                    if (half == 0 && t.rows > 32) half = 1; else { half = 0; ++ti; }
+                }
+            }
+            group_off.push_back(n_ranges);
         }
+        const size_t groups_at = tab.size();
+        tab.insert(tab.end(), group_off.begin(), group_off.end());
         if ((int64_t)tab.size() > (int64_t)s->seg_cap * 3) return MLORA_E_UNSUPPORTED;
         SegArgs a{};
         // a batch whose tables fit the kernel arguments needs no copy in front of its launches
-        a.inl_on = 2 * nt + 3 * n_ranges <= kSegInline && s->d.n_slots <= 0xffff && !tuning("seg_table_copy");
+        bool rows_fit = true;                          // a piece's row count shares a word with its slot
+        for (int32_t j = 0; j < n_ranges; ++j) rows_fit = rows_fit && tab[4 * (nt + j) + 2] <= 0xffff;
+        a.inl_on = 2 * nt + 3 * n_ranges + n_groups + 1 <= kSegInline && s->d.n_slots <= 0xffff && rows_fit &&
+                   !tuning("seg_table_copy");
         if (a.inl_on) {
             for (int32_t i = 0; i < nt; ++i) {
                 a.inl[2 * i] = (uint32_t)tab[4 * i + 1];
@@ -304,6 +334,7 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
                 uint32_t *o = a.inl + 2 * nt + 3 * j;
                 o[0] = (uint32_t)r[1]; o[1] = (uint32_t)r[0] | (uint32_t)r[2] << 16; o[2] = (uint32_t)r[3];
             }
+            for (int32_t g = 0; g <= n_groups; ++g) a.inl[2 * nt + 3 * n_ranges + g] = (uint32_t)group_off[g];
         } else {
             int32_t rc = stage_table(s, tab, st);
             if (rc) return rc;
@@ -312,6 +343,7 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
         a.a_tab = s->a_tab; a.b_tab = s->b_tab; a.meta.rank = s->rank; a.meta.scale = s->scale;
         a.tiles = s->seg_dev; a.n_tiles = nt;
         a.ranges = s->seg_dev + (int64_t)nt * 4; a.n_ranges = n_ranges;
+        a.groups = s->seg_dev + (int64_t)groups_at; a.n_groups = n_groups;
         a.d_in = d_in; a.d_out = d_out;
         a.hcount = (int32_t *)((char *)s->xch + kXchBytes);
         a.hfin = (uint16_t *)((char *)a.hcount + kSegCountBytes);

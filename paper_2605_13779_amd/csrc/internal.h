@@ -101,8 +101,13 @@ struct SegArgs {
     MetaView meta;
     const int32_t *tiles;    // [4 * n_tiles]: slot, first row, rows (<= 64), 0 -- consecutive pieces of the segments
     int32_t n_tiles;
-    const int32_t *ranges;   // [4 * n_ranges]: slot, first row, rows, first tile -- runs of whole tiles of one segment
+    // Expand work: a piece is a run of rows of one segment (slot, first row, rows, row of hfin that
+    // holds its first row's h); it starts on a 32-row block of a tile.  Workgroup group g owns the
+    // pieces [groups[g], groups[g + 1]): every group has the same number of 32-row blocks (+-1).
+    const int32_t *ranges;   // [4 * n_ranges] pieces
     int32_t n_ranges;
+    const int32_t *groups;   // [n_groups + 1]
+    int32_t n_groups;
     int32_t d_in, d_out;
     float *hpart;            // [n_swg + n_tiles][64 rows][64] fp32 partial shrink results, one block per (workgroup, tile) piece
     uint16_t *hfin;          // [n_tiles][64 rows][64 bf16 heads | 64 bf16 tails] scaled shrink result
@@ -111,14 +116,16 @@ struct SegArgs {
     int32_t n_swg;           // workgroups of the shrink launch; n_swg * 3 <= n_tiles * upt
     int32_t n_slices;        // output slices of 512
     // Small batches carry both tables inside the kernel arguments (no table copy in front of the
-    // launches): tile i = words 2i (first row) and 2i + 1 (slot | rows << 16), range j = words
-    // 2 * n_tiles + 3j (first row), + 1 (slot | rows << 16), + 2 (first tile).  inl_on = 0: read tiles / ranges.
+    // launches): tile i = words 2i (first row) and 2i + 1 (slot | rows << 16), piece j = words
+    // 2 * n_tiles + 3j (first row), + 1 (slot | rows << 16), + 2 (hfin row), then n_groups + 1 words
+    // of group offsets.  inl_on = 0: read tiles / ranges / groups.
     int32_t inl_on;
     uint32_t inl[kSegInline];
 };
 hipError_t launch_seg_mfma(const SegArgs &a, hipStream_t st);
 int seg_unit();
 int seg_shrink_capacity();
+int seg_expand_capacity();
 
 int tuning(const char *name);   // api.hip
 uint64_t *debug_prof();         // api.hip

@@ -13,9 +13,11 @@
 //           h as bf16 head + tail (16 mantissa bits reach the expand's MFMA; the shrink result is
 //           never rounded to bf16).  Nobody waits: whoever arrives last does the sum.
 //   expand  Y[rows x 512 outputs] += h * B_s^T
-//           A workgroup owns a run of up to several tiles of one segment and a slice of 512 outputs;
-//           every wave keeps its 64 rows of B_s in registers for the whole run and walks the run 32
-//           rows at a time, with the next block's h and y already requested.  The accumulators pass
+//           A workgroup owns a slice of 512 outputs of a group of rows; every group is the same
+//           number of 32-row blocks (cut wherever that falls, inside or across segments), so the
+//           launch is one round of equal items.  Every wave keeps its 64 rows of B_s in registers
+//           (fetched again where the adapter changes inside the group) and walks the rows 32 at a
+//           time, with the next block's h and y already requested.  The accumulators pass
 //           through a wave-private LDS tile so that the in-place bf16 add on y moves row-contiguous
 //           16-byte pieces.
 //
@@ -84,6 +86,10 @@ __device__ __forceinline__ SegRec seg_range(const SegArgs &a, int j)
         return {(int)(r[1] & 0xffffu), (int)r[0], (int)(r[1] >> 16), (int)r[2]};
     }
     return {a.ranges[4 * j], a.ranges[4 * j + 1], a.ranges[4 * j + 2], a.ranges[4 * j + 3]};
+}
+__device__ __forceinline__ int seg_group_off(const SegArgs &a, int g)
+{
+    return a.inl_on ? (int)a.inl[2 * a.n_tiles + 3 * a.n_ranges + g] : a.groups[g];
 }
 
 // Workgroups are dealt round-robin to the 8 XCDs; work ids are laid out so that an XCD gets a
@@ -300,23 +306,20 @@ void seg_expand_kernel(const SegArgs a)
     __shared__ __attribute__((aligned(16))) float stg_all[NW][16 * ST_LD];
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, kh = lane >> 5;
     const int id = xcd_contiguous_id();
-    if (id >= a.n_ranges * a.n_slices) return;
-    // The output slices of one row range are neighbours (same XCD, started together): between them
-    // they sweep whole rows of y, which the memory side serves better than the same slice of many
-    // ranges (1 KB pieces 14 KB apart per workgroup either way; measured 1 % on the call), and they
-    // share the range's h.
-    const int rg = id / a.n_slices, sl = id - rg * a.n_slices;
-    const SegRec rr = seg_range(a, rg);
-    const int slot = rr.slot, row0 = rr.row0, nrows = rr.rows, tile0 = rr.tile0;
-    if (slot < 0 || a.meta.rank[slot] <= 0) return;
-    const float scale = a.meta.scale[slot];
+    if (id >= a.n_groups * a.n_slices) return;
+    // The output slices of one group of rows are neighbours (same XCD, started together): between
+    // them they sweep whole rows of y, which the memory side serves better than the same slice of
+    // many row ranges (1 KB pieces 14 KB apart per workgroup either way), and they share the rows' h.
+    const int grp = id / a.n_slices, sl = id - grp * a.n_slices;
+    const int p_end = seg_group_off(a, grp + 1);
+    int slot = -1, row0 = 0, nrows = 0;
 
     // this wave's 64 rows of B_s, as operands of the 16 x 16 x 32 MFMA: bv[cb][ks] = ranks
     // ks*32 + kq*8 .. +7 of row o_w + cb*16 + mm
     const int mm = lane & 15, kq = lane >> 4;
     const int o_w = sl * ES + w * 64;
     uint4 bv[4][2];
-    {
+    auto b_load = [&]() {
         const uint16_t *Bg = a.b_tab + (int64_t)slot * a.d_out * 64;
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) {
@@ -324,10 +327,10 @@ void seg_expand_kernel(const SegArgs a)
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) bv[cb][ks] = *(const uint4 *)(Bg + (int64_t)o * 64 + ks * 32 + kq * 8);
         }
-    }
+    };
     // h of a 32-row block is 32 x 256 bytes (64 heads, 64 tails per row): one 16-byte piece per thread
     const int hrow = tid >> 4, hpc = tid & 15;
-    const uint16_t *hf0 = a.hfin + (int64_t)tile0 * (TM * 128) + hpc * 8;
+    const uint16_t *hf0 = a.hfin + hpc * 8;            // + (hfin row of the piece's first row) * 128, per piece
     uint4 hv;
     auto h_fetch = [&](int blk) {
         const int r = min(blk * 32 + hrow, nrows - 1);
@@ -404,14 +407,26 @@ void seg_expand_kernel(const SegArgs a)
             __syncthreads();                           // h tile cur has been read by all; tile cur^1 is complete
         }
     };
-    const int n_blk = (nrows + 31) >> 5;
-    h_fetch(0);
-    y_fetch(0, std::integral_constant<int, 0>{});
-    y_fetch(0, std::integral_constant<int, 1>{});
-    h_store(0);
-    __syncthreads();
-    for (int blk = 0; blk + 1 < n_blk; ++blk) block(blk, std::true_type{});
-    block(n_blk - 1, std::false_type{});
+    // The group's pieces in turn; B_s is fetched again only where the adapter changes (a segment
+    // boundary inside the group).
+    bool first = true;
+    for (int p = seg_group_off(a, grp); p < p_end; ++p) {
+        const SegRec rr = seg_range(a, p);
+        if (rr.slot < 0 || a.meta.rank[rr.slot] <= 0) continue;      // the shrink skips the same rows
+        if (!first) __syncthreads();                   // the last h tile of the piece before has been read by all
+        first = false;
+        if (rr.slot != slot) { slot = rr.slot; b_load(); }
+        row0 = rr.row0; nrows = rr.rows;
+        hf0 = a.hfin + (int64_t)rr.tile0 * 128 + hpc * 8;
+        const int n_blk = (nrows + 31) >> 5;
+        h_fetch(0);
+        y_fetch(0, std::integral_constant<int, 0>{});
+        y_fetch(0, std::integral_constant<int, 1>{});
+        h_store(0);
+        __syncthreads();
+        for (int blk = 0; blk + 1 < n_blk; ++blk) block(blk, std::true_type{});
+        block(n_blk - 1, std::false_type{});
+    }
 }
 
 int seg_unit() { return KU; }
@@ -429,15 +444,28 @@ int seg_shrink_capacity()
     return cap;
 }
 
+int seg_expand_capacity()
+{
+    static int cap = 0;
+    if (cap == 0) {
+        int per_cu = 0, cus = 0, dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, seg_expand_kernel, NT, 0) != hipSuccess) return 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cap = per_cu * cus;
+    }
+    return cap;
+}
+
 hipError_t launch_seg_mfma(const SegArgs &a, hipStream_t st)
 {
-    if (a.n_tiles <= 0 || a.n_ranges <= 0) return hipSuccess;
+    if (a.n_tiles <= 0 || a.n_ranges <= 0 || a.n_groups <= 0) return hipSuccess;
     if (a.n_swg < 1 || a.upt != (a.d_in + KU - 1) / KU) return hipErrorInvalidValue;
     const unsigned gs = (unsigned)((a.n_swg + 7) / 8 * 8);
     seg_shrink_kernel<<<dim3(gs), dim3(NT), 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const unsigned ge = (unsigned)(((int64_t)a.n_ranges * a.n_slices + 7) / 8 * 8);
+    const unsigned ge = (unsigned)(((int64_t)a.n_groups * a.n_slices + 7) / 8 * 8);
     seg_expand_kernel<<<dim3(ge), dim3(NT), 0, st>>>(a);
     return hipGetLastError();
 }
