@@ -535,6 +535,40 @@ def test_segmented_many_tiles_in_batches(M, oracle):
     check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0))
 
 
+@pytest.mark.parametrize("seed", [1, 2])
+def test_prefill_random_segment_structures(M, oracle, seed):
+    """Rank-64 prefill on segment structures nobody picked by hand: segments of 0 .. 200 rows, runs
+    of tiny segments (several per 32-row block), one long segment among short ones; slots of rank
+    64, of a smaller true rank and empty ones, segments without adapter; widths that are not
+    multiples of a workgroup's slice.  (The expand cuts the rows into equal groups of blocks
+    wherever the count falls, so every boundary case of that cut shows up here.)"""
+    rng = np.random.default_rng(9900 + seed)
+    for it in range(12):
+        S = int(rng.integers(1, 7))
+        ranks = [int(rng.choice([64, 64, 64, 37, 0])) for _ in range(S)]
+        if max(ranks) == 0:
+            ranks[0] = 64
+        nseg = int(rng.integers(1, 40))
+        if it % 3 == 0:
+            lens = rng.integers(0, 200, size=nseg)
+        elif it % 3 == 1:
+            lens = rng.integers(0, 12, size=nseg)
+        else:
+            lens = np.concatenate([rng.integers(0, 40, size=nseg), [int(rng.integers(500, 2500))]])
+        lens[0] += 1
+        seg_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        seg_slot = rng.integers(-1, S, size=len(lens)).astype(np.int32)
+        d_in, d_out = int(rng.integers(1, 40)) * 16, int(rng.integers(1, 160)) * 8
+        print(f"prefill{seed}_{it}: T {int(lens.sum())} segs {len(lens)} d_in {d_in} d_out {d_out} ranks {ranks}", flush=True)
+        c = W.seg_case(f"prefill{seed}_{it}", 9950 + 16 * seed + it, int(lens.sum()), len(lens), d_in, d_out, S, 64,
+                       (rng.random(S) * 100 + 1).round(2), ranks=ranks, seg_off=seg_off, seg_slot=seg_slot,
+                       std_a=0.05, std_b=0.05)
+        site = dense_site(M, c)
+        rows = None if c.T <= 600 else np.sort(rng.permutation(c.T)[:400])
+        check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0), rows=rows)
+        site.close()
+
+
 def test_segmented_rejects_bad_offsets(M):
     site = M.Site(64, 64, 64, 2)
     x = torch.zeros((10, 64), dtype=torch.bfloat16, device="cuda")
