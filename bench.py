@@ -12,7 +12,10 @@ forward pass over 36 layers.  The timed loop is a HIP graph replay.
 
 Prints ONE JSON line: tokens/s of the layer step, the HBM roofline of the dominant kernel, and
 the CPU oracle timed on the same workload.  Other configurations are reported under
-"per_config".  `--workload c3|c4|c4d|c4m|c5|c5w` times a single configuration (used for profiling).
+"per_config", together with two yardsticks measured with library kernels on the same GPU (a
+device-to-device copy and an in-place read-modify-write over 768 MiB).
+`--workload c3|c4|c4d|c4m|c5|c5w` times a single configuration (used for profiling);
+`--cache-warm` adds, separately labelled, each step on one buffer set over and over.
 """
 import argparse
 import json
