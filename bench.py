@@ -71,6 +71,12 @@ def time_region(fn, iters, warmup, stats=None):
     return ev[0].elapsed_time(ev[n_b]) / iters
 
 
+def sweeps(steps, per_sweep, least=5):
+    """Whole sweeps over the buffer sets that cover at least `steps` steps, and never fewer than five,
+    so that every timed region splits into five batches (median and minimum are reported)."""
+    return max(least, -(-steps // per_sweep))
+
+
 def graph_of(fn):
     import torch
     fn()                                   # first launch outside capture (module load, lazy init)
@@ -143,7 +149,7 @@ def bench_c2(M, W, steps, warmup, n_layers=8, eager=True, cache_warm=False):
     g_full = graph_of(all_layers)
     g_apply = graph_of(lambda: all_layers(False))
     g_dom = graph_of(lambda: all_layers(True, True))       # the dominant kernel alone: the two grouped launches, as in the step
-    reps, wreps = max(1, steps // n_layers), max(1, warmup // n_layers)
+    reps, wreps = sweeps(steps, n_layers), sweeps(warmup, n_layers, 1)
     st = {}
     ms_full = time_region(g_full.replay, reps, wreps, st) / n_layers
     ms_apply = time_region(g_apply.replay, reps, wreps) / n_layers
@@ -191,7 +197,7 @@ def bench_c3(M, W, steps, warmup, n_sets=24, cache_warm=False):
             M.lora_apply_decode(site, x, y, ts)
 
     g_full = graph_of(sweep)
-    reps, wreps = max(1, steps // n_sets), max(1, warmup // n_sets)
+    reps, wreps = sweeps(steps, n_sets), sweeps(warmup, n_sets, 1)
     st = {}
     ms_full = time_region(g_full.replay, reps, wreps, st) / n_sets
     ms_warm = None
@@ -230,7 +236,7 @@ def bench_c4(M, W, steps, warmup, n_sets=2, fused=True):
                     M.moe_lora_apply_planned(site, plan, x, y)
 
     g_full, g_apply = graph_of(sweep), graph_of(lambda: sweep(False))
-    reps, wreps = max(1, steps // n_sets), max(1, warmup // n_sets)
+    reps, wreps = sweeps(steps, n_sets), sweeps(warmup, n_sets, 1)
     st = {}
     ms_full = time_region(g_full.replay, reps, wreps, st) / n_sets
     ms_apply = time_region(g_apply.replay, reps, wreps) / n_sets
@@ -271,7 +277,7 @@ def bench_c4_down(M, W, steps, warmup, n_sets=2):
 
     g = graph_of(sweep)
     st = {}
-    ms = time_region(g.replay, max(1, steps // n_sets), max(1, warmup // n_sets), st) / n_sets
+    ms = time_region(g.replay, sweeps(steps, n_sets), sweeps(warmup, n_sets, 1), st) / n_sets
     return {"ms_per_step": ms, "ms_apply_only": ms, "tokens": c.T, "launches_per_step": 2,
             "bytes_per_step": moe_down_bytes(c),
             "batch_stats": {k: (v / n_sets if k != "batches" else v) for k, v in st.items()}}
@@ -297,7 +303,7 @@ def bench_c4_mixed(M, W, steps, warmup, n_sets=2):
         for site, x, y in sets:
             M.moe_lora_apply_planned(site, plan, x, y)
 
-    reps, wreps = max(1, steps // n_sets), max(1, warmup // n_sets)
+    reps, wreps = sweeps(steps, n_sets), sweeps(warmup, n_sets, 1)
     ms = time_region(graph_of(sweep).replay, reps, wreps) / n_sets
     M.set_tuning("rows_rank_bound", -1)
     try:
@@ -578,6 +584,9 @@ def main():
                           "trade k-slice sums)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(),
+                "traffic_source": "committed counter summary profiles/c2_decode_layer_hbm_traffic.txt (rocprofv3 --pmc "
+                                  "FETCH_SIZE and WRITE_SIZE runs of this command, scaled by the copy-kernel "
+                                  "calibration); not measured in this run",
                 "alg_bytes_per_launch": head["dom_bytes_per_launch"],
                 "us_per_launch": round(head["dom_us_per_launch"], 3)}
     line = {"metric": "LoRA-applied tokens/s + achieved HBM GB/s (% of peak) per config, 1 MI355X",

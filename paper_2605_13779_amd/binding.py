@@ -6,7 +6,7 @@ import numpy as np
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libmlora.so")
+LIB_PATH = os.environ.get("MLORA_LIB") or os.path.join(HERE, "libmlora.so")   # MLORA_LIB: a variant build of the same library
 
 STATUS = {0: "MLORA_OK", -1: "MLORA_E_INVALID", -2: "MLORA_E_SHAPE", -3: "MLORA_E_SLOT",
           -4: "MLORA_E_SEGMENTS", -5: "MLORA_E_HIP", -6: "MLORA_E_UNSUPPORTED"}

@@ -4,10 +4,8 @@
 
 #include <algorithm>
 #include <cstring>
-#include <map>
-#include <mutex>
+#include <atomic>
 #include <new>
-#include <string>
 #include <vector>
 
 using namespace mlora;
@@ -58,8 +56,11 @@ constexpr int32_t kSegMaxTiles = 256;              // tiles of 64 rows per batch
 constexpr size_t kSegCountBytes = 16384;
 constexpr int32_t kSegHpBlocks = (int32_t)((kSegXchBytes - kXchBytes - kSegCountBytes - (size_t)kSegMaxTiles * 16384) / 16384);
 
-std::mutex g_tune_mu;
-std::map<std::string, int> g_tune;
+std::atomic<int32_t> g_knob[kKnobCount];
+const char *const kKnobName[kKnobCount] = {
+    "rows_poll_limit", "rows_rank_bound", "rows_items_target", "rows_mode", "rows_waves", "rows_prefetch", "plan_general",
+    "plan_separate", "plan_pipeline", "seg_expand_groups", "seg_table_copy", "seg_shrink_wgs", "seg_no_mfma", "seg_fused",
+    "upload_piece_kb", "down_tile_rows"};
 
 // Host-side record of a slot's rank (the kernels read the device table; this only tells the launch
 // code whether any slot is padded, i.e. whether rank-bounded reads of A can save traffic).
@@ -176,7 +177,9 @@ RowsArgs rows_args(const mlora_site *s, const void *x, int64_t ldx, void *y, int
     a.n_experts = s->E; a.top_k = 1;
     a.xch = s->xch; a.ctrl = s->ctrl; a.xch_chunks = s->xch ? kXchChunks : 0;   // a rank-64 site's larger area holds these too
     a.rank_bound = s->n_short > 0 ? 1 : 0;      // the launch code keeps it only where it pays
+#ifdef MLORA_PROF
     a.prof = debug_prof();
+#endif
     return a;
 }
 
@@ -194,7 +197,7 @@ int32_t plan_decode_impl(mlora_plan *plan, const int32_t *token_slot, int32_t T,
     plan->items = T; plan->top_k = 1; plan->n_experts = 1; plan->n_slots = n_slots; plan->moe = false;
     plan->grid_chunks = (int32_t)max_chunks(T, n_slots);
     hipError_t e;
-    if (T <= kDensePrivItems && !tuning("plan_general"))
+    if (T <= kDensePrivItems && !tuning(kPlanGeneral))
         e = launch_plan_dense_small(plan->pv, token_slot, T, n_slots, ready_rank, st);
     else
         e = launch_plan_general(plan->pv, nullptr, token_slot, T, 1, 1, n_slots, ready_rank, nullptr, nullptr, st);
@@ -273,7 +276,7 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
     // launch ran in two to three rounds of uneven items and its time moved by 15 % with the run length.
     const int32_t cap_e = seg_expand_capacity();
     if (cap_e <= 0) return MLORA_E_HIP;
-    int32_t groups_wanted = tuning("seg_expand_groups");
+    int32_t groups_wanted = tuning(kSegExpandGroups);
     if (groups_wanted < 1) groups_wanted = cap_e / n_slices > 0 ? cap_e / n_slices : 1;
     for (int64_t t0 = 0; t0 < n_all; t0 += batch_tiles) {
         const int32_t nt = (int32_t)(n_all - t0 < batch_tiles ? n_all - t0 : batch_tiles);
@@ -323,7 +326,7 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
         bool rows_fit = true;                          // a piece's row count shares a word with its slot
         for (int32_t j = 0; j < n_ranges; ++j) rows_fit = rows_fit && tab[4 * (nt + j) + 2] <= 0xffff;
         a.inl_on = 2 * nt + 3 * n_ranges + n_groups + 1 <= kSegInline && s->d.n_slots <= 0xffff && rows_fit &&
-                   !tuning("seg_table_copy");
+                   !tuning(kSegTableCopy);
         if (a.inl_on) {
             for (int32_t i = 0; i < nt; ++i) {
                 a.inl[2 * i] = (uint32_t)tab[4 * i + 1];
@@ -350,7 +353,7 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
         a.hpart = (float *)((char *)a.hfin + (size_t)kSegMaxTiles * 16384);
         a.upt = upt; a.n_slices = n_slices;
         int64_t swg = (int64_t)nt * upt / 3;               // every workgroup keeps three units in flight
-        const int tuned = tuning("seg_shrink_wgs");
+        const int tuned = tuning(kSegShrinkWgs);
         // As many workgroups as the GPU holds at once; a whole number per tile instead, where that
         // still fills three quarters of it: no share then crosses a tile boundary, and a share that
         // does pays a hand-over in the middle of its stream (c5: 405 workgroups, three per tile,
@@ -367,22 +370,24 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
 
 }  // namespace
 
+#ifdef MLORA_PROF
 static uint64_t *g_prof = nullptr;
+#endif
 namespace mlora {
+#ifdef MLORA_PROF
 uint64_t *debug_prof() { return g_prof; }
-int tuning(const char *name)
-{
-    std::lock_guard<std::mutex> g(g_tune_mu);
-    auto it = g_tune.find(name);
-    return it == g_tune.end() ? 0 : it->second;
-}
+#endif
+int tuning(Knob k) { return g_knob[k].load(std::memory_order_relaxed); }
 }  // namespace mlora
 
 extern "C" {
 
-// Debug hook (not part of the public header): device buffer that receives per-workgroup
-// phase timestamps of the vector kernel, 8 x uint64 per workgroup; null switches it off.
+#ifdef MLORA_PROF
+// Profiling builds only (-DMLORA_PROF; not in the default library, not in the public header): device
+// buffer that receives per-workgroup phase timestamps of the vector kernel, 8 x uint64 per
+// workgroup; null switches it off.
 void mlora_debug_set_prof(void *dev) { g_prof = (uint64_t *)dev; }
+#endif
 
 const char *mlora_status_str(int32_t st)
 {
@@ -401,9 +406,12 @@ const char *mlora_status_str(int32_t st)
 int32_t mlora_set_tuning(const char *name, int32_t value)
 {
     if (!name) return MLORA_E_INVALID;
-    std::lock_guard<std::mutex> g(g_tune_mu);
-    g_tune[name] = value;
-    return MLORA_OK;
+    for (int k = 0; k < kKnobCount; ++k)
+        if (std::strcmp(name, kKnobName[k]) == 0) {
+            g_knob[k].store(value, std::memory_order_relaxed);
+            return MLORA_OK;
+        }
+    return MLORA_E_INVALID;                        // unknown knob
 }
 
 int32_t mlora_site_bytes(const mlora_site_desc *d, size_t *a_tab, size_t *b_tab, size_t *meta, size_t *scratch)
@@ -596,7 +604,7 @@ int32_t lora_slots_upload_experts(mlora_site *s, int32_t slot, int64_t catalog_i
     // after a failed copy the earlier pieces may still be leaving the image: wait before it can be reused
     auto drain = [&]() { (void)hipStreamSynchronize(st); return (int32_t)MLORA_E_HIP; };
     const int64_t a_exp = rp * s->d.d_in * 2, b_exp = (int64_t)s->d.d_out * rp * 2;       // bytes per expert
-    const int64_t piece = (int64_t)(tuning("upload_piece_kb") > 0 ? tuning("upload_piece_kb") : 2048) << 10;
+    const int64_t piece = (int64_t)(tuning(kUploadPieceKb) > 0 ? tuning(kUploadPieceKb) : 2048) << 10;
     const int64_t a_step = std::max<int64_t>(1, piece / a_exp), b_step = std::max<int64_t>(1, piece / b_exp);
     for (int64_t e0 = 0; e0 < E; e0 += a_step) {
         const int64_t e1 = std::min(E, e0 + a_step);
@@ -625,7 +633,9 @@ int32_t mlora_site_check(mlora_site *s, void *stream)
     uint32_t flag = 0;
     if (!ok(hipMemcpy(&flag, s->ctrl + 1, sizeof flag, hipMemcpyDeviceToHost))) return MLORA_E_HIP;
     if (flag) {
-        (void)launch_fill_i32((int32_t *)s->ctrl + 1, 0, 1, (hipStream_t)stream);
+        // back to a working exchange: counters and flag cleared, a fresh tag
+        (void)launch_fill_i32((int32_t *)s->ctrl, 0, (int64_t)(kCtrlBytes / 4), (hipStream_t)stream);
+        (void)launch_fill_i32((int32_t *)s->ctrl, 1, 1, (hipStream_t)stream);
         return MLORA_E_HIP;
     }
     return MLORA_OK;
@@ -778,8 +788,8 @@ int32_t lora_plan_apply_decode_multi(mlora_site *const *sites, int32_t n_sites, 
     RowsArgs grp[kMaxMulti];
     int32_t n = 0;
     if (T <= rows_local_plan_rows() && n_slots <= rows_local_plan_slots() && max_chunks(T, n_slots) <= rows_local_plan_rows() &&
-        !tuning("plan_general") &&
-        !tuning("plan_separate")) {
+        !tuning(kPlanGeneral) &&
+        !tuning(kPlanSeparate)) {
         while (n < n_sites && n < kMaxMulti) {
             RowsArgs a = rows_args(sites[n], xs[n], ldxs[n], ys[n], ldys[n]);
             a.chunks = plan->pv.chunks; a.top_k = 1; a.grid_chunks = (int32_t)max_chunks(T, n_slots);
@@ -900,7 +910,7 @@ int32_t lora_apply_decode(mlora_site *s, const void *x, int64_t ldx, void *y, in
     DeviceGuard g(s->d.device);
     if (!g.good) return MLORA_E_HIP;
     hipStream_t st = (hipStream_t)stream;
-    if (s->r_pad <= 2 && !tuning("plan_general") && !tuning("plan_separate")) {
+    if (s->r_pad <= 2 && !tuning(kPlanGeneral) && !tuning(kPlanSeparate)) {
         // Tiny adapters (the compact rank-1 catalog of Section 4): rows are applied one by one, without
         // a plan -- grouping would save at most two adapter rows per row, a planner launch costs more.
         RowsArgs a = rows_args(s, x, ldx, y, ldy);
@@ -915,7 +925,7 @@ int32_t lora_apply_decode(mlora_site *s, const void *x, int64_t ldx, void *y, in
         // a small batch on a site whose launch can plan for itself needs no planner launch (same plan,
         // same bits; see lora_plan_apply_decode_multi)
         if (n <= rows_local_plan_rows() && s->d.n_slots <= rows_local_plan_slots() &&
-            max_chunks(n, s->d.n_slots) <= rows_local_plan_rows() && !tuning("plan_general") && !tuning("plan_separate")) {
+            max_chunks(n, s->d.n_slots) <= rows_local_plan_rows() && !tuning(kPlanGeneral) && !tuning(kPlanSeparate)) {
             mlora_plan *plan = &s->priv;
             RowsArgs a = rows_args(s, xs, ldx, ys, ldy);
             a.chunks = plan->pv.chunks; a.top_k = 1; a.grid_chunks = (int32_t)max_chunks(n, s->d.n_slots);
@@ -953,7 +963,7 @@ int32_t lora_apply_segmented(mlora_site *s, const void *x, int64_t ldx, void *y,
     if (!g.good) return MLORA_E_HIP;
     hipStream_t st = (hipStream_t)stream;
 
-    const bool mfma = s->r_pad == 64 && (s->d.d_in & 15) == 0 && s->xch && !tuning("seg_no_mfma");
+    const bool mfma = s->r_pad == 64 && (s->d.d_in & 15) == 0 && s->xch && !tuning(kSegNoMfma);
     if (mfma) return segmented_mfma(s, x, ldx, y, ldy, seg_off, seg_slot, S, st);
     std::vector<int32_t> tab;
     for (int32_t k = 0; k < S; ++k) {

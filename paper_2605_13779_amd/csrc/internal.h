@@ -78,7 +78,9 @@ struct RowsArgs {
     // out_f32[p, :] (no read); a second launch adds a token's rows in order
     float *out_f32; int64_t ldo;
     const float *row_w;
-    uint64_t *prof;          // debug: per-workgroup phase timestamps (null in normal use)
+#ifdef MLORA_PROF
+    uint64_t *prof;          // per-workgroup phase timestamps (builds with -DMLORA_PROF only)
+#endif
 };
 hipError_t launch_rows(const RowsArgs &a, hipStream_t st);
 constexpr int kMaxMulti = 4;     // sites per grouped launch
@@ -127,8 +129,17 @@ int seg_unit();
 int seg_shrink_capacity();
 int seg_expand_capacity();
 
-int tuning(const char *name);   // api.hip
-uint64_t *debug_prof();         // api.hip
+// Launch-shape overrides (mlora_set_tuning): one relaxed atomic per knob, 0 = automatic.  Sweeps and
+// tests set them; the launch code reads each knob it needs once per call.
+enum Knob {
+    kRowsPollLimit, kRowsRankBound, kRowsItemsTarget, kRowsMode, kRowsWaves, kRowsPrefetch, kPlanGeneral, kPlanSeparate,
+    kPlanPipeline, kSegExpandGroups, kSegTableCopy, kSegShrinkWgs, kSegNoMfma, kSegFused, kUploadPieceKb, kDownTileRows,
+    kKnobCount
+};
+int tuning(Knob k);             // api.hip
+#ifdef MLORA_PROF
+uint64_t *debug_prof();         // api.hip (builds with -DMLORA_PROF only)
+#endif
 
 }  // namespace mlora
 
@@ -150,6 +161,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 // own work is done, sees all sign-ins, clears the counters and advances the tag.  ctrl[1] is an
 // error flag raised when a bounded wait gives up.
 constexpr int kSpinLimit = 1 << 18;
+constexpr uint32_t kTagPoison = 0xffffffffu;   // exchange switched off after a bounded wait gave up (see tag_advance)
 constexpr int kPollLimit = 512;   // polls of an exchange word before a reader computes the value itself
 
 __device__ __forceinline__ void xch_put(uint64_t *p, float v, uint32_t tag)
@@ -167,7 +179,7 @@ __device__ __forceinline__ uint32_t tag_read(const uint32_t *ctrl)
 // One thread per workgroup, after its tag_read has returned (the branch makes the add depend on it).
 __device__ __forceinline__ void tag_sign_in(uint32_t *ctrl, int wg, uint32_t tag)
 {
-    if (tag != 0xffffffffu)
+    if (tag != kTagPoison)
         (void)__hip_atomic_fetch_add(ctrl + 8 + (wg & 63), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 // Called by one full wave of the last workgroup of the grid when its work is done.
@@ -186,11 +198,16 @@ __device__ __forceinline__ void tag_advance(uint32_t *ctrl, int n_wg, uint32_t t
         __hip_atomic_store(ctrl + 8 + lane, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (lane == 0) {
             uint32_t nt = tag + 1;
-            if (nt == 0 || nt == 0xffffffffu) nt = 1;
+            if (nt == 0 || nt == kTagPoison) nt = 1;
             __hip_atomic_store(ctrl, nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     } else if (lane == 0) {
-        __hip_atomic_store(ctrl + 1, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // never expected
+        // Never expected.  The sign-in count can no longer be trusted, so no later launch may take a
+        // word of the exchange area for current: the tag is set to a value under which every item runs
+        // on its own (whole shrink, nothing published, nothing awaited; results stay right) until
+        // mlora_site_check has reported the flag and reset the control block.
+        __hip_atomic_store(ctrl, kTagPoison, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(ctrl + 1, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 

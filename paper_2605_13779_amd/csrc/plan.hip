@@ -329,7 +329,7 @@ void plan_route_one_kernel(PlanView pv, const int32_t *__restrict__ topk, const 
 
 bool plan_route_in_one_launch(int64_t P, int64_t NK)
 {
-    return P <= kOnePairs && NK <= kOneKeys && !tuning("plan_pipeline");
+    return P <= kOnePairs && NK <= kOneKeys && !tuning(kPlanPipeline);
 }
 
 hipError_t launch_plan_general(const PlanView &pv, const int32_t *topk, const int32_t *token_slot,

@@ -168,7 +168,11 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int jg = w % C::JG, ks = w / C::JG;
     const int U = a.d_in >> 3;                               // 16-byte units per row of x / A
-    uint64_t *prof = a.prof ? a.prof + (int64_t)wg * 8 : nullptr;
+#ifdef MLORA_PROF
+    uint64_t *prof = a.prof ? a.prof + (int64_t)wg * 8 : nullptr;     // per-phase timestamps (profiling builds)
+#else
+    constexpr uint64_t *prof = nullptr;                              // the stamps below compile away
+#endif
     if (prof && tid == 0) { prof[0] = wall_clock64(); prof[7] = 0; }
 
     const bool use_x = XCH && a.mode != 0;                   // this site's items exchange partial results
@@ -202,18 +206,16 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         // ---- which chunk, which part of it ----
         int chunk, kslice = 0, out0 = 0, out1 = a.d_out;
         bool do_shrink = true, do_expand = true;
-        const bool solo = solo_next;
-        solo_next = false;
+        int part_i = 0;
         if (a.tile_par > 1) {
             // workgroups are dealt round-robin to the 8 XCDs: keep the parts of one chunk (they share
             // the chunk's rows of x and its exchange words) on one XCD and its L2, and deal the chunks
             // over the XCDs
             const int idx = item >> 3, grp8 = idx / a.tile_par;
-            const int part_i = idx - grp8 * a.tile_par;
+            part_i = idx - grp8 * a.tile_par;
             chunk = grp8 * 8 + (item & 7);
             out0 = part_i * a.out_per_part; out1 = min(a.d_out, out0 + a.out_per_part);
             do_expand = out0 < out1;
-            if (use_x && !solo) { kslice = part_i; do_shrink = part_i < a.ksplit; }   // else every part does the whole shrink
             if (chunk >= a.grid_chunks) continue;
         } else {
             // neighbouring chunks can belong to one adapter (and expert): keep them on one XCD, where
@@ -262,6 +264,11 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         }
         if (prof && tid == 0 && first_item) prof[6] = wall_clock64();      // ... and the launch tag
         if (cnt <= 0) { first_item = false; continue; }            // record past the live chunks of this batch
+        // An item runs on its own (whole shrink, nothing published or awaited) when its bounded wait
+        // has just given up, or when an earlier launch's give-up has switched the exchange off.
+        const bool solo = solo_next || (XCH && tag == kTagPoison);
+        solo_next = false;
+        if (a.tile_par > 1 && use_x && !solo) { kslice = part_i; do_shrink = part_i < a.ksplit; }   // else every part does the whole shrink
 #pragma unroll
         for (int c = 1; c < kChunk; ++c) row[c] = c < cnt ? row[c] : row[0];
         static_assert(kChunk == 4 && kRec == 8, "record layout: two 16-byte loads");
@@ -600,7 +607,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         if (wg == n_wg - 1 && w == 0) {
             if (!first_item) tag = s_tag;
             else tag = __shfl(tag, 0, 64);
-            tag_advance(a.ctrl, n_wg, tag, lane);
+            if (tag != kTagPoison) tag_advance(a.ctrl, n_wg, tag, lane);
         }
     }
 }
@@ -714,7 +721,7 @@ static void set_parts(RowsArgs &a, int parts, bool exchange)
     a.mode = 0; a.ksplit = 1; a.kslice_units = U;
     // "rows_poll_limit" (testing): a negative value makes every reader give up at once, so that each
     // item runs the path that does not depend on other workgroups
-    const int pl = tuning("rows_poll_limit");
+    const int pl = tuning(kRowsPollLimit);
     a.poll_limit = pl < 0 ? 0 : (pl > 0 ? pl : kPollLimit);
     if (exchange && a.tile_par > 1) {
         int ku = (U + a.tile_par - 1) / a.tile_par;
@@ -735,7 +742,7 @@ static int fused_grid(const RowsArgs &a)
 // items), not where the launch is one short chain.  "rows_rank_bound": 1 always, -1 never.
 static int use_rank_bound(const RowsArgs &a, int cap)
 {
-    const int t = tuning("rows_rank_bound");
+    const int t = tuning(kRowsRankBound);
     if (t) return t > 0 ? 1 : 0;
     return a.rank_bound && a.mode != 2 && (int64_t)a.grid_chunks * 2 >= cap;
 }
@@ -744,14 +751,14 @@ static int items_target(int cap)
 {
     // the chunk count used for the division is an upper bound; live chunks are fewer, and a launch
     // whose live items all fit on the GPU at once finishes in one round (measured best at 3/4)
-    const int t = tuning("rows_items_target");
+    const int t = tuning(kRowsItemsTarget);
     return t > 0 ? t : cap * 3 / 4;
 }
 
 template <int RP, int NW>
 static hipError_t launch_rp(RowsArgs a, hipStream_t st)
 {
-    const int mode = tuning("rows_mode");     // 0 auto, 1 parts that redo the shrink, 3 one item per chunk
+    const int mode = tuning(kRowsMode);     // 0 auto, 1 parts that redo the shrink, 3 one item per chunk
     const int cap = rows_capacity<RP, NW, true>();
     if (cap <= 0) return hipErrorUnknown;
     const bool exchange = can_exchange(a) && mode == 0 && !a.row_slot;
@@ -769,7 +776,7 @@ template <int RP>
 static hipError_t launch_nw(const RowsArgs &a, hipStream_t st)
 {
     const int U = a.d_in >> 3;
-    int nw = tuning("rows_waves");
+    int nw = tuning(kRowsWaves);
     if (nw != 4 && nw != 8) nw = U >= RowsCfg<RP, 8>::FLU * 3 / 4 ? 8 : 4;   // 4 when 8 would be mostly idle lanes
     if constexpr (RP >= 64) nw = 8;
     if (nw >= 8) return launch_rp<RP, 8>(a, st);
@@ -787,7 +794,7 @@ static hipError_t launch_multi_rp(const RowsArgs *sites, int n, hipStream_t st, 
     m.first[0] = 0;
     // every item of the launch should move about the same number of bytes
     double total = 0.0;
-    bool exchange = tuning("rows_mode") == 0;
+    bool exchange = tuning(kRowsMode) == 0;
     for (int k = 0; k < n; ++k) { total += chunk_bytes(sites[k]); exchange = exchange && can_exchange(sites[k]); }
     const double per_item = total * sites[0].grid_chunks / items_target(cap);
     bool any_x = false;
@@ -818,7 +825,7 @@ static hipError_t launch_multi_rp(const RowsArgs *sites, int n, hipStream_t st, 
 // 8-wave shrink busy, a packed MoE site takes 4 waves when 8 would be mostly idle.
 int rows_group_waves(const RowsArgs &a)
 {
-    if ((a.r_pad != 8 && a.r_pad != 16) || a.out_f32 || tuning("rows_waves")) return 0;
+    if ((a.r_pad != 8 && a.r_pad != 16) || a.out_f32 || tuning(kRowsWaves)) return 0;
     const int U = a.d_in >> 3;
     const int flu8 = a.r_pad == 8 ? RowsCfg<8, 8>::FLU : RowsCfg<16, 8>::FLU;
     if (U >= flu8 * 3 / 4) return 8;
@@ -843,7 +850,7 @@ static bool wide_enough_for_8_waves(int U) { return RP >= 64 || U >= RowsCfg<RP,
 
 bool rows_plans_alone(const RowsArgs &a)
 {
-    if (a.n_experts != 1 || a.out_f32 || tuning("rows_waves")) return false;
+    if (a.n_experts != 1 || a.out_f32 || tuning(kRowsWaves)) return false;
     const int U = a.d_in >> 3;
     switch (a.r_pad) {
         case 1:  return wide_enough_for_8_waves<1>(U);

@@ -33,6 +33,17 @@ def check_close(got_bits, ref, what=""):
     return float(err.max()), float((err / np.maximum(np.abs(ref), 1e-30)).max())
 
 
+def report(config, got_bits, ref, n_units, unit):
+    """One line of the per-config error table (max abs error; max relative error where |ref| >= 1e-3).
+    Collected by running the GPU tests with -s."""
+    got = widen(got_bits)
+    err = np.abs(got - ref)
+    big = np.abs(ref) >= 1e-3
+    rel = float((err[big] / np.abs(ref[big])).max()) if big.any() else 0.0
+    print(f"PARITY {config}: {n_units} {unit} compared (all of them), max_abs_err {err.max():.3g}, max_rel_err {rel:.3g}",
+          flush=True)
+
+
 def check_delta(got_bits, delta_ref, what=""):
     """y0 = 0 run: the output is the LoRA delta, rounded once to bf16."""
     got = widen(got_bits)

@@ -48,12 +48,16 @@ def run_decode(M, site, c, y0_bits, planned=False):
     return P.host_bits(y)
 
 
-def check_dense(M, oracle, c, runner, rows=None):
-    """Full comparison + the three vacuity guards.  rows: optional subset of rows sent to the oracle."""
+def check_dense(M, oracle, c, runner, rows=None, report=None):
+    """Full comparison + the three vacuity guards.  rows: optional subset of rows sent to the oracle
+    (never used on the benchmark configurations); report: name of a line of the error table."""
     sel = np.arange(c.T) if rows is None else np.asarray(rows)
     ref = oracle.apply_decode(c.x[sel], c.y0[sel], c.A, c.B, c.rank, c.alpha, c.token_slot[sel])
     got = runner(c.y0)
     P.check_close(got[sel], ref, c.name)
+    if report:
+        assert rows is None
+        P.report(report, got, ref, c.T, "rows")
     eff = np.array([s >= 0 and c.rank[s] > 0 for s in c.token_slot])
     P.check_untouched(got, c.y0, ~eff, c.name)
     zero = np.zeros_like(c.y0)
@@ -68,7 +72,7 @@ def check_dense(M, oracle, c, runner, rows=None):
 def test_c1_tiny_decode(M, oracle):
     c = W.c1_tiny_decode()
     site = dense_site(M, c)
-    check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0))
+    check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0), report=c.name)
     check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0, planned=True))
 
 
@@ -269,6 +273,44 @@ def test_decode_parts_when_partners_never_answer(M, oracle):
         M.set_tuning("rows_poll_limit", 0)
 
 
+def test_decode_after_an_exchange_wait_gave_up(M, oracle):
+    """If the last workgroup of a launch ever gives up waiting for the other workgroups' sign-ins, it
+    leaves the site's launch tag at a value that switches the exchange of partial sums off: every
+    later item runs on its own until mlora_site_check has reported the flag and reset the control
+    block.  The host plants that state here (the control block sits in front of the 1 MiB of
+    exchange words at the end of a site's scratch buffer); results must stay right, the check must
+    report once, and the launches after it must trade partial sums again (same bits as before)."""
+    c = W.dense_case("poison", 3360, 77, 4608, 520, 6, 16, 32.0, std_a=0.05, std_b=0.05)     # few chunks, large d_in: parts that trade
+    site = dense_site(M, c)
+    plan = M.Plan(77, 6)
+    M.lora_plan_decode(plan, torch.from_numpy(c.token_slot).cuda(), 6)
+    x = P.dev_bf16(c.x)
+    ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+
+    def run():
+        y = P.dev_bf16(c.y0)
+        M.lora_apply_decode_planned(site, plan, x, y)
+        torch.cuda.synchronize()
+        return P.host_bits(y)
+    before = run()
+    P.check_close(before, ref, "before")
+    site.check()
+    ctrl = site.bufs[3][site.bytes[3] - (1 << 20) - 1024:][:1024].view(torch.int32)
+    assert int(ctrl[0]) >= 2 and int(ctrl[1]) == 0           # the launch tag has moved on, no flag
+    ctrl[0] = -1                                             # the switched-off value
+    ctrl[1] = 2
+    torch.cuda.synchronize()
+    for _ in range(2):
+        P.check_close(run(), ref, "exchange switched off")
+        assert int(ctrl[0]) == -1
+    with pytest.raises(M.MLoraError):
+        site.check()
+    site.check()                                             # reported once, then clear
+    assert int(ctrl[0]) == 1 and int(ctrl[1]) == 0
+    assert np.array_equal(run(), before)
+    assert int(ctrl[0]) == 2
+
+
 @pytest.mark.parametrize("mode", [1, 3])
 def test_decode_launch_shapes_forced(M, oracle, mode):
     """The launch shapes a dense site does not get by default at these sizes: parts that each redo
@@ -443,13 +485,12 @@ def test_graph_replay_keeps_results_right(M, oracle):
 
 def test_c2_dense_decode_layer(M, oracle):
     """The seven projections at full size, each in a launch of its own and then in the launch
-    configuration the benchmark times (q|k|v and gate|up grouped, o and down alone); 48 sampled
-    rows go to the oracle."""
+    configuration the benchmark times (the step's first launch plans inside itself for q|k|v, then o,
+    gate|up grouped, down); every one of the 256 rows goes to the oracle, also in the y0 = 0 run."""
     cases = W.c2_dense_decode()
     ts = torch.from_numpy(cases[0].token_slot).cuda()
     plan = M.Plan(256, 64)
     M.lora_plan_decode(plan, ts, 64)
-    sample = W.rng(77).permutation(256)[:48]
     sites = []
     for c in cases:
         site = dense_site(M, c)
@@ -460,20 +501,32 @@ def test_c2_dense_decode_layer(M, oracle):
             M.lora_apply_decode_planned(site, plan, x, y)
             torch.cuda.synchronize()
             return P.host_bits(y)
-        check_dense(M, oracle, c, runner, rows=sample)
-    xs = [P.dev_bf16(c.x) for c in cases]
-    ys = [P.dev_bf16(c.y0) for c in cases]
-    for grp in [(0, 1, 2), (3,), (4, 5), (6,)]:
-        if len(grp) == 1:
-            M.lora_apply_decode_planned(sites[grp[0]], plan, xs[grp[0]], ys[grp[0]])
-        else:
-            M.lora_apply_decode_multi([sites[k] for k in grp], plan, [xs[k] for k in grp], [ys[k] for k in grp])
-    torch.cuda.synchronize()
-    for c, site, y in zip(cases, sites, ys):
-        ref = oracle.apply_decode(c.x[sample], c.y0[sample], c.A, c.B, c.rank, c.alpha, c.token_slot[sample])
-        got = P.host_bits(y)
-        P.check_close(got[sample], ref, c.name + " (layer launches)")
-        P.check_untouched(got, c.y0, c.token_slot < 0, c.name)
+        check_dense(M, oracle, c, runner, report=c.name + " (own launch)")
+
+    def layer(y0s):
+        """One layer step as bench.py issues it: four launches, the first one plans."""
+        step_plan = M.Plan(256, 64)
+        xs = [P.dev_bf16(c.x) for c in cases]
+        ys = [P.dev_bf16(y0) for y0 in y0s]
+        for gi, grp in enumerate([(0, 1, 2), (3,), (4, 5), (6,)]):
+            if gi == 0:
+                M.lora_plan_apply_decode_multi([sites[k] for k in grp], step_plan, ts, 64, [xs[k] for k in grp], [ys[k] for k in grp])
+            elif len(grp) == 1:
+                M.lora_apply_decode_planned(sites[grp[0]], step_plan, xs[grp[0]], ys[grp[0]])
+            else:
+                M.lora_apply_decode_multi([sites[k] for k in grp], step_plan, [xs[k] for k in grp], [ys[k] for k in grp])
+        torch.cuda.synchronize()
+        return [P.host_bits(y) for y in ys]
+
+    got = layer([c.y0 for c in cases])
+    gz = layer([np.zeros_like(c.y0) for c in cases])
+    for c, site, g, z in zip(cases, sites, got, gz):
+        ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+        P.check_close(g, ref, c.name + " (layer launches)")
+        P.report(c.name + " (layer step launches)", g, ref, c.T, "rows")
+        P.check_untouched(g, c.y0, c.token_slot < 0, c.name)
+        dref = oracle.apply_decode(c.x, np.zeros_like(c.y0), c.A, c.B, c.rank, c.alpha, c.token_slot)
+        P.check_delta(z, dref, c.name + " delta (layer launches)")
         site.check()
         site.close()
 
@@ -481,7 +534,7 @@ def test_c2_dense_decode_layer(M, oracle):
 def test_c3_rank1_catalog(M, oracle):
     c = W.c3_rank1_catalog()
     site = dense_site(M, c)
-    check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0))
+    check_dense(M, oracle, c, lambda y0: run_decode(M, site, c, y0), report=c.name)
     assert np.array_equal(site.meta()[2], c.catalog_id)
 
 
@@ -579,21 +632,16 @@ def test_segmented_rejects_bad_offsets(M):
         assert e.value.status == code
 
 
-def test_c5_segmented_sampled(M, oracle):
-    """Full-size prefill (both widths); the oracle checks a sample of rows that covers every
-    segment's first and last row."""
-    for wide in (False, True):
-        c = W.c5_segmented(wide)
-        site = dense_site(M, c)
-        rows = set(W.rng(5).permutation(c.T)[:40].tolist())
-        for k in range(16):
-            rows.add(int(c.seg_off[k]))
-            rows.add(int(c.seg_off[k + 1] - 1))
-        rows = np.array(sorted(rows))
-        check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0), rows=rows)
-        site.close()
-        del site
-        torch.cuda.empty_cache()
+@pytest.mark.parametrize("wide", [False, True])
+def test_c5_segmented_full(M, oracle, wide):
+    """Full-size prefill (7168 -> 7168 and 7168 -> 18432): all 8192 rows go to the oracle, with the
+    batch's y0 and with y0 = 0."""
+    c = W.c5_segmented(wide)
+    site = dense_site(M, c)
+    check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0), report=c.name)
+    site.close()
+    del site
+    torch.cuda.empty_cache()
 
 
 # ------------------------------------------------------------------ MoE
@@ -614,7 +662,7 @@ def run_moe(M, site, c, y0_bits, want_idx=True):
     return P.host_bits(y), (sp.cpu().numpy() if want_idx else None), (go.cpu().numpy() if want_idx else None)
 
 
-def check_moe(M, oracle, c, site, pairs=None):
+def check_moe(M, oracle, c, site, pairs=None, report=None):
     sel = np.arange(c.T * c.K) if pairs is None else np.asarray(pairs)
     got, sp, go = run_moe(M, site, c, c.y0)
     rsp, rgo = oracle.route_sort(c.topk, c.token_slot, c.rank, c.E)
@@ -625,6 +673,9 @@ def check_moe(M, oracle, c, site, pairs=None):
     sub_topk = c.topk.reshape(-1)[sel].reshape(-1, 1)
     ref = oracle.apply_moe(c.x[tok], c.y0[sel], c.A, c.B, c.rank, c.alpha, sub_topk, c.token_slot[tok])
     P.check_close(got[sel], ref, c.name)
+    if report:
+        assert pairs is None
+        P.report(report, got, ref, c.T * c.K, "pairs")
     eff = np.repeat(np.array([s >= 0 and c.rank[s] > 0 for s in c.token_slot]), c.K)
     P.check_untouched(got, c.y0, ~eff, c.name)
     zero = np.zeros_like(c.y0)
@@ -782,13 +833,16 @@ def run_moe_down(M, site, c, y0_bits):
     return P.host_bits(y)
 
 
-def check_moe_down(M, oracle, c, site, tokens=None):
+def check_moe_down(M, oracle, c, site, tokens=None, report=None):
     sel = np.arange(c.T) if tokens is None else np.asarray(tokens)
     pairs = (sel[:, None] * c.K + np.arange(c.K)[None, :]).reshape(-1)
     args = (c.A, c.B, c.rank, c.alpha, c.topk[sel], c.w[sel], c.token_slot[sel])
     ref = oracle.apply_moe_down(c.x[pairs], c.y0[sel], *args)
     got = run_moe_down(M, site, c, c.y0)
     P.check_close(got[sel], ref, c.name)
+    if report:
+        assert tokens is None
+        P.report(report, got, ref, c.T, "tokens")
     eff = np.array([s >= 0 and c.rank[s] > 0 for s in c.token_slot])
     P.check_untouched(got, c.y0, ~eff, c.name)
     zero = np.zeros_like(c.y0)
@@ -813,10 +867,11 @@ def test_moe_down_small(M, oracle, T, K, E, S, r):
     check_moe_down(M, oracle, c, site)
 
 
-def test_c4_moe_down_sampled(M, oracle):
+def test_c4_moe_down_full(M, oracle):
+    """The down projection at the c4 size: all 2048 tokens (16384 pairs) against the oracle."""
     c = W.c4_moe_down()
     site = moe_site(M, c)
-    check_moe_down(M, oracle, c, site, tokens=np.sort(W.rng(79).permutation(c.T)[:160]))
+    check_moe_down(M, oracle, c, site, report=c.name)
 
 
 def test_upload_from_per_expert_tensors_equals_packed_upload(M, oracle):
@@ -844,30 +899,62 @@ def test_upload_from_per_expert_tensors_equals_packed_upload(M, oracle):
     assert frag.meta()[0].tolist() == [3, 5, 8] and frag.meta()[2][0] == 9
 
 
-def test_c4_moe_packed_sampled(M, oracle):
+def test_c4_moe_packed_full(M, oracle):
+    """moe_lora_apply_packed at the c4 size: all 16384 pairs against the oracle, indices bit for bit."""
     c = W.c4_moe_packed("gate")
     site = moe_site(M, c)
-    pairs = np.sort(W.rng(6).permutation(c.T * c.K)[:512])
-    check_moe(M, oracle, c, site, pairs=pairs)
+    check_moe(M, oracle, c, site, report=c.name + " (moe_lora_apply_packed)")
 
 
-def test_c4_gate_up_one_launch_sampled(M, oracle):
+def test_c4_gate_up_one_launch_full(M, oracle):
     """The benchmark's launch configuration of c4: gate and up in one launch over one route plan, at
-    full size, sampled pairs against the oracle."""
+    full size, every pair against the oracle, with the batch's y0 and with y0 = 0."""
     cg, cu = W.c4_moe_packed("gate"), W.c4_moe_packed("up")
     sites = [moe_site(M, cg), moe_site(M, cu)]
     plan = M.Plan(cg.T * cg.K, cg.n_slots * cg.E)
     M.moe_plan_route(plan, torch.from_numpy(cg.topk).cuda(), torch.from_numpy(cg.token_slot).cuda(), cg.n_slots, cg.E)
     x = P.dev_bf16(cg.x)
-    ys = [P.dev_bf16(cg.y0), P.dev_bf16(cu.y0)]
-    M.moe_lora_apply_multi(sites, plan, [x, x], ys)
-    torch.cuda.synchronize()
-    sel = np.sort(W.rng(7).permutation(cg.T * cg.K)[:384])
-    tok = sel // cg.K
-    for c, y in zip((cg, cu), ys):
-        sub_topk = c.topk.reshape(-1)[sel].reshape(-1, 1)
-        ref = oracle.apply_moe(cg.x[tok], c.y0[sel], c.A, c.B, c.rank, c.alpha, sub_topk, c.token_slot[tok])
-        P.check_close(P.host_bits(y)[sel], ref, c.name)
+    for zero in (False, True):
+        y0s = [np.zeros_like(c.y0) if zero else c.y0 for c in (cg, cu)]
+        ys = [P.dev_bf16(y0) for y0 in y0s]
+        M.moe_lora_apply_multi(sites, plan, [x, x], ys)
+        torch.cuda.synchronize()
+        for c, y0, y in zip((cg, cu), y0s, ys):
+            ref = oracle.apply_moe(cg.x, y0, c.A, c.B, c.rank, c.alpha, c.topk, c.token_slot)
+            if zero:
+                P.check_delta(P.host_bits(y), ref, c.name + " delta (one launch)")
+                P.noop_must_fail(c.y0, ref, np.arange(c.T * c.K))
+            else:
+                P.check_close(P.host_bits(y), ref, c.name)
+                P.report(c.name + " (gate|up in one launch)", P.host_bits(y), ref, c.T * c.K, "pairs")
+
+
+def test_c4_mixed_rank_full(M, oracle):
+    """The gate site with slot ranks drawn from {2, 4, 8} in rank-8 tables, as bench.py times it
+    (route plan, then moe_lora_apply_planned, rank-bounded reads by default and switched off): all
+    16384 pairs against the oracle."""
+    c = W.c4_moe_mixed_rank()
+    site = moe_site(M, c)
+    plan = M.Plan(c.T * c.K, c.n_slots * c.E)
+    M.moe_plan_route(plan, torch.from_numpy(c.topk).cuda(), torch.from_numpy(c.token_slot).cuda(), c.n_slots, c.E)
+    x = P.dev_bf16(c.x)
+    ref = oracle.apply_moe(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, c.token_slot)
+    dref = oracle.apply_moe(c.x, np.zeros_like(c.y0), c.A, c.B, c.rank, c.alpha, c.topk, c.token_slot)
+    for force in (0, -1):
+        M.set_tuning("rows_rank_bound", force)
+        try:
+            y, z = P.dev_bf16(c.y0), P.dev_bf16(np.zeros_like(c.y0))
+            M.moe_lora_apply_planned(site, plan, x, y)
+            M.moe_lora_apply_planned(site, plan, x, z)
+            torch.cuda.synchronize()
+        finally:
+            M.set_tuning("rows_rank_bound", 0)
+        P.check_close(P.host_bits(y), ref, c.name)
+        P.check_delta(P.host_bits(z), dref, c.name + " delta")
+        if force == 0:
+            P.report(c.name, P.host_bits(y), ref, c.T * c.K, "pairs")
+    P.noop_must_fail(c.y0, dref, np.arange(c.T * c.K))
+    check_moe(M, oracle, c, site)                      # and through the one-call entry point, indices included
 
 
 # ------------------------------------------------------------------ ABI errors on the device box
