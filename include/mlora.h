@@ -222,6 +222,21 @@ int32_t moe_lora_apply_down(mlora_site *site, const mlora_plan *plan, const void
 int32_t lora_apply_decode(mlora_site *site, const void *x, int64_t ldx, void *y, int64_t ldy,
                           const int32_t *token_slot, int32_t T, void *stream);
 
+/* lora_apply_decode for callers that cannot allocate device memory, and cannot let a library do it:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same result bit for bit; it allocates nothing (no hipMalloc / hipFree, no allocating
+ * library call).  What lora_apply_decode keeps in the site's scratch buffer -- the batch plan, the
+ * control block and the exchange words of launches whose workgroups trade partial sums -- lives in a
+ * device array inside the library: 1,115,136 bytes per GPU the library runs on, held until the process ends
+ * and set up by the first call on that GPU (a few small fill launches on `stream`, waited for once;
+ * make that first call outside any graph capture).
+ * Limits: T <= 1024 rows and a site of at most 1024 slots, else MLORA_E_UNSUPPORTED (nothing is
+ * launched).  Every call on a GPU shares that GPU's array, whatever the site: calls that overlap on
+ * one GPU (different streams) race; calls on one stream, or otherwise ordered, are safe.  The array
+ * keeps the last call's contents; what has to start clean is cleared by the kernels themselves. */
+int32_t lora_apply_decode_noalloc(mlora_site *site, const void *x, int64_t ldx, void *y, int64_t ldy,
+                                  const int32_t *token_slot, int32_t T, void *stream);
+
 /* Segmented prefill: rows [seg_off[k], seg_off[k+1]) all use slot seg_slot[k] (a request's
  * prompt is one contiguous run).  seg_off (int32[S+1]) and seg_slot (int32[S]) are HOST arrays;
  * they are validated here (MLORA_E_SEGMENTS / MLORA_E_SLOT) and copied to the device.  Sites

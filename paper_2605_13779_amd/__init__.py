@@ -7,7 +7,7 @@ raises if the library has not been built.
 """
 from .binding import (  # noqa: F401
     MLoraError, Site, Plan, load_library, set_tuning,
-    lora_slots_upload, lora_slots_evict, lora_apply_decode, lora_apply_segmented,
+    lora_slots_upload, lora_slots_evict, lora_apply_decode, lora_apply_decode_noalloc, lora_apply_segmented,
     moe_lora_apply_packed, lora_plan_decode, lora_apply_decode_planned, moe_plan_route,
     moe_lora_apply_planned, moe_lora_apply_multi, lora_apply_decode_multi, lora_plan_apply_decode_multi, moe_down_workspace_bytes, moe_lora_apply_down,
     pack_experts, lora_slots_upload_experts, ExpertTensors, SiteDesc, Resident, lora_slot_lookup,

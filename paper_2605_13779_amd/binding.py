@@ -60,6 +60,7 @@ SIGNATURES = {
     "mlora_resident_pin": (_i32, [_vp, _i32, _i32]),
     "mlora_resident_stats": (_i32, [_vp, C.POINTER(_i64)]),
     "lora_apply_decode": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _i32, _vp]),
+    "lora_apply_decode_noalloc": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _i32, _vp]),
     "lora_apply_segmented": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _vp, _i32, _i32, _vp]),
     "moe_lora_apply_packed": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _vp, _i32, _i32, _vp, _vp, _vp]),
 }
@@ -252,6 +253,15 @@ def lora_apply_decode(site, x, y, token_slot, stream=None):
     T = x.shape[0]
     assert y.shape[0] == T and token_slot.shape == (T,)
     _check("lora_apply_decode", load_library().lora_apply_decode(
+        site.handle, px, ldx, py, ldy, _dev_ptr(token_slot, torch.int32), T, _stream(stream)))
+
+
+def lora_apply_decode_noalloc(site, x, y, token_slot, stream=None):
+    px, ldx = _rows(x)
+    py, ldy = _rows(y)
+    T = x.shape[0]
+    assert y.shape[0] == T and token_slot.shape == (T,)
+    _check("lora_apply_decode_noalloc", load_library().lora_apply_decode_noalloc(
         site.handle, px, ldx, py, ldy, _dev_ptr(token_slot, torch.int32), T, _stream(stream)))
 
 

@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstring>
 #include <atomic>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -898,36 +899,40 @@ int32_t moe_lora_apply_down(mlora_site *s, const mlora_plan *plan, const void *x
                                  s->d.n_slots, T, plan->top_k, s->d.d_out, st)) ? MLORA_OK : MLORA_E_HIP;
 }
 
-int32_t lora_apply_decode(mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy,
-                          const int32_t *token_slot, int32_t T, void *stream)
+// Where a decode call keeps what lives beyond its inputs and outputs: the batch plan and, for
+// launches whose workgroups trade partial sums, the control block and the exchange words.
+struct DecodeScratch {
+    mlora_plan *plan;
+    uint32_t *ctrl;
+    uint64_t *xch;
+};
+
+static int32_t apply_decode_impl(mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy,
+                                 const int32_t *token_slot, int32_t T, hipStream_t st, const DecodeScratch &sc)
 {
-    if (!s || T < 0) return MLORA_E_INVALID;
-    if (s->d.n_experts > 0) return MLORA_E_UNSUPPORTED;
-    if (T == 0) return MLORA_OK;
-    if (!token_slot) return MLORA_E_INVALID;
-    int32_t rc = check_xy(s, x, ldx, y, ldy);
-    if (rc) return rc;
-    DeviceGuard g(s->d.device);
-    if (!g.good) return MLORA_E_HIP;
-    hipStream_t st = (hipStream_t)stream;
+    auto args = [&](const void *xp, void *yp) {
+        RowsArgs a = rows_args(s, xp, ldx, yp, ldy);
+        a.xch = sc.xch; a.ctrl = sc.ctrl; a.xch_chunks = sc.xch ? kXchChunks : 0;
+        return a;
+    };
     if (s->r_pad <= 2 && !tuning(kPlanGeneral) && !tuning(kPlanSeparate)) {
         // Tiny adapters (the compact rank-1 catalog of Section 4): rows are applied one by one, without
         // a plan -- grouping would save at most two adapter rows per row, a planner launch costs more.
-        RowsArgs a = rows_args(s, x, ldx, y, ldy);
+        RowsArgs a = args(x, y);
         a.row_slot = token_slot; a.row_slots = s->d.n_slots; a.top_k = 1; a.grid_chunks = T;
         return ok(launch_rows(a, st)) ? MLORA_OK : MLORA_E_HIP;
     }
+    mlora_plan *plan = sc.plan;
     // batches beyond the private plan are processed in slices; rows are independent
-    for (int32_t t0 = 0; t0 < T; t0 += s->priv.max_items) {
-        const int32_t n = T - t0 < s->priv.max_items ? T - t0 : s->priv.max_items;
+    for (int32_t t0 = 0; t0 < T; t0 += plan->max_items) {
+        const int32_t n = T - t0 < plan->max_items ? T - t0 : plan->max_items;
         const uint16_t *xs = (const uint16_t *)x + (int64_t)t0 * ldx;
         uint16_t *ys = (uint16_t *)y + (int64_t)t0 * ldy;
         // a small batch on a site whose launch can plan for itself needs no planner launch (same plan,
         // same bits; see lora_plan_apply_decode_multi)
         if (n <= rows_local_plan_rows() && s->d.n_slots <= rows_local_plan_slots() &&
             max_chunks(n, s->d.n_slots) <= rows_local_plan_rows() && !tuning(kPlanGeneral) && !tuning(kPlanSeparate)) {
-            mlora_plan *plan = &s->priv;
-            RowsArgs a = rows_args(s, xs, ldx, ys, ldy);
+            RowsArgs a = args(xs, ys);
             a.chunks = plan->pv.chunks; a.top_k = 1; a.grid_chunks = (int32_t)max_chunks(n, s->d.n_slots);
             if (rows_plans_alone(a)) {
                 plan->items = n; plan->top_k = 1; plan->n_experts = 1; plan->n_slots = s->d.n_slots; plan->moe = false;
@@ -936,12 +941,96 @@ int32_t lora_apply_decode(mlora_site *s, const void *x, int64_t ldx, void *y, in
                 continue;
             }
         }
-        rc = plan_decode_impl(&s->priv, token_slot + t0, n, s->d.n_slots, s->rank, st);
+        int32_t rc = plan_decode_impl(plan, token_slot + t0, n, s->d.n_slots, s->rank, st);
         if (rc) return rc;
-        rc = apply_planned_impl(s, &s->priv, xs, ldx, ys, ldy, st);
-        if (rc) return rc;
+        RowsArgs a = args(xs, ys);
+        a.chunks = plan->pv.chunks; a.top_k = plan->top_k; a.grid_chunks = plan->grid_chunks;
+        if (!ok(launch_rows(a, st))) return MLORA_E_HIP;
     }
     return MLORA_OK;
+}
+
+static int32_t check_decode_call(mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy,
+                                 const int32_t *token_slot, int32_t T)
+{
+    if (!s || T < 0) return MLORA_E_INVALID;
+    if (s->d.n_experts > 0) return MLORA_E_UNSUPPORTED;
+    if (T == 0) return MLORA_OK;
+    if (!token_slot) return MLORA_E_INVALID;
+    return check_xy(s, x, ldx, y, ldy);
+}
+
+int32_t lora_apply_decode(mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy,
+                          const int32_t *token_slot, int32_t T, void *stream)
+{
+    int32_t rc = check_decode_call(s, x, ldx, y, ldy, token_slot, T);
+    if (rc || T == 0) return rc;
+    DeviceGuard g(s->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    return apply_decode_impl(s, x, ldx, y, ldy, token_slot, T, (hipStream_t)stream, DecodeScratch{&s->priv, s->ctrl, s->xch});
+}
+
+// ---- the decode call for callers that cannot allocate ----------------------------------------
+// What lora_apply_decode keeps in the site's caller-allocated scratch buffer (the batch plan, the
+// control block and the exchange words of launches whose workgroups trade partial sums) lives here
+// in a file-scope device array of fixed size, one copy per GPU, held until the process ends.
+constexpr int32_t kNoAllocRows = 1024;             // largest batch (rows) and slot count the array is sized for
+constexpr int32_t kNoAllocSlots = 1024;
+constexpr size_t kNoAllocPlanBytes = 65536;        // >= plan_words(kNoAllocRows, kNoAllocSlots) * 4, checked at set-up
+constexpr size_t kNoAllocBytes = kNoAllocPlanBytes + kCtrlBytes + kXchBytes;      // 1.07 MB
+static __device__ __align__(256) unsigned char scratch[kNoAllocBytes];
+
+constexpr int kNoAllocDevices = 64;
+struct NoAllocState {
+    bool ready = false;
+    mlora_plan plan;                               // view into this device's copy of the array
+    uint32_t *ctrl = nullptr;
+    uint64_t *xch = nullptr;
+};
+static NoAllocState g_noalloc[kNoAllocDevices];
+static std::mutex g_noalloc_mu;
+
+// The device's copy of the array, set up on the first call on that device (which must be current).
+// `scratch` itself is only a host-side handle; the device address comes from hipGetSymbolAddress.
+static int32_t noalloc_state(int device, hipStream_t st, NoAllocState **out)
+{
+    if (device < 0 || device >= kNoAllocDevices) return MLORA_E_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_noalloc_mu);
+    NoAllocState &n = g_noalloc[device];
+    if (!n.ready) {
+        if (plan_words(kNoAllocRows, kNoAllocSlots) * 4 > kNoAllocPlanBytes) return MLORA_E_UNSUPPORTED;
+        void *ptr = nullptr;
+        if (!ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) || !ptr) return MLORA_E_HIP;
+        if ((uintptr_t)ptr & 255) return MLORA_E_HIP;
+        init_plan(&n.plan, kNoAllocRows, kNoAllocSlots, device, ptr);
+        n.ctrl = (uint32_t *)((char *)ptr + kNoAllocPlanBytes);
+        n.xch = (uint64_t *)((char *)n.ctrl + kCtrlBytes);
+        // What must start at zero: the plan's header and counters, the control block, the exchange
+        // words (tag 0 = never written); the first launch tag is 1.  Fill kernels on the caller's
+        // stream, waited for once, so that later calls on any stream find the array set up.
+        hipError_t e = launch_fill_i32(n.plan.pv.hdr, 0, 8 + 3 * ((int64_t)kNoAllocSlots + 1), st);
+        if (ok(e)) e = launch_fill_i32((int32_t *)n.ctrl, 0, (int64_t)((kCtrlBytes + kXchBytes) / 4), st);
+        if (ok(e)) e = launch_fill_i32((int32_t *)n.ctrl, 1, 1, st);
+        if (!ok(e) || !ok(hipStreamSynchronize(st))) return MLORA_E_HIP;
+        n.ready = true;
+    }
+    *out = &n;
+    return MLORA_OK;
+}
+
+int32_t lora_apply_decode_noalloc(mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy,
+                                  const int32_t *token_slot, int32_t T, void *stream)
+{
+    int32_t rc = check_decode_call(s, x, ldx, y, ldy, token_slot, T);
+    if (rc) return rc;
+    if (T > kNoAllocRows || s->d.n_slots > kNoAllocSlots) return MLORA_E_UNSUPPORTED;   // beyond what the array holds
+    if (T == 0) return MLORA_OK;
+    DeviceGuard g(s->d.device);
+    if (!g.good) return MLORA_E_HIP;
+    NoAllocState *n = nullptr;
+    rc = noalloc_state(s->d.device, (hipStream_t)stream, &n);
+    if (rc) return rc;
+    return apply_decode_impl(s, x, ldx, y, ldy, token_slot, T, (hipStream_t)stream, DecodeScratch{&n->plan, n->ctrl, n->xch});
 }
 
 int32_t lora_apply_segmented(mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy,
