@@ -62,7 +62,7 @@ struct RowsArgs {
     int32_t grid_chunks;     // upper bound on the number of chunks
     // exchange area of the site (null on sites that only run fused launches)
     uint64_t *xch;           // [xch_chunks][<= 128 values][kChunk] words
-    uint32_t *ctrl;          // [0] launch tag, [1] error flag, [2] top sign-in, [8..72) group sign-ins
+    uint32_t *ctrl;          // [0] launch tag, [1] error flag, [8..72) sign-ins
     int32_t xch_chunks;
     // filled in by the launcher
     int32_t mode;            // 0 nothing crosses workgroups; 2 parts that trade k-slices
@@ -162,7 +162,8 @@ typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 // error flag raised when a bounded wait gives up.
 constexpr int kSpinLimit = 1 << 18;
 constexpr uint32_t kTagPoison = 0xffffffffu;   // exchange switched off after a bounded wait gave up (see tag_advance)
-constexpr int kPollLimit = 512;   // polls of an exchange word before a reader computes the value itself
+constexpr int kPollLimit = 4096;  // polls of an exchange word before a reader computes the value itself (a partner can start late,
+                                  // e.g. when its part of the chip comes out of an idle state; results do not depend on the outcome)
 
 __device__ __forceinline__ void xch_put(uint64_t *p, float v, uint32_t tag)
 {

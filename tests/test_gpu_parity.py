@@ -250,27 +250,35 @@ def test_decode_parts_when_partners_never_answer(M, oracle):
     sites = [dense_site(M, c) for c in cases]
     plan = M.Plan(77, 6)
     M.lora_plan_decode(plan, torch.from_numpy(slots).cuda(), 6)
-    M.set_tuning("rows_poll_limit", -1)
-    try:
+    grp = [0, 2]                                       # same rank: one launch
+
+    def run_all():
+        out = []
         for c, site in zip(cases, sites):
             y = P.dev_bf16(c.y0)
             M.lora_apply_decode_planned(site, plan, P.dev_bf16(c.x), y)
-            torch.cuda.synchronize()
-            ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
-            P.check_close(P.host_bits(y), ref, c.name)
-            P.check_untouched(P.host_bits(y), c.y0, c.token_slot < 0, c.name)
-            site.check()
-        grp = [0, 2]                                   # same rank: one launch
+            out.append(y)
         xs = [P.dev_bf16(cases[k].x) for k in grp]
         ys = [P.dev_bf16(cases[k].y0) for k in grp]
         M.lora_apply_decode_multi([sites[k] for k in grp], plan, xs, ys)
         torch.cuda.synchronize()
-        for k, y in zip(grp, ys):
-            c = cases[k]
-            ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
-            P.check_close(P.host_bits(y), ref, c.name + " (grouped)")
+        return [P.host_bits(y) for y in out + ys]
+    traded = run_all()
+    M.set_tuning("rows_poll_limit", -1)
+    try:
+        alone = run_all()
     finally:
         M.set_tuning("rows_poll_limit", 0)
+    for k, (c, a, b) in enumerate(zip(cases + [cases[k] for k in grp], traded, alone)):
+        ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+        P.check_close(b, ref, c.name + (" (grouped)" if k >= len(cases) else ""))
+        P.check_untouched(b, c.y0, c.token_slot < 0, c.name)
+        # (an item on its own adds the k-slices of d_in in one sweep instead of slice by slice: the two
+        # results may differ in the last bit of an output, never by more)
+        wa, wb = P.widen(a), P.widen(b)
+        assert np.all(np.abs(wa - wb) <= 2.0 ** -7 * np.maximum(np.abs(wa), np.abs(wb))), c.name
+    for site in sites:
+        site.check()
 
 
 def test_decode_after_an_exchange_wait_gave_up(M, oracle):
@@ -375,8 +383,19 @@ def test_decode_step_that_plans_inside_its_first_launch(M, oracle, T, S):
         M.lora_plan_apply_decode_multi(ss, pb, ts, S, xs, yb, ready_from=ss[0])
         torch.cuda.synchronize()
         for c, a, b in zip(cs, ya, yb):
-            assert torch.equal(a, b), c.name
             ref = oracle.apply_decode(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.token_slot)
+            if not torch.equal(a, b):                  # say where before failing
+                ga, gb = P.host_bits(a), P.host_bits(b)
+                d = ga != gb
+                rows, cols = np.nonzero(d.any(axis=1))[0], np.nonzero(d.any(axis=0))[0]
+                tol = 2e-2 + 2e-2 * np.abs(ref)
+                print(f"{c.name} order {order}: {int(d.sum())} elements differ, rows {rows.tolist()} (slots {slots[rows].tolist()}), "
+                      f"columns {cols.min()}..{cols.max()} ({len(cols)}), two calls outside tolerance {int((np.abs(P.widen(ga) - ref) > tol).sum())}, "
+                      f"one call {int((np.abs(P.widen(gb) - ref) > tol).sum())}, max |a - b| {np.abs(P.widen(ga) - P.widen(gb)).max():.4g}", flush=True)
+                for k_, s_ in zip(order, ss):
+                    ctrl = s_.bufs[3][s_.bytes[3] - (1 << 20) - 1024:][:1024].view(torch.int32)
+                    print(f"   site {k_}: tag {int(ctrl[0])} flag {int(ctrl[1])}", flush=True)
+            assert torch.equal(a, b), c.name
             P.check_close(P.host_bits(b), ref, c.name)
         (ha, sa, ra), (hb, sb, rb) = _plan_words(pa, max(T, 1), S), _plan_words(pb, max(T, 1), S)
         assert np.array_equal(ha, hb), (ha, hb)
