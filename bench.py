@@ -247,8 +247,8 @@ def bench_c4(M, W, steps, warmup, n_sets=2, fused=True):
 
 def moe_down_bytes(c):
     """Algorithmic bytes: every pair's input row, y once in and once out, each touched (slot, expert)
-    adapter once, weights and indices.  The fp32 workspace the two-launch form writes and reads
-    (T*K*d_out*4 bytes each way) is not algorithmic."""
+    adapter once, weights and indices.  The per-pair rank-r vectors that the first launch hands to
+    the second (T*K*r words each way) are not algorithmic."""
     keys = set((int(c.token_slot[t]) * c.E + int(e)) for t in range(c.T) for e in c.topk[t])
     P = c.T * c.K
     return P * c.d_in * 2 + 2 * c.T * c.d_out * 2 + len(keys) * c.r_max * (c.d_in + c.d_out) * 2 + 2 * P * 4 + c.T * 4

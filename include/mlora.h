@@ -198,11 +198,22 @@ int32_t moe_lora_apply_multi(mlora_site *const *sites, int32_t n_sites, const ml
  *
  *     y[t, :] += sum_{k = 0..K-1} pair_w[t, k] * (alpha_s / r_s) * B_{s,e(t,k)} * (A_{s,e(t,k)} * x[p, :])
  *
- * with k upwards in fp32 and one rounding to bf16: no atomics, the result is deterministic.
+ * summed in fp32 and rounded to bf16 once: every output row has one writer, no atomics, and the
+ * summation order is fixed (by expert id), so the result is deterministic.
  *   plan: from moe_plan_route on the same topk_ids / token_slot;  x: [T*K, d_in];  y: [T, d_out];
- *   pair_w: DEVICE fp32 [T, K];  token_slot: DEVICE int32[T], the array given to moe_plan_route;
- *   workspace: DEVICE, moe_down_workspace_bytes(T, K, d_out) bytes, 16-byte aligned, overwritten.
- * Two launches: weighted fp32 deltas per pair into the workspace, then the per-token sum.
+ *   pair_w: DEVICE fp32 [T, K];  token_slot: DEVICE int32[T], the array given to moe_plan_route
+ *   (the plan already holds the grouping of the tokens by slot; the argument is checked, not read);
+ *   workspace: DEVICE, moe_down_workspace_bytes(T, K, d_out) bytes (T * K * MLORA_MAX_RANK 32-bit
+ *   words), 16-byte aligned, overwritten.
+ * Two launches.  The first leaves in the workspace, for every pair of the plan, the rank-r vector
+ * h[p] = pair_w[p] * (alpha / r) * A x[p] as bf16 head and tail (one wave per (slot, expert) group,
+ * so that an adapter's A rows are read once).  The second is, per slot, the dense contraction
+ * Y_s += H_s * Bcat_s on the matrix cores: H_s holds h[(t, k)] in the r columns of expert e(t, k)
+ * of row t, Bcat_s is the slot's per-expert B tensors stacked along the contraction axis, as the
+ * packed tables store them.  Pairs that the plan left out (expert ids outside [0, n_experts), slots
+ * not ready when the plan was built) add nothing, whatever the workspace holds.
+ * Limits: K <= 16, and 32 * (n_experts + 4 * K * max(r_pad, 8)) bytes of tables must fit the LDS
+ * of a compute unit (n_experts = 1024 at rank 8 and K = 8 does; MLORA_E_UNSUPPORTED otherwise).
  * Errors: as moe_lora_apply_planned; MLORA_E_INVALID on null pointers. */
 int32_t moe_down_workspace_bytes(int32_t T, int32_t K, int32_t d_out, size_t *bytes);
 int32_t moe_lora_apply_down(mlora_site *site, const mlora_plan *plan, const void *x, int64_t ldx,
@@ -227,7 +238,7 @@ int32_t lora_apply_decode(mlora_site *site, const void *x, int64_t ldx, void *y,
  * arguments, same result bit for bit; it allocates nothing (no hipMalloc / hipFree, no allocating
  * library call).  What lora_apply_decode keeps in the site's scratch buffer -- the batch plan, the
  * control block and the exchange words of launches whose workgroups trade partial sums -- lives in a
- * device array inside the library: 1,115,136 bytes per GPU the library runs on, held until the process ends
+ * device array inside the library: 1,147,904 bytes per GPU the library runs on, held until the process ends
  * and set up by the first call on that GPU (a few small fill launches on `stream`, waited for once;
  * make that first call outside any graph capture).
  * Limits: T <= 1024 rows and a site of at most 1024 slots, else MLORA_E_UNSUPPORTED (nothing is

@@ -6,7 +6,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmlora.so")
-SOURCES = ["api.hip", "plan.hip", "rows.hip", "seg_mfma.hip", "resident.hip"]
+SOURCES = ["api.hip", "plan.hip", "rows.hip", "seg_mfma.hip", "moe_down.hip", "resident.hip"]
 # packed-fp32 VALU forms are switched off for all device code: hipcc forms them by itself from plain
 # float code and some of those forms have given wrong results on this hardware
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",

@@ -61,7 +61,7 @@ std::atomic<int32_t> g_knob[kKnobCount];
 const char *const kKnobName[kKnobCount] = {
     "rows_poll_limit", "rows_rank_bound", "rows_items_target", "rows_mode", "rows_waves", "rows_prefetch", "plan_general",
     "plan_separate", "plan_pipeline", "seg_expand_groups", "seg_table_copy", "seg_shrink_wgs", "seg_no_mfma", "seg_fused",
-    "upload_piece_kb", "down_tile_rows"};
+    "upload_piece_kb", "down_rows_shrink"};
 
 // Host-side record of a slot's rank (the kernels read the device table; this only tells the launch
 // code whether any slot is padded, i.e. whether rank-bounded reads of A can save traffic).
@@ -462,6 +462,7 @@ int32_t mlora_site_create(const mlora_site_desc *d, void *a_tab, void *b_tab, vo
     if (!g.good) { delete s; return MLORA_E_HIP; }
     meta_clear_kernel<<<dim3((d->n_slots + 255) / 256), dim3(256), 0, 0>>>(s->rank, s->scale, s->catalog, d->n_slots);
     hipError_t e = launch_fill_i32(s->priv.pv.hdr, 0, 8 + 3 * (NK + 1), 0);
+    if (ok(e)) e = launch_fill_i32(s->priv.pv.tok_hdr, 0, 8 + 2 * (NK + 1), 0);
     if (ok(e) && s->ctrl) {
         e = launch_fill_i32((int32_t *)s->ctrl, 0, (int64_t)((kCtrlBytes + (s->r_pad == 64 ? kSegXchBytes : kXchBytes)) / 4), 0);   // tag 0 = never written
         if (ok(e)) e = launch_fill_i32((int32_t *)s->ctrl, 1, 1, 0);                               // first launch tag
@@ -682,6 +683,7 @@ int32_t mlora_plan_create(int32_t max_items, int32_t n_keys, int32_t device, voi
     DeviceGuard g(device);
     if (!g.good) { delete p; return MLORA_E_HIP; }
     hipError_t e = launch_fill_i32(p->pv.hdr, 0, 8 + 3 * ((int64_t)n_keys + 1), 0);
+    if (ok(e)) e = launch_fill_i32(p->pv.tok_hdr, 0, 8 + 2 * ((int64_t)n_keys + 1), 0);
     if (!ok(e) || !ok(hipStreamSynchronize(0))) { delete p; return MLORA_E_HIP; }
     *out = p;
     return MLORA_OK;
@@ -870,7 +872,8 @@ int32_t moe_lora_apply_multi(mlora_site *const *sites, int32_t n_sites, const ml
 int32_t moe_down_workspace_bytes(int32_t T, int32_t K, int32_t d_out, size_t *bytes)
 {
     if (!bytes || T < 0 || K <= 0 || d_out <= 0 || (d_out & 7)) return MLORA_E_INVALID;
-    *bytes = align256((size_t)T * K * d_out * sizeof(float));
+    // one 32-bit word per pair and (padded) rank value: the first launch's h, whatever the site's rank
+    *bytes = align256((size_t)T * K * MLORA_MAX_RANK * sizeof(uint32_t));
     return MLORA_OK;
 }
 
@@ -883,20 +886,35 @@ int32_t moe_lora_apply_down(mlora_site *s, const mlora_plan *plan, const void *x
     if (plan->items == 0) return MLORA_OK;
     if (plan->n_experts != s->d.n_experts || plan->n_slots > s->d.n_slots) return MLORA_E_SHAPE;
     if (!pair_w || !token_slot || !workspace || !aligned16(workspace)) return MLORA_E_INVALID;
+    const int tile_rows = moe_down_tile_rows(s->r_pad, plan->top_k, s->E);
+    if (plan->top_k > moe_down_max_k() || tile_rows <= 0 || (int64_t)s->E * s->d.d_out * s->r_pad * 2 >= ((int64_t)1 << 32)) return MLORA_E_UNSUPPORTED;
     int32_t rc = check_xy(s, x, ldx, y, ldy);
     if (rc) return rc;
     DeviceGuard g(s->d.device);
     if (!g.good) return MLORA_E_HIP;
     hipStream_t st = (hipStream_t)stream;
-    RowsArgs a = rows_args(s, x, ldx, y, ldy);
-    a.chunks = plan->pv.chunks;
-    a.top_k = 1;                                   // one input row per pair
-    a.grid_chunks = plan->grid_chunks;
-    a.out_f32 = (float *)workspace; a.ldo = s->d.d_out; a.row_w = pair_w;
-    if (!ok(launch_rows(a, st))) return MLORA_E_HIP;
     const int32_t T = plan->items / plan->top_k;
-    return ok(launch_moe_combine((uint16_t *)y, ldy, (const float *)workspace, s->d.d_out, token_slot, s->rank,
-                                 s->d.n_slots, T, plan->top_k, s->d.d_out, st)) ? MLORA_OK : MLORA_E_HIP;
+    MoeDownArgs d{};
+    d.y = (uint16_t *)y; d.ldy = ldy; d.b_tab = s->b_tab; d.rank = s->rank; d.h = (uint32_t *)workspace;
+    d.key_of = plan->pv.key_of; d.sorted = plan->pv.sorted; d.group_off = plan->pv.group_off;
+    d.tok_sorted = plan->pv.tok_sorted; d.tok_off = plan->pv.tok_off;
+    d.T = T; d.K = plan->top_k; d.E = s->E; d.n_slots = plan->n_slots; d.d_out = s->d.d_out; d.r_pad = s->r_pad;
+    d.x = (const uint16_t *)x; d.ldx = ldx; d.a_tab = s->a_tab; d.scale = s->scale; d.pair_w = pair_w; d.d_in = s->d.d_in;
+    // first launch: per (slot, expert) group, h = w * (alpha / r) * A x for the group's pairs
+    if (moe_down_shrinks_by_group(s->r_pad) && !tuning(kDownRowsShrink)) {
+        if (!ok(launch_moe_down_shrink(d, st))) return MLORA_E_HIP;
+    } else {
+        RowsArgs a = rows_args(s, x, ldx, y, ldy);
+        a.chunks = plan->pv.chunks;
+        a.top_k = 1;                                   // one input row per pair
+        a.grid_chunks = plan->grid_chunks;
+        a.h_out = (uint32_t *)workspace; a.row_w = pair_w;
+        if (!ok(launch_rows(a, st))) return MLORA_E_HIP;
+    }
+    // second launch: per slot and tile of its tokens, y += H x Bcat on the matrix cores
+    d.n_mtiles = T / tile_rows + plan->n_slots;
+    d.n_ntiles = (s->d.d_out + moe_down_tile_cols() - 1) / moe_down_tile_cols();
+    return ok(launch_moe_down(d, st)) ? MLORA_OK : MLORA_E_HIP;
 }
 
 // Where a decode call keeps what lives beyond its inputs and outputs: the batch plan and, for
@@ -976,8 +994,8 @@ int32_t lora_apply_decode(mlora_site *s, const void *x, int64_t ldx, void *y, in
 // in a file-scope device array of fixed size, one copy per GPU, held until the process ends.
 constexpr int32_t kNoAllocRows = 1024;             // largest batch (rows) and slot count the array is sized for
 constexpr int32_t kNoAllocSlots = 1024;
-constexpr size_t kNoAllocPlanBytes = 65536;        // >= plan_words(kNoAllocRows, kNoAllocSlots) * 4, checked at set-up
-constexpr size_t kNoAllocBytes = kNoAllocPlanBytes + kCtrlBytes + kXchBytes;      // 1.07 MB
+constexpr size_t kNoAllocPlanBytes = 98304;        // >= plan_words(kNoAllocRows, kNoAllocSlots) * 4, checked at set-up
+constexpr size_t kNoAllocBytes = kNoAllocPlanBytes + kCtrlBytes + kXchBytes;      // 1.1 MB
 static __device__ __align__(256) unsigned char scratch[kNoAllocBytes];
 
 constexpr int kNoAllocDevices = 64;
@@ -1009,6 +1027,7 @@ static int32_t noalloc_state(int device, hipStream_t st, NoAllocState **out)
         // words (tag 0 = never written); the first launch tag is 1.  Fill kernels on the caller's
         // stream, waited for once, so that later calls on any stream find the array set up.
         hipError_t e = launch_fill_i32(n.plan.pv.hdr, 0, 8 + 3 * ((int64_t)kNoAllocSlots + 1), st);
+        if (ok(e)) e = launch_fill_i32(n.plan.pv.tok_hdr, 0, 8 + 2 * ((int64_t)kNoAllocSlots + 1), st);
         if (ok(e)) e = launch_fill_i32((int32_t *)n.ctrl, 0, (int64_t)((kCtrlBytes + kXchBytes) / 4), st);
         if (ok(e)) e = launch_fill_i32((int32_t *)n.ctrl, 1, 1, st);
         if (!ok(e) || !ok(hipStreamSynchronize(st))) return MLORA_E_HIP;

@@ -30,7 +30,26 @@ struct PlanView {
     int32_t *tmp;         // [max_items]
     int32_t *sorted;      // [max_items]
     int32_t *chunks;      // [kRec * max_chunks]
+    // Route plans also group the batch's TOKENS by slot (the MoE down projection sums a token's pairs
+    // into one output row and works per slot): tok_hdr[1] = usable tokens, tok_off = exclusive prefix
+    // of the slots' token counts, tok_sorted = tokens grouped by slot, ascending inside a slot; the
+    // rest is the planner's working space for that grouping.
+    int32_t *tok_hdr;     // [8]
+    int32_t *tok_count;   // [n_keys + 1]  zero between calls
+    int32_t *tok_off;     // [n_keys + 1]
+    int32_t *tok_key_of;  // [max_items]
+    int32_t *tok_ticket;  // [max_items]
+    int32_t *tok_tmp;     // [max_items]
+    int32_t *tok_sorted;  // [max_items]
 };
+// The view the planner kernels take for the token-level grouping (no chunk records).
+__host__ __device__ inline PlanView plan_token_view(const PlanView &v)
+{
+    PlanView t{};
+    t.hdr = v.tok_hdr; t.count = v.tok_count; t.group_off = v.tok_off; t.chunk_base = nullptr;
+    t.key_of = v.tok_key_of; t.ticket = v.tok_ticket; t.tmp = v.tok_tmp; t.sorted = v.tok_sorted; t.chunks = nullptr;
+    return t;
+}
 
 size_t plan_words(int64_t max_items, int64_t n_keys);
 PlanView plan_view(void *base, int64_t max_items, int64_t n_keys);
@@ -74,9 +93,10 @@ struct RowsArgs {
     // ungrouped launch (ranks 1 and 2 only): item i is row i with slot row_slot[i]; `chunks` is not read
     const int32_t *row_slot;
     int32_t row_slots;       // slots the site holds (indices outside [0, row_slots) leave the row untouched)
-    // MoE down projection: instead of adding into y, row p writes row_w[p] * delta as fp32 into
-    // out_f32[p, :] (no read); a second launch adds a token's rows in order
-    float *out_f32; int64_t ldo;
+    // MoE down projection, first launch: no expand; row p's scaled h times row_w[p] goes to
+    // h_out[p][r_pad], one word per value (bf16 head | bf16 tail << 16); the second launch
+    // (moe_down.hip) multiplies it with the B tables on the matrix cores, token by token
+    uint32_t *h_out;
     const float *row_w;
 #ifdef MLORA_PROF
     uint64_t *prof;          // per-workgroup phase timestamps (builds with -DMLORA_PROF only)
@@ -91,8 +111,34 @@ int rows_local_plan_slots();
 hipError_t launch_rows_multi_plan(const RowsArgs *sites, int n, const PlanView &pv, const int32_t *token_slot, int T,
                                   int n_slots, const int32_t *ready_rank, hipStream_t st);
 hipError_t launch_rows_multi(const RowsArgs *sites, int n, hipStream_t st);
-hipError_t launch_moe_combine(uint16_t *y, int64_t ldy, const float *parts, int64_t ldo, const int32_t *token_slot,
-                              const int32_t *rank, int32_t n_slots, int32_t T, int32_t K, int32_t d_out, hipStream_t st);
+
+// moe_down.hip: second launch of the MoE down projection (expand + routing-weight combine on the matrix cores)
+struct MoeDownArgs {
+    uint16_t *y; int64_t ldy;
+    const uint16_t *b_tab;       // [n_slots][E][d_out][r_pad]
+    const int32_t *rank;         // [n_slots]
+    uint32_t *h;                 // [T*K][r_pad]: written by the first launch, read by the second
+    const int32_t *key_of;       // [T*K] the plan's key of each pair (slot * E + expert, -1: not in the plan)
+    const int32_t *sorted;       // the plan's pairs grouped by (slot, expert)
+    const int32_t *group_off;    // [n_slots*E + 1]
+    const int32_t *tok_sorted;   // the plan's tokens grouped by slot
+    const int32_t *tok_off;      // [n_slots + 1]
+    int32_t T, K, E, n_slots, d_out, r_pad;
+    int32_t n_mtiles;            // upper bound on the number of token tiles: T / tile + n_slots
+    int32_t n_ntiles;            // output tiles per token tile
+    // first launch (one wave per group) only:
+    const uint16_t *x; int64_t ldx;   // one input row per pair
+    const uint16_t *a_tab;            // [n_slots][E][r_pad][d_in]
+    const float *scale;               // [n_slots] alpha / r
+    const float *pair_w;              // [T*K] routing weights
+    int32_t d_in;
+};
+bool moe_down_shrinks_by_group(int r_pad);
+hipError_t launch_moe_down_shrink(const MoeDownArgs &a, hipStream_t st);
+hipError_t launch_moe_down(const MoeDownArgs &a, hipStream_t st);
+int moe_down_tile_rows(int r_pad, int K, int E);   // 0: this shape does not fit
+int moe_down_tile_cols();
+int moe_down_max_k();
 
 // seg_mfma.hip: rank-64 segmented apply on the matrix cores (a shrink launch, then an expand launch)
 constexpr int kSegInline = 832;   // words of tables inside the kernel arguments (the whole argument block stays below 4 KB)
@@ -133,7 +179,7 @@ int seg_expand_capacity();
 // tests set them; the launch code reads each knob it needs once per call.
 enum Knob {
     kRowsPollLimit, kRowsRankBound, kRowsItemsTarget, kRowsMode, kRowsWaves, kRowsPrefetch, kPlanGeneral, kPlanSeparate,
-    kPlanPipeline, kSegExpandGroups, kSegTableCopy, kSegShrinkWgs, kSegNoMfma, kSegFused, kUploadPieceKb, kDownTileRows,
+    kPlanPipeline, kSegExpandGroups, kSegTableCopy, kSegShrinkWgs, kSegNoMfma, kSegFused, kUploadPieceKb, kDownRowsShrink,
     kKnobCount
 };
 int tuning(Knob k);             // api.hip
@@ -145,6 +191,9 @@ uint64_t *debug_prof();         // api.hip (builds with -DMLORA_PROF only)
 
 #ifdef __HIPCC__
 namespace mlora {
+
+// a compile-time integer as a function argument (static loops over register arrays)
+template <int I> struct IntC { static constexpr int value = I; };
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;

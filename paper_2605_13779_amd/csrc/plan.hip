@@ -9,7 +9,8 @@ namespace mlora {
 
 size_t plan_words(int64_t M, int64_t NK)
 {
-    return 8 + 3 * (NK + 1) + 4 * M + kRec * max_chunks(M, NK) + 64;
+    return 8 + 3 * (NK + 1) + 4 * M + kRec * max_chunks(M, NK) + 64      // the grouping of the items and its chunk records
+         + 8 + 2 * (NK + 1) + 4 * M;                                       // the grouping of the tokens (route plans)
 }
 
 PlanView plan_view(void *base, int64_t M, int64_t NK)
@@ -24,7 +25,14 @@ PlanView plan_view(void *base, int64_t M, int64_t NK)
     v.ticket = p;         p += M;
     v.tmp = p;            p += M;
     v.sorted = p;         p += M;
-    v.chunks = p;
+    v.chunks = p;         p += kRec * max_chunks(M, NK) + 64;
+    v.tok_hdr = p;        p += 8;
+    v.tok_count = p;      p += NK + 1;
+    v.tok_off = p;        p += NK + 1;
+    v.tok_key_of = p;     p += M;
+    v.tok_ticket = p;     p += M;
+    v.tok_tmp = p;        p += M;
+    v.tok_sorted = p;
     return v;
 }
 
@@ -146,7 +154,7 @@ void plan_scan_kernel(PlanView pv, int NK, int32_t *__restrict__ out_group_off)
         int c = pv.count[k];
         pv.group_off[k] = run_i;
         if (out_group_off) out_group_off[k] = run_i;
-        pv.chunk_base[k] = run_c;
+        if (pv.chunk_base) pv.chunk_base[k] = run_c;
         pv.count[k] = 0;                           // leave the histogram clean for the next call
         run_i += c;
         run_c += (c + kChunk - 1) / kChunk;
@@ -154,7 +162,7 @@ void plan_scan_kernel(PlanView pv, int NK, int32_t *__restrict__ out_group_off)
     if (tid == 1023) {
         pv.group_off[NK] = inc_i;
         if (out_group_off) out_group_off[NK] = inc_i;
-        pv.chunk_base[NK] = inc_c;
+        if (pv.chunk_base) pv.chunk_base[NK] = inc_c;
         pv.hdr[0] = inc_c;
         pv.hdr[1] = inc_i;
     }
@@ -175,7 +183,8 @@ void plan_fix_kernel(PlanView pv, int P, int32_t *__restrict__ out_sorted, int r
     int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= P) return;
     const int n_rows = pv.hdr[1];
-    if (j >= pv.hdr[0] && j < rec_bound) pv.chunks[(int64_t)j * kRec + 1] = 0;   // empty record past the live chunks
+    const bool records = pv.chunks != nullptr;            // (the token-level grouping of a route plan has none)
+    if (records && j >= pv.hdr[0] && j < rec_bound) pv.chunks[(int64_t)j * kRec + 1] = 0;   // empty record past the live chunks
     if (j >= n_rows) {
         pv.sorted[j] = -1;
         if (out_sorted) out_sorted[j] = -1;
@@ -188,6 +197,7 @@ void plan_fix_kernel(PlanView pv, int P, int32_t *__restrict__ out_sorted, int r
     for (int m = 0; m < n; ++m) r += (pv.tmp[off + m] < p);
     pv.sorted[off + r] = p;
     if (out_sorted) out_sorted[off + r] = p;
+    if (!records) return;
     int32_t *rec = pv.chunks + (int64_t)(pv.chunk_base[key] + r / kChunk) * kRec;
     rec[4 + (r % kChunk)] = p;
     if (r % kChunk == 0) { rec[0] = key; rec[1] = min(kChunk, n - r); rec[2] = off + r; rec[3] = 0; }
@@ -220,10 +230,10 @@ __device__ __forceinline__ int route_key(const int32_t *__restrict__ topk, const
     return -1;
 }
 
-__global__ __launch_bounds__(kOneThreads)
-void plan_route_one_kernel(PlanView pv, const int32_t *__restrict__ topk, const int32_t *__restrict__ token_slot,
-                           int P, uint32_t k_magic, int E, int n_slots, const int32_t *__restrict__ ready_rank,
-                           int32_t *__restrict__ out_sorted, int32_t *__restrict__ out_group_off, int rec_bound)
+__device__ __forceinline__
+void plan_route_one_body(const PlanView &pv, const int32_t *__restrict__ topk, const int32_t *__restrict__ token_slot,
+                         int P, uint32_t k_magic, int E, int n_slots, const int32_t *__restrict__ ready_rank,
+                         int32_t *__restrict__ out_sorted, int32_t *__restrict__ out_group_off, int rec_bound, const int block)
 {
     __shared__ int32_t goff[kOneKeys + 1];       // histogram of all pairs, then exclusive group starts
     __shared__ int32_t pre[kOneKeys];            // histogram of the pairs in front of this range
@@ -233,7 +243,8 @@ void plan_route_one_kernel(PlanView pv, const int32_t *__restrict__ topk, const 
     __shared__ __attribute__((aligned(16))) int32_t wave_tot[16];
     static_assert(kOneThreads == 4 * kOneRange, "four threads per pair in the in-range rank");
     const int tid = threadIdx.x, NK = n_slots * E;
-    const int p0 = (int)blockIdx.x * kOneRange;
+    const int p0 = block * kOneRange;
+    const bool records = pv.chunks != nullptr;   // (the token-level grouping of a route plan has none)
     for (int k = tid; k < NK; k += kOneThreads) { goff[k] = 0; pre[k] = 0; }
     if (tid < kOneRange) lkey[tid] = -1;         // positions past the batch
     __syncthreads();
@@ -297,33 +308,53 @@ void plan_route_one_kernel(PlanView pv, const int32_t *__restrict__ topk, const 
     if (tid == kOneThreads - 1) { goff[NK] = inc_i; cbase[NK] = inc_c; }
     __syncthreads();
     const int n_rows = goff[NK], n_chunks = cbase[NK];
-    if (blockIdx.x == 0) {
+    if (block == 0) {
         for (int k = tid; k <= NK; k += kOneThreads) {
             pv.group_off[k] = goff[k];
             if (out_group_off) out_group_off[k] = goff[k];
-            pv.chunk_base[k] = cbase[k];
+            if (records) pv.chunk_base[k] = cbase[k];
         }
         if (tid == 0) { pv.hdr[0] = n_chunks; pv.hdr[1] = n_rows; }
     }
     if (tid < kOneRange) {
         const int j = p0 + tid;                  // this range also owns positions / records [p0, p0 + kOneRange)
         if (j < P) {
-            if (j >= n_chunks && j < rec_bound) pv.chunks[(int64_t)j * kRec + 1] = 0;   // empty record past the live chunks
+            if (records && j >= n_chunks && j < rec_bound) pv.chunks[(int64_t)j * kRec + 1] = 0;   // empty record past the live chunks
             if (j >= n_rows) {
                 pv.sorted[j] = -1;
                 if (out_sorted) out_sorted[j] = -1;
             }
             const int key = lkey[tid];
+            pv.key_of[j] = key;                      // (the key as this plan saw it: the MoE down projection asks per pair)
             if (key >= 0) {
                 const int r = pre[key] + lrank[tid];
                 const int off = goff[key], n = goff[key + 1] - off;
                 pv.sorted[off + r] = j;
                 if (out_sorted) out_sorted[off + r] = j;
-                int32_t *rec = pv.chunks + (int64_t)(cbase[key] + r / kChunk) * kRec;
-                rec[4 + (r % kChunk)] = j;
-                if (r % kChunk == 0) { rec[0] = key; rec[1] = min(kChunk, n - r); rec[2] = off + r; rec[3] = 0; }
+                if (records) {
+                    int32_t *rec = pv.chunks + (int64_t)(cbase[key] + r / kChunk) * kRec;
+                    rec[4 + (r % kChunk)] = j;
+                    if (r % kChunk == 0) { rec[0] = key; rec[1] = min(kChunk, n - r); rec[2] = off + r; rec[3] = 0; }
+                }
             }
         }
+    }
+}
+
+// Workgroups [0, pair_blocks) group the routed pairs by (slot, expert); the workgroups behind them
+// (route plans only) group the tokens by slot with the same code: key = slot, one item per token.
+__global__ __launch_bounds__(kOneThreads)
+void plan_route_one_kernel(PlanView pv, const int32_t *__restrict__ topk, const int32_t *__restrict__ token_slot,
+                           int P, uint32_t k_magic, int E, int n_slots, const int32_t *__restrict__ ready_rank,
+                           int32_t *__restrict__ out_sorted, int32_t *__restrict__ out_group_off, int rec_bound,
+                           int pair_blocks, int T)
+{
+    const int b = (int)blockIdx.x;
+    if (b < pair_blocks) {
+        plan_route_one_body(pv, topk, token_slot, P, k_magic, E, n_slots, ready_rank, out_sorted, out_group_off, rec_bound, b);
+    } else {
+        const PlanView tv = plan_token_view(pv);
+        plan_route_one_body(tv, nullptr, token_slot, T, 0u, 1, n_slots, ready_rank, nullptr, nullptr, 0, b - pair_blocks);
     }
 }
 
@@ -337,10 +368,12 @@ hipError_t launch_plan_general(const PlanView &pv, const int32_t *topk, const in
                                int32_t *out_sorted, int32_t *out_group_off, hipStream_t st)
 {
     const int P = T * K, NK = n_slots * E;
+    const bool route = topk != nullptr;            // a route plan also groups the tokens by slot
     if (plan_route_in_one_launch(P, NK)) {
-        plan_route_one_kernel<<<dim3((unsigned)((P + kOneRange - 1) / kOneRange)), dim3(kOneThreads), 0, st>>>(
+        const int pair_blocks = (P + kOneRange - 1) / kOneRange, tok_blocks = route ? (T + kOneRange - 1) / kOneRange : 0;
+        plan_route_one_kernel<<<dim3((unsigned)(pair_blocks + tok_blocks)), dim3(kOneThreads), 0, st>>>(
             pv, topk, token_slot, P, K > 1 ? (uint32_t)((0x100000000ull + (uint64_t)K - 1) / (uint64_t)K) : 0u, E, n_slots,
-            ready_rank, out_sorted, out_group_off, (int)max_chunks(P, NK));
+            ready_rank, out_sorted, out_group_off, (int)max_chunks(P, NK), pair_blocks, T);
         return hipGetLastError();
     }
     const unsigned nb = (unsigned)((P + 255) / 256);
@@ -348,6 +381,14 @@ hipError_t launch_plan_general(const PlanView &pv, const int32_t *topk, const in
     plan_scan_kernel<<<dim3(1), dim3(1024), 0, st>>>(pv, NK, out_group_off);
     plan_scatter_kernel<<<dim3(nb), dim3(256), 0, st>>>(pv, P);
     plan_fix_kernel<<<dim3(nb), dim3(256), 0, st>>>(pv, P, out_sorted, (int)max_chunks(P, NK));
+    if (route) {
+        const PlanView tv = plan_token_view(pv);
+        const unsigned tb = (unsigned)((T + 255) / 256);
+        plan_hist_kernel<<<dim3(tb), dim3(256), 0, st>>>(tv, nullptr, token_slot, T, 1, 1, n_slots, ready_rank);
+        plan_scan_kernel<<<dim3(1), dim3(1024), 0, st>>>(tv, n_slots, nullptr);
+        plan_scatter_kernel<<<dim3(tb), dim3(256), 0, st>>>(tv, T);
+        plan_fix_kernel<<<dim3(tb), dim3(256), 0, st>>>(tv, T, nullptr, 0);
+    }
     return hipGetLastError();
 }
 

@@ -21,6 +21,7 @@
 //                        are needed; a part whose partners have not published after a bounded
 //                        number of polls takes its item again on its own, with the whole shrink.
 #include "plan_device.h"
+#include "wave_ops.h"
 
 namespace mlora {
 
@@ -51,60 +52,8 @@ struct RowsCfg {
     static_assert(JG * KS == NW && EU >= 1, "wave layout");
 };
 
-// Value of lane (l ^ D).  D = 1, 2, 4, 8 are DPP moves inside a row of 16 lanes, 16 is an LDS
-// crossbar swizzle inside each half wave, 32 goes through ds_bpermute.
-template <int D>
-__device__ __forceinline__ float lane_xor(float v)
-{
-    const int x = __float_as_int(v);
-    int r;
-    if constexpr (D == 1) r = __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xf, 0xf, true);          // quad_perm [1,0,3,2]
-    else if constexpr (D == 2) r = __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xf, 0xf, true);     // quad_perm [2,3,0,1]
-    else if constexpr (D == 4) {
-        r = __builtin_amdgcn_update_dpp(0, x, 0x104, 0xf, 0x5, false);                          // row_shl:4, lanes with bit 2 clear
-        r = __builtin_amdgcn_update_dpp(r, x, 0x114, 0xf, 0xa, false);                          // row_shr:4, lanes with bit 2 set
-    } else if constexpr (D == 8) r = __builtin_amdgcn_update_dpp(0, x, 0x128, 0xf, 0xf, true);  // row_ror:8
-    else if constexpr (D == 16) r = __builtin_amdgcn_ds_swizzle(x, 0x401F);                     // xor 16 in groups of 32
-    else r = __shfl_xor(x, 32, 64);
-    return __int_as_float(r);
-}
-
-// Sum each of the N per-lane values over the 64 lanes of the wave.  On return lane L holds in
-// v[0] the total of original index bitreverse(L mod N): each step a lane hands half of its
-// values to its partner and keeps the other half, so the work halves every step.
-template <int N, int H, int D>
-struct TransposeStep {
-    static __device__ __forceinline__ void run(float (&v)[N], int lane)
-    {
-        const bool up = (lane & D) != 0;
-#pragma unroll
-        for (int i = 0; i < H; ++i) {
-            const float send = up ? v[i] : v[i + H];
-            const float keep = up ? v[i + H] : v[i];
-            v[i] = keep + lane_xor<D>(send);
-        }
-        TransposeStep<N, H / 2, D * 2>::run(v, lane);
-    }
-};
-template <int N, int D>
-struct TransposeStep<N, 0, D> {
-    static __device__ __forceinline__ void run(float (&v)[N], int lane)
-    {
-        if constexpr (D < 64) {
-            v[0] += lane_xor<D>(v[0]);
-            TransposeStep<N, 0, D * 2>::run(v, lane);
-        }
-    }
-};
-template <int N>
-__device__ __forceinline__ void wave_sum_transpose(float (&v)[N], int lane)
-{
-    TransposeStep<N, N / 2, 1>::run(v, lane);
-}
-
 // Calls f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N - 1>): a loop whose
 // index is a compile-time constant inside the body (register arrays stay in registers).
-template <int I> struct IntC { static constexpr int value = I; };
 template <int N, int I = 0, typename F>
 __device__ __forceinline__ void static_for(F &&f)
 {
@@ -113,18 +62,6 @@ __device__ __forceinline__ void static_for(F &&f)
         static_for<N, I + 1>(f);
     }
 }
-
-template <int BITS>
-__device__ __forceinline__ int bitrev(int x)
-{
-    int r = 0;
-#pragma unroll
-    for (int b = 0; b < BITS; ++b) r |= ((x >> b) & 1) << (BITS - 1 - b);
-    return r;
-}
-
-template <int N> struct Log2 { static constexpr int v = 1 + Log2<N / 2>::v; };
-template <> struct Log2<1> { static constexpr int v = 0; };
 
 template <int OPL> struct YVec;
 template <> struct YVec<1> { typedef uint16_t T; };
@@ -205,7 +142,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         const int jg = w % C::JG, ks = w / C::JG;
         // ---- which chunk, which part of it ----
         int chunk, kslice = 0, out0 = 0, out1 = a.d_out;
-        bool do_shrink = true, do_expand = true;
+        bool do_shrink = true, do_expand = a.h_out == nullptr;      // (h_out: the first launch of the MoE down projection only shrinks)
         int part_i = 0;
         if (a.tile_par > 1) {
             // workgroups are dealt round-robin to the 8 XCDs: keep the parts of one chunk (they share
@@ -215,7 +152,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
             part_i = idx - grp8 * a.tile_par;
             chunk = grp8 * 8 + (item & 7);
             out0 = part_i * a.out_per_part; out1 = min(a.d_out, out0 + a.out_per_part);
-            do_expand = out0 < out1;
+            do_expand = out0 < out1 && a.h_out == nullptr;
             if (chunk >= a.grid_chunks) continue;
         } else {
             // neighbouring chunks can belong to one adapter (and expert): keep them on one XCD, where
@@ -286,15 +223,15 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         const bool xitem = use_x && !solo;
         // ---- one flight: every load of this item is issued here ----
         const uint16_t *Bg = a.b_tab + (int64_t)key * a.d_out * RP;
-        const bool to_parts = a.out_f32 != nullptr;               // MoE down projection: weighted fp32 deltas, no add into y
+        // MoE down projection, first launch: no expand here; the chunk's scaled h, times the row's
+        // routing weight, goes to a.h_out (the weights travel with the flight)
+        const bool h_only = a.h_out != nullptr;
         uint16_t *yrow[kChunk];
-        float *prow[kChunk];
         float wrow[kChunk];
 #pragma unroll
         for (int c = 0; c < kChunk; ++c) {
             yrow[c] = a.y + (int64_t)row[c] * a.ldy;
-            prow[c] = a.out_f32 + (int64_t)row[c] * a.ldo;
-            wrow[c] = to_parts ? a.row_w[row[c] + lane_zero] : 1.f;
+            wrow[c] = h_only ? a.row_w[row[c] + lane_zero] : 1.f;
         }
         // Matrix-core expand: the result comes out with lane l holding row l%4 of the chunk and the four
         // outputs of its block (see below), so a lane reads and writes 8 contiguous bytes of its own row:
@@ -302,8 +239,6 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         const int r4 = lane & 3;
         const int my_row = r4 == 0 ? row[0] : (r4 == 1 ? row[1] : (r4 == 2 ? row[2] : row[3]));
         char *const y_lane = (char *)(a.y + (int64_t)my_row * a.ldy);
-        char *const p_lane = (char *)(a.out_f32 + (int64_t)my_row * a.ldo);
-        const float w_lane = (C::MX && to_parts) ? a.row_w[my_row] : 1.f;
         uint4 braw[C::DEPTH][C::EU][C::BV];
         yvec_t yraw[C::DEPTH][C::EU][C::MX ? 1 : kChunk];
         uint2 yq[C::DEPTH][C::EU];
@@ -317,7 +252,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                 // uniform 64-bit base + 32-bit per-lane byte offset: no 64-bit address registers per lane
 #pragma unroll
                 for (int q = 0; q < C::BV; ++q) braw[d][e][q] = *(const uint4 *)((const char *)Bg + (oc * (uint32_t)(RP * 2) + (uint32_t)(q * 16)));
-                if (!to_parts) {
+                {
                     if constexpr (C::MX) {
                         yq[d][e] = *(const uint2 *)(y_lane + (oc & ~3u) * 2u);
                     } else {
@@ -444,6 +379,16 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         const bool h_thread = tid < kChunk * RP && hc < cnt;
         if (!xitem) {
             if (tid < kChunk * RP) hs[hc][hj] = own * scale;
+            if (h_only) {
+                // weighted, scaled h of row hc as a bf16 head (truncated) and tail (rounded) in one word:
+                // 16 bits of it reach the matrix cores of the second launch; rows of an empty slot are skipped there too
+                if (h_thread && rank > 0) {
+                    const float f = own * scale * (hc == 0 ? wrow[0] : (hc == 1 ? wrow[1] : (hc == 2 ? wrow[2] : wrow[3])));
+                    const int hrow = hc == 0 ? row[0] : (hc == 1 ? row[1] : (hc == 2 ? row[2] : row[3]));
+                    const uint32_t hi = __float_as_uint(f) & 0xffff0000u;
+                    a.h_out[(int64_t)hrow * RP + hj] = (hi >> 16) | (f2bf(f - __uint_as_float(hi)) << 16);
+                }
+            }
             __syncthreads();
         } else {
             uint64_t *xw = a.xch + ((int64_t)(chunk * a.ksplit) * kChunk + hc) * RP + hj;   // + k * kChunk * RP: slice k
@@ -538,16 +483,10 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                                 }
                                 const int ob = o & ~3;                            // first output of this lane's block
                                 if (r4 < cnt && ob < out1 && rank > 0) {          // empty slot: rows stay untouched
-                                    if (to_parts) {
-                                        st_quiet(p_lane + (uint32_t)ob * 4u,
-                                                 make_uint4(__float_as_uint(w_lane * (d0[0] + d1[0])), __float_as_uint(w_lane * (d0[1] + d1[1])),
-                                                            __float_as_uint(w_lane * (d0[2] + d1[2])), __float_as_uint(w_lane * (d0[3] + d1[3]))));
-                                    } else {
-                                        const uint2 yv = yq[d][e];
-                                        st_quiet(y_lane + (uint32_t)ob * 2u,
-                                                 make_uint2(pack_bf2(bf_lo(yv.x) + (d0[0] + d1[0]), bf_hi(yv.x) + (d0[1] + d1[1])),
-                                                            pack_bf2(bf_lo(yv.y) + (d0[2] + d1[2]), bf_hi(yv.y) + (d0[3] + d1[3]))));
-                                    }
+                                    const uint2 yv = yq[d][e];
+                                    st_quiet(y_lane + (uint32_t)ob * 2u,
+                                             make_uint2(pack_bf2(bf_lo(yv.x) + (d0[0] + d1[0]), bf_hi(yv.x) + (d0[1] + d1[1])),
+                                                        pack_bf2(bf_lo(yv.y) + (d0[2] + d1[2]), bf_hi(yv.y) + (d0[3] + d1[3]))));
                                 }
                             } else {
                                 // hs is re-read for every output group: keeping all of it in registers across
@@ -566,12 +505,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                                 for (int c = 0; c < kChunk; ++c) {
                                     if (c < cnt && o < out1 && rank > 0) {        // empty slot: rows stay untouched
                                         float yf[C::OPL];
-                                        if (to_parts) {
-#pragma unroll
-                                            for (int q = 0; q < C::OPL; ++q) yf[q] = 0.f;
-                                        } else {
-                                            y_unpack(yraw[d][e][c], yf);
-                                        }
+                                        y_unpack(yraw[d][e][c], yf);
 #pragma unroll
                                         for (int q = 0; q < C::OPL; ++q) {
                                             float dlt = 0.f;
@@ -579,14 +513,9 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                                             for (int j = 0; j < RP; ++j) dlt = fmaf(hs[c][j], bf[q * RP + j], dlt);
                                             yf[q] += dlt;
                                         }
-                                        if (to_parts) {
-#pragma unroll
-                                            for (int q = 0; q < C::OPL; ++q) st_quiet(prow[c] + o + q, __float_as_uint(wrow[c] * yf[q]));
-                                        } else {
-                                            yvec_t out;
-                                            y_pack(yf, out);
-                                            st_quiet(yrow[c] + o, out);
-                                        }
+                                        yvec_t out;
+                                        y_pack(yf, out);
+                                        st_quiet(yrow[c] + o, out);
                                     }
                                 }
                             }
@@ -714,7 +643,7 @@ static void set_parts(RowsArgs &a, int parts, bool exchange)
         if (parts * a.r_pad > 128) parts = 128 / a.r_pad;
     }
     if (parts > groups) parts = groups;
-    if (parts < 1 || a.n_experts != 1) parts = 1;
+    if (parts < 1 || a.n_experts != 1 || a.h_out) parts = 1;       // (a launch that only shrinks has no outputs to divide)
     const int gpp = (groups + parts - 1) / parts;
     a.out_per_part = gpp * 64;
     a.tile_par = (groups + gpp - 1) / gpp;
@@ -825,7 +754,7 @@ static hipError_t launch_multi_rp(const RowsArgs *sites, int n, hipStream_t st, 
 // 8-wave shrink busy, a packed MoE site takes 4 waves when 8 would be mostly idle.
 int rows_group_waves(const RowsArgs &a)
 {
-    if ((a.r_pad != 8 && a.r_pad != 16) || a.out_f32 || tuning(kRowsWaves)) return 0;
+    if ((a.r_pad != 8 && a.r_pad != 16) || a.h_out || tuning(kRowsWaves)) return 0;
     const int U = a.d_in >> 3;
     const int flu8 = a.r_pad == 8 ? RowsCfg<8, 8>::FLU : RowsCfg<16, 8>::FLU;
     if (U >= flu8 * 3 / 4) return 8;
@@ -850,7 +779,7 @@ static bool wide_enough_for_8_waves(int U) { return RP >= 64 || U >= RowsCfg<RP,
 
 bool rows_plans_alone(const RowsArgs &a)
 {
-    if (a.n_experts != 1 || a.out_f32 || tuning(kRowsWaves)) return false;
+    if (a.n_experts != 1 || a.h_out || tuning(kRowsWaves)) return false;
     const int U = a.d_in >> 3;
     switch (a.r_pad) {
         case 1:  return wide_enough_for_8_waves<1>(U);
@@ -909,54 +838,6 @@ hipError_t launch_rows(const RowsArgs &a, hipStream_t st)
         case 64: return launch_nw<64>(a, st);
     }
     return hipErrorInvalidValue;
-}
-
-// Second launch of the MoE down projection: token t adds its K rows of weighted fp32 deltas, k
-// upwards (a fixed order: no atomics, the result is deterministic), to y[t, :] and rounds once.
-// Tokens whose slot holds no adapter are skipped; their rows of `parts` were never written.
-__global__ __launch_bounds__(256)
-void moe_combine_kernel(uint16_t *y, int64_t ldy, const float *parts, int64_t ldo, const int32_t *token_slot,
-                        const int32_t *rank, int32_t n_slots, int32_t K, int32_t d_out)
-{
-    const int t = (int)blockIdx.x;
-    const int s = token_slot[t];
-    if (s < 0 || s >= n_slots || rank[s] <= 0) return;
-    uint16_t *yr = y + (int64_t)t * ldy;
-    const float *pr = parts + (int64_t)t * K * ldo;
-    for (int o = (int)threadIdx.x * 8; o < d_out; o += 256 * 8) {
-        const uint4 yv = *(const uint4 *)(yr + o);
-        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int k0 = 0; k0 < K; k0 += 4) {            // four rows in flight at a time
-            float4 v[4][2];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int kk = min(k0 + k, K - 1);
-                v[k][0] = *(const float4 *)(pr + (int64_t)kk * ldo + o);
-                v[k][1] = *(const float4 *)(pr + (int64_t)kk * ldo + o + 4);
-            }
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                if (k0 + k < K) {
-                    acc[0] += v[k][0].x; acc[1] += v[k][0].y; acc[2] += v[k][0].z; acc[3] += v[k][0].w;
-                    acc[4] += v[k][1].x; acc[5] += v[k][1].y; acc[6] += v[k][1].z; acc[7] += v[k][1].w;
-                }
-            }
-        }
-        uint4 out;
-        out.x = pack_bf2(bf_lo(yv.x) + acc[0], bf_hi(yv.x) + acc[1]);
-        out.y = pack_bf2(bf_lo(yv.y) + acc[2], bf_hi(yv.y) + acc[3]);
-        out.z = pack_bf2(bf_lo(yv.z) + acc[4], bf_hi(yv.z) + acc[5]);
-        out.w = pack_bf2(bf_lo(yv.w) + acc[6], bf_hi(yv.w) + acc[7]);
-        *(uint4 *)(yr + o) = out;
-    }
-}
-
-hipError_t launch_moe_combine(uint16_t *y, int64_t ldy, const float *parts, int64_t ldo, const int32_t *token_slot,
-                              const int32_t *rank, int32_t n_slots, int32_t T, int32_t K, int32_t d_out, hipStream_t st)
-{
-    if (T <= 0) return hipSuccess;
-    moe_combine_kernel<<<dim3((unsigned)T), dim3(256), 0, st>>>(y, ldy, parts, ldo, token_slot, rank, n_slots, K, d_out);
-    return hipGetLastError();
 }
 
 }  // namespace mlora

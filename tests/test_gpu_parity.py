@@ -872,10 +872,12 @@ def check_moe_down(M, oracle, c, site, tokens=None, report=None):
     assert np.array_equal(got, run_moe_down(M, site, c, c.y0)), "two runs differ: the combine must be deterministic"
 
 
-@pytest.mark.parametrize("T,K,E,S,r", [(37, 2, 4, 3, 8), (200, 4, 16, 5, 4), (64, 8, 8, 2, 16), (9, 1, 1, 2, 2), (50, 3, 6, 4, 1)])
+@pytest.mark.parametrize("T,K,E,S,r", [(37, 2, 4, 3, 8), (200, 4, 16, 5, 4), (64, 8, 8, 2, 16), (9, 1, 1, 2, 2), (50, 3, 6, 4, 1),
+                                       (300, 2, 5, 2, 8), (70, 2, 4, 2, 32), (40, 2, 3, 2, 64), (260, 4, 40, 2, 16)])
 def test_moe_down_small(M, oracle, T, K, E, S, r):
     """Down projection with the routing-weight combine: ragged widths, tokens without adapter, an
-    empty slot, K from 1 to 8, every padded rank path of the vector kernel."""
+    empty slot, K from 1 to 8, every padded rank, odd expert counts (a half-filled last contraction
+    step), slots with more tokens than one tile holds, several chunks of the contraction axis."""
     ranks = [r] * S
     if S > 2:
         ranks[1] = 0
@@ -884,6 +886,78 @@ def test_moe_down_small(M, oracle, T, K, E, S, r):
     c.token_slot[::7] = -1
     site = moe_site(M, c)
     check_moe_down(M, oracle, c, site)
+
+
+def test_moe_down_pairs_the_plan_left_out(M, oracle):
+    """Pairs that the route plan drops must add nothing: expert ids outside [0, E) (masked or padded
+    routing tables), and tokens whose slot was not ready at the site the plan was built against
+    although it is at the down site.  Whatever the workspace held before (NaN patterns here) must
+    not reach y."""
+    c = W.moe_down_case("down_masked", 5390, 90, 4, 8, 136, 200, 4, 8, 16.0, std_a=0.05, std_b=0.05)
+    c.token_slot[::9] = -1
+    masked = c.topk.copy()
+    masked[::3, 1] = -1                                # a masked entry in every third token
+    masked[5::7, 3] = c.E + 2                          # and some ids past the last expert
+    site = moe_site(M, c)
+    # the oracle takes valid ids only: the dropped pairs get weight 0 on expert 0
+    dropped = (masked < 0) | (masked >= c.E)
+    ok_topk, ok_w = np.where(dropped, 0, masked).astype(np.int32), np.where(dropped, 0.0, c.w).astype(np.float32)
+    ref = oracle.apply_moe_down(c.x, c.y0, c.A, c.B, c.rank, c.alpha, ok_topk, ok_w, c.token_slot)
+
+    def run(topk, ready_from):
+        x, y = P.dev_bf16(c.x), P.dev_bf16(c.y0)
+        ts = torch.from_numpy(c.token_slot).cuda()
+        plan = M.Plan(c.T * c.K, c.n_slots * c.E)
+        M.moe_plan_route(plan, torch.from_numpy(topk).cuda(), ts, c.n_slots, c.E, ready_from=ready_from)
+        ws = torch.empty(M.moe_down_workspace_bytes(c.T, c.K, c.d_out), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)
+        M.moe_lora_apply_down(site, plan, x, torch.from_numpy(c.w).cuda(), ts, ws, y)
+        torch.cuda.synchronize()
+        return P.host_bits(y)
+    for pipeline in (0, 1):                            # both forms of the route index build record the pairs' keys
+        M.set_tuning("plan_pipeline", pipeline)
+        try:
+            got = run(masked, site)
+        finally:
+            M.set_tuning("plan_pipeline", 0)
+        P.check_close(got, ref, f"masked ids (pipeline={pipeline})")
+        P.check_untouched(got, c.y0, c.token_slot < 0, "masked ids")
+    # a plan built against a site where slot 2 is empty: the tokens of slot 2 stay untouched here
+    other = moe_site(M, c)
+    M.lora_slots_evict(other, 2)
+    got = run(c.topk, other)
+    slots2 = np.where(c.token_slot == 2, -1, c.token_slot).astype(np.int32)
+    ref2 = oracle.apply_moe_down(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, c.w, slots2)
+    P.check_close(got, ref2, "plan from another site")
+    P.check_untouched(got, c.y0, slots2 < 0, "plan from another site")
+    assert not np.array_equal(got[slots2 >= 0], c.y0[slots2 >= 0])
+
+
+def test_moe_down_shrink_through_the_chunk_kernels(M, oracle):
+    """Ranks above 16 take the first launch through the chunk kernels; the switch sends a rank-8 site
+    the same way, and the result must meet the oracle like the wave-per-group launch does."""
+    c = W.moe_down_case("down_rows_shrink", 5397, 120, 4, 16, 136, 200, 3, 8, 16.0, std_a=0.05, std_b=0.05)
+    site = moe_site(M, c)
+    M.set_tuning("down_rows_shrink", 1)
+    try:
+        check_moe_down(M, oracle, c, site)
+    finally:
+        M.set_tuning("down_rows_shrink", 0)
+
+
+def test_moe_down_limits(M, oracle):
+    """Sixteen experts per token is the most the down projection takes; more is refused before any launch."""
+    c = W.moe_down_case("down_k16", 5395, 40, 16, 32, 72, 136, 3, 4, 8.0, std_a=0.05, std_b=0.05)
+    check_moe_down(M, oracle, c, moe_site(M, c))
+    c17 = W.moe_down_case("down_k17", 5396, 8, 17, 32, 72, 136, 3, 4, 8.0, std_a=0.05, std_b=0.05)
+    site = moe_site(M, c17)
+    plan = M.Plan(c17.T * c17.K, c17.n_slots * c17.E)
+    ts = torch.from_numpy(c17.token_slot).cuda()
+    M.moe_plan_route(plan, torch.from_numpy(c17.topk).cuda(), ts, c17.n_slots, c17.E)
+    ws = torch.empty(M.moe_down_workspace_bytes(c17.T, c17.K, c17.d_out), dtype=torch.uint8, device="cuda")
+    with pytest.raises(M.MLoraError) as e:
+        M.moe_lora_apply_down(site, plan, P.dev_bf16(c17.x), torch.from_numpy(c17.w).cuda(), ts, ws, P.dev_bf16(c17.y0))
+    assert e.value.status == -6
 
 
 def test_c4_moe_down_full(M, oracle):
