@@ -232,38 +232,79 @@ __device__ __forceinline__ int route_key(const int32_t *__restrict__ topk, const
 
 __device__ __forceinline__
 void plan_route_one_body(const PlanView &pv, const int32_t *__restrict__ topk, const int32_t *__restrict__ token_slot,
-                         int P, uint32_t k_magic, int E, int n_slots, const int32_t *__restrict__ ready_rank,
+                         int P, int K, uint32_t k_magic, int E, int n_slots, const int32_t *__restrict__ ready_rank,
                          int32_t *__restrict__ out_sorted, int32_t *__restrict__ out_group_off, int rec_bound, const int block)
 {
-    __shared__ int32_t goff[kOneKeys + 1];       // histogram of all pairs, then exclusive group starts
-    __shared__ int32_t pre[kOneKeys];            // histogram of the pairs in front of this range
+    __shared__ int32_t goff[kOneKeys + 1];       // exclusive group starts
+    __shared__ uint32_t cnt2[kOneKeys];          // per key: pairs in the batch (low half) | pairs in front of this range (high half)
     __shared__ int32_t cbase[kOneKeys + 1];      // first chunk of each group
     __shared__ __attribute__((aligned(16))) int32_t lkey[kOneRange];
     __shared__ int32_t lrank[kOneRange];
     __shared__ __attribute__((aligned(16))) int32_t wave_tot[16];
     static_assert(kOneThreads == 4 * kOneRange, "four threads per pair in the in-range rank");
+    static_assert(kOnePairs <= 32768, "two 16-bit counts per word");
     const int tid = threadIdx.x, NK = n_slots * E;
     const int p0 = block * kOneRange;
     const bool records = pv.chunks != nullptr;   // (the token-level grouping of a route plan has none)
-    for (int k = tid; k < NK; k += kOneThreads) { goff[k] = 0; pre[k] = 0; }
+    for (int k = tid; k < NK; k += kOneThreads) cnt2[k] = 0u;
     if (tid < kOneRange) lkey[tid] = -1;         // positions past the batch
     __syncthreads();
-    constexpr int kU = 16;                                      // keys per thread in flight
-    for (int q0 = 0; q0 < P; q0 += kU * kOneThreads) {
-        int key[kU];
+    // one visit per pair: both counts in one LDS add, and the keys of this range kept
+    auto visit = [&](int q, int key) __attribute__((always_inline)) {
+        if (key >= 0) atomicAdd(&cnt2[key], q < p0 ? 0x10001u : 1u);
+        if (q >= p0 && q < p0 + kOneRange) lkey[q - p0] = key;
+    };
+    if (topk && K > 1) {
+        // a thread takes whole tokens: the slot (and whether it is ready) once, the token's K experts
+        // as 16-byte pieces where K allows -- an eighth of the loads of a pair-by-pair walk at K = 8
+        const int T = P / K;
+        const bool vec = K <= 16 && !(K & 3) && !((uintptr_t)topk & 15);    // a token's experts as 16-byte pieces
+        constexpr int kT = 2;                                   // tokens per thread in flight
+        for (int t0 = 0; t0 < T; t0 += kT * kOneThreads) {
+            int sl[kT];
+            int4 ex[kT][4];
 #pragma unroll
-        for (int u = 0; u < kU; ++u) {
-            const int q = q0 + u * kOneThreads + tid;
-            key[u] = q < P ? route_key(topk, token_slot, ready_rank, q, k_magic, E, n_slots) : -1;
-        }
+            for (int u = 0; u < kT; ++u) {
+                const int t = t0 + u * kOneThreads + tid;
+                sl[u] = t < T ? token_slot[t] : -1;
+                if (t < T && vec) {
 #pragma unroll
-        for (int u = 0; u < kU; ++u) {
-            const int q = q0 + u * kOneThreads + tid;
-            if (key[u] >= 0) {
-                atomicAdd(&goff[key[u]], 1);
-                if (q < p0) atomicAdd(&pre[key[u]], 1);
+                    for (int v = 0; v < 4; ++v) if (4 * v < K) ex[u][v] = *(const int4 *)(topk + (int64_t)t * K + 4 * v);
+                }
             }
-            if (q >= p0 && q < p0 + kOneRange) lkey[q - p0] = key[u];
+#pragma unroll
+            for (int u = 0; u < kT; ++u) {
+                const int t = t0 + u * kOneThreads + tid;
+                if (t >= T) continue;
+                const int s = sl[u];
+                const bool ok = s >= 0 && s < n_slots && !(ready_rank && ready_rank[s] <= 0);
+                if (vec) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        if (4 * v >= K) break;
+                        const int e4[4] = {ex[u][v].x, ex[u][v].y, ex[u][v].z, ex[u][v].w};
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) visit(t * K + 4 * v + i, ok && e4[i] >= 0 && e4[i] < E ? s * E + e4[i] : -1);
+                    }
+                } else {
+                    for (int k = 0; k < K; ++k) {
+                        const int e = topk[(int64_t)t * K + k];
+                        visit(t * K + k, ok && e >= 0 && e < E ? s * E + e : -1);
+                    }
+                }
+            }
+        }
+    } else {
+        constexpr int kU = 16;                                  // keys per thread in flight
+        for (int q0 = 0; q0 < P; q0 += kU * kOneThreads) {
+            int key[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const int q = q0 + u * kOneThreads + tid;
+                key[u] = q < P ? route_key(topk, token_slot, ready_rank, q, k_magic, E, n_slots) : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u) visit(q0 + u * kOneThreads + tid, key[u]);
         }
     }
     if (tid < kOneRange) lrank[tid] = 0;
@@ -283,19 +324,19 @@ void plan_route_one_body(const PlanView &pv, const int32_t *__restrict__ topk, c
             if (r) atomicAdd(&lrank[i], r);
         }
     }
-    // exclusive scans of the group sizes and of the groups' chunk counts, in place
+    // exclusive scans of the group sizes and of the groups' chunk counts: one scan of both, 16 bits
+    // each (at most kOnePairs = 2^15 pairs, and no more chunks than pairs)
     const int per = (NK + kOneThreads - 1) / kOneThreads;       // <= 4
     const int lo = min(NK, tid * per), hi = min(NK, lo + per);
-    int cnt[kOneKeys / kOneThreads], items = 0, chunks = 0;
+    int cnt[kOneKeys / kOneThreads], both = 0;
 #pragma unroll
     for (int u = 0; u < kOneKeys / kOneThreads; ++u) {
-        cnt[u] = lo + u < hi ? goff[lo + u] : 0;
-        items += cnt[u];
-        chunks += (cnt[u] + kChunk - 1) / kChunk;
+        cnt[u] = lo + u < hi ? (int)(cnt2[lo + u] & 0xffffu) : 0;
+        both += cnt[u] | ((cnt[u] + kChunk - 1) / kChunk) << 16;
     }
-    const int inc_i = block_scan<false>(items, tid, 16, wave_tot);
-    const int inc_c = block_scan<false>(chunks, tid, 16, wave_tot);
-    int run_i = inc_i - items, run_c = inc_c - chunks;
+    const int inc = block_scan<false>(both, tid, 16, wave_tot);
+    const int inc_i = inc & 0xffff, inc_c = (int)((uint32_t)inc >> 16);
+    int run_i = inc_i - (both & 0xffff), run_c = inc_c - (int)((uint32_t)both >> 16);
 #pragma unroll
     for (int u = 0; u < kOneKeys / kOneThreads; ++u) {
         if (lo + u < hi) {
@@ -327,7 +368,7 @@ void plan_route_one_body(const PlanView &pv, const int32_t *__restrict__ topk, c
             const int key = lkey[tid];
             pv.key_of[j] = key;                      // (the key as this plan saw it: the MoE down projection asks per pair)
             if (key >= 0) {
-                const int r = pre[key] + lrank[tid];
+                const int r = (int)(cnt2[key] >> 16) + lrank[tid];
                 const int off = goff[key], n = goff[key + 1] - off;
                 pv.sorted[off + r] = j;
                 if (out_sorted) out_sorted[off + r] = j;
@@ -345,16 +386,16 @@ void plan_route_one_body(const PlanView &pv, const int32_t *__restrict__ topk, c
 // (route plans only) group the tokens by slot with the same code: key = slot, one item per token.
 __global__ __launch_bounds__(kOneThreads)
 void plan_route_one_kernel(PlanView pv, const int32_t *__restrict__ topk, const int32_t *__restrict__ token_slot,
-                           int P, uint32_t k_magic, int E, int n_slots, const int32_t *__restrict__ ready_rank,
+                           int P, int K, uint32_t k_magic, int E, int n_slots, const int32_t *__restrict__ ready_rank,
                            int32_t *__restrict__ out_sorted, int32_t *__restrict__ out_group_off, int rec_bound,
                            int pair_blocks, int T)
 {
     const int b = (int)blockIdx.x;
     if (b < pair_blocks) {
-        plan_route_one_body(pv, topk, token_slot, P, k_magic, E, n_slots, ready_rank, out_sorted, out_group_off, rec_bound, b);
+        plan_route_one_body(pv, topk, token_slot, P, K, k_magic, E, n_slots, ready_rank, out_sorted, out_group_off, rec_bound, b);
     } else {
         const PlanView tv = plan_token_view(pv);
-        plan_route_one_body(tv, nullptr, token_slot, T, 0u, 1, n_slots, ready_rank, nullptr, nullptr, 0, b - pair_blocks);
+        plan_route_one_body(tv, nullptr, token_slot, T, 1, 0u, 1, n_slots, ready_rank, nullptr, nullptr, 0, b - pair_blocks);
     }
 }
 
@@ -372,7 +413,7 @@ hipError_t launch_plan_general(const PlanView &pv, const int32_t *topk, const in
     if (plan_route_in_one_launch(P, NK)) {
         const int pair_blocks = (P + kOneRange - 1) / kOneRange, tok_blocks = route ? (T + kOneRange - 1) / kOneRange : 0;
         plan_route_one_kernel<<<dim3((unsigned)(pair_blocks + tok_blocks)), dim3(kOneThreads), 0, st>>>(
-            pv, topk, token_slot, P, K > 1 ? (uint32_t)((0x100000000ull + (uint64_t)K - 1) / (uint64_t)K) : 0u, E, n_slots,
+            pv, topk, token_slot, P, K, K > 1 ? (uint32_t)((0x100000000ull + (uint64_t)K - 1) / (uint64_t)K) : 0u, E, n_slots,
             ready_rank, out_sorted, out_group_off, (int)max_chunks(P, NK), pair_blocks, T);
         return hipGetLastError();
     }

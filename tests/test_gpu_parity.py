@@ -778,6 +778,28 @@ def test_rank_bounded_reads_of_padded_slots(M, oracle):
     check_moe(M, oracle, big, moe_site(M, big), pairs=np.sort(rng.choice(1500 * 4, 500, replace=False)))
 
 
+def test_route_index_build_from_an_unaligned_routing_table(M, oracle):
+    """The one-launch build reads a token's experts as 16-byte pieces where it can; a routing table
+    that does not start on a 16-byte boundary (a view into a larger buffer) must give the same index."""
+    T, K, E, S = 333, 8, 32, 6
+    g = W.rng(7790)
+    topk = g.integers(0, E, size=(T, K)).astype(np.int32)
+    slots = g.integers(-1, S, size=T).astype(np.int32)
+    ref_sp, ref_go = oracle.route_sort(topk, slots, np.ones(S, dtype=np.int32), E)
+    big = torch.zeros(T * K + 4, dtype=torch.int32, device="cuda")
+    for shift in (1, 2, 3):
+        tk = big[shift:shift + T * K].view(T, K)
+        tk.copy_(torch.from_numpy(topk))
+        assert tk.data_ptr() % 16 != 0
+        plan = M.Plan(T * K, S * E)
+        sp = torch.full((T * K,), -7, dtype=torch.int32, device="cuda")
+        go = torch.full((S * E + 1,), -7, dtype=torch.int32, device="cuda")
+        M.moe_plan_route(plan, tk, torch.from_numpy(slots).cuda(), S, E, out_sorted_pair=sp, out_group_off=go)
+        torch.cuda.synchronize()
+        assert np.array_equal(go.cpu().numpy(), ref_go)
+        assert np.array_equal(sp.cpu().numpy(), ref_sp)
+
+
 def test_moe_planned_reuse(M, oracle):
     """One route plan shared by two sites (gate and up share the routing)."""
     ca = W.moe_case("gate", 5200, 120, 4, 8, 128, 64, 4, 8, 16.0, std_a=0.05, std_b=0.05)
@@ -796,7 +818,7 @@ def test_moe_planned_reuse(M, oracle):
 
 
 @pytest.mark.parametrize("T,K,E,S", [(37, 2, 4, 3), (1000, 3, 7, 5), (300, 1, 1, 9), (2048, 8, 128, 32), (4096, 8, 64, 64),
-                                     (4097, 8, 64, 64), (640, 4, 160, 32)])
+                                     (4097, 8, 64, 64), (640, 4, 160, 32), (50, 12, 20, 3), (30, 20, 24, 2), (1500, 16, 64, 8)])
 def test_route_index_build_paths_agree(M, oracle, T, K, E, S):
     """The route index build has a one-launch form (every workgroup histograms all pairs in LDS) for
     up to 32768 pairs and 4096 (slot, expert) keys, and a four-launch pipeline for everything else:
