@@ -35,6 +35,8 @@ struct mlora_site {
     hipEvent_t stage_ev[2];
     bool stage_busy[2];
     int stage_next;
+    hipStream_t seg_side = nullptr;   // rank-64 prefill with batches in flight: the shrinks' stream and its events (lazy)
+    hipEvent_t seg_ev[5] = {};
     std::vector<int32_t> host_rank;   // what the uploads asked for, per slot (0 = empty): a hint for the launch shape only
     int32_t n_short = 0;        // slots whose rank is below the padded rank of the tables
     void *pack;                 // pinned host image of one slot (A part, then B part) for uploads from per-expert tensors (lazy)
@@ -60,7 +62,7 @@ constexpr int32_t kSegHpBlocks = (int32_t)((kSegXchBytes - kXchBytes - kSegCount
 std::atomic<int32_t> g_knob[kKnobCount];
 const char *const kKnobName[kKnobCount] = {
     "rows_poll_limit", "rows_rank_bound", "rows_items_target", "rows_mode", "rows_waves", "rows_prefetch", "plan_general",
-    "plan_separate", "plan_pipeline", "seg_expand_groups", "seg_table_copy", "seg_shrink_wgs", "seg_no_mfma", "seg_fused",
+    "plan_separate", "plan_pipeline", "seg_expand_groups", "seg_table_copy", "seg_shrink_wgs", "seg_no_mfma", "seg_overlap",
     "upload_piece_kb", "down_rows_shrink"};
 
 // Host-side record of a slot's rank (the kernels read the device table; this only tells the launch
@@ -246,6 +248,30 @@ int32_t stage_table(mlora_site *s, const std::vector<int32_t> &tab, hipStream_t 
     return MLORA_OK;
 }
 
+// Batches of the rank-64 prefill with their shrinks on the site's second stream, one batch ahead of the
+// expands on the caller's stream.  Batch i uses half i % 2 of the partial-result buffers, so shrink
+// i + 2 waits for expand i.  The second stream forks from the caller's stream and is joined back into it
+// (the last expand waits for the last shrink), so the call behaves like work on `st` alone, also
+// under stream capture.
+int32_t launch_seg_overlapped(mlora_site *s, const std::vector<SegArgs> &subs, hipStream_t st)
+{
+    if (!s->seg_side) {
+        if (!ok(hipStreamCreateWithFlags(&s->seg_side, hipStreamNonBlocking))) return MLORA_E_HIP;
+        for (int k = 0; k < 5; ++k)
+            if (!ok(hipEventCreateWithFlags(&s->seg_ev[k], hipEventDisableTiming))) return MLORA_E_HIP;
+    }
+    hipEvent_t fork = s->seg_ev[0], *shrunk = s->seg_ev + 1, *expanded = s->seg_ev + 3;
+    if (!ok(hipEventRecord(fork, st)) || !ok(hipStreamWaitEvent(s->seg_side, fork, 0))) return MLORA_E_HIP;
+    const int n = (int)subs.size();
+    for (int i = 0; i < n; ++i) {
+        if (i >= 2 && !ok(hipStreamWaitEvent(s->seg_side, expanded[i & 1], 0))) return MLORA_E_HIP;
+        if (!ok(launch_seg_shrink(subs[i], s->seg_side)) || !ok(hipEventRecord(shrunk[i & 1], s->seg_side))) return MLORA_E_HIP;
+        if (!ok(hipStreamWaitEvent(st, shrunk[i & 1], 0)) || !ok(launch_seg_expand(subs[i], st))) return MLORA_E_HIP;
+        if (i + 2 < n && !ok(hipEventRecord(expanded[i & 1], st))) return MLORA_E_HIP;
+    }
+    return MLORA_OK;
+}
+
 // Rank-64 prefill: cut the segments into tiles of 64 rows (shrink items) and into equal groups of
 // 32-row blocks (expand items), in batches that fit the partial-result buffer, and launch shrink +
 // expand per batch.
@@ -279,9 +305,11 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
     if (cap_e <= 0) return MLORA_E_HIP;
     int32_t groups_wanted = tuning(kSegExpandGroups);
     if (groups_wanted < 1) groups_wanted = cap_e / n_slices > 0 ? cap_e / n_slices : 1;
-    for (int64_t t0 = 0; t0 < n_all; t0 += batch_tiles) {
-        const int32_t nt = (int32_t)(n_all - t0 < batch_tiles ? n_all - t0 : batch_tiles);
-        std::vector<int32_t> tab;
+    // One batch of launches: tiles [t0, t0 + nt) of the call; `half` selects which half of the partial-result
+    // buffers it uses (0: the whole buffers).  Returns the launch arguments in `a` and the tables in `tab`
+    // (the caller stages them if they did not fit the kernel arguments).
+    auto build_batch = [&](int64_t t0, int32_t nt, int32_t halves, int32_t half, SegArgs &a, std::vector<int32_t> &tab) -> int32_t {
+        tab.clear();
         tab.reserve((size_t)nt * 8);
         for (int32_t i = 0; i < nt; ++i) {
             const Tile &t = tiles[t0 + i];
@@ -322,7 +350,7 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
         const size_t groups_at = tab.size();
         tab.insert(tab.end(), group_off.begin(), group_off.end());
         if ((int64_t)tab.size() > (int64_t)s->seg_cap * 3) return MLORA_E_UNSUPPORTED;
-        SegArgs a{};
+        a = SegArgs{};
         // a batch whose tables fit the kernel arguments needs no copy in front of its launches
         bool rows_fit = true;                          // a piece's row count shares a word with its slot
         for (int32_t j = 0; j < n_ranges; ++j) rows_fit = rows_fit && tab[4 * (nt + j) + 2] <= 0xffff;
@@ -339,9 +367,6 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
                 o[0] = (uint32_t)r[1]; o[1] = (uint32_t)r[0] | (uint32_t)r[2] << 16; o[2] = (uint32_t)r[3];
             }
             for (int32_t g = 0; g <= n_groups; ++g) a.inl[2 * nt + 3 * n_ranges + g] = (uint32_t)group_off[g];
-        } else {
-            int32_t rc = stage_table(s, tab, st);
-            if (rc) return rc;
         }
         a.x = (const uint16_t *)x; a.ldx = ldx; a.y = (uint16_t *)y; a.ldy = ldy;
         a.a_tab = s->a_tab; a.b_tab = s->b_tab; a.meta.rank = s->rank; a.meta.scale = s->scale;
@@ -349,9 +374,13 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
         a.ranges = s->seg_dev + (int64_t)nt * 4; a.n_ranges = n_ranges;
         a.groups = s->seg_dev + (int64_t)groups_at; a.n_groups = n_groups;
         a.d_in = d_in; a.d_out = d_out;
+        const int32_t hp_blocks = kSegHpBlocks / halves;
         a.hcount = (int32_t *)((char *)s->xch + kXchBytes);
         a.hfin = (uint16_t *)((char *)a.hcount + kSegCountBytes);
         a.hpart = (float *)((char *)a.hfin + (size_t)kSegMaxTiles * 16384);
+        a.hcount += (size_t)half * (kSegCountBytes / 4 / halves);
+        a.hfin += (size_t)half * (kSegMaxTiles / halves) * 8192;
+        a.hpart += (size_t)half * hp_blocks * 4096;
         a.upt = upt; a.n_slices = n_slices;
         int64_t swg = (int64_t)nt * upt / 3;               // every workgroup keeps three units in flight
         const int tuned = tuning(kSegShrinkWgs);
@@ -362,9 +391,44 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
         int64_t fit = cap;
         if (nt > 0 && cap / nt >= 2 && (int64_t)(cap / nt) * nt * 4 >= (int64_t)cap * 3) fit = (int64_t)(cap / nt) * nt;
         if (swg > (tuned > 0 ? tuned : fit)) swg = tuned > 0 ? tuned : fit;
-        if (swg > kSegHpBlocks - nt) swg = kSegHpBlocks - nt;     // one partial block per (workgroup, tile) piece
+        if (swg > hp_blocks - nt) swg = hp_blocks - nt;           // one partial block per (workgroup, tile) piece
         a.n_swg = (int32_t)(swg < 1 ? 1 : swg);
-        if (!ok(launch_seg_mfma(a, st))) return MLORA_E_HIP;
+        return MLORA_OK;
+    };
+    SegArgs a;
+    std::vector<int32_t> tab;
+    // Several batches in flight: the shrinks run on a second stream, one batch ahead of the expands
+    // (two halves of the partial-result buffers in turn), so that one batch's hand-over -- the end of
+    // its shrink, the start of its expand -- overlaps the neighbouring batches' streams.  Only for
+    // batches whose tables travel in the kernel arguments.
+    const int32_t n_sub = tuning(kSegOverlap);
+    if (n_sub >= 2 && n_all >= 2 * n_sub) {
+        int64_t sub_tiles = (n_all + n_sub - 1) / n_sub;
+        if (sub_tiles > kSegMaxTiles / 2) sub_tiles = kSegMaxTiles / 2;
+        if (sub_tiles > kSegHpBlocks / 2 - cap) sub_tiles = kSegHpBlocks / 2 - cap;
+        if (sub_tiles >= 1) {
+            std::vector<SegArgs> subs;
+            bool all_inline = true;
+            int32_t i = 0;
+            for (int64_t t0 = 0; t0 < n_all && all_inline; t0 += sub_tiles, ++i) {
+                const int32_t nt = (int32_t)(n_all - t0 < sub_tiles ? n_all - t0 : sub_tiles);
+                int32_t rc = build_batch(t0, nt, 2, i & 1, a, tab);
+                if (rc) return rc;
+                all_inline = a.inl_on != 0;
+                subs.push_back(a);
+            }
+            if (all_inline) return launch_seg_overlapped(s, subs, st);
+        }
+    }
+    for (int64_t t0 = 0; t0 < n_all; t0 += batch_tiles) {
+        const int32_t nt = (int32_t)(n_all - t0 < batch_tiles ? n_all - t0 : batch_tiles);
+        int32_t rc = build_batch(t0, nt, 1, 0, a, tab);
+        if (rc) return rc;
+        if (!a.inl_on) {
+            rc = stage_table(s, tab, st);
+            if (rc) return rc;
+        }
+        if (!ok(launch_seg_shrink(a, st)) || !ok(launch_seg_expand(a, st))) return MLORA_E_HIP;
     }
     return MLORA_OK;
 }
@@ -481,6 +545,11 @@ void mlora_site_destroy(mlora_site *s)
             (void)hipEventDestroy(s->stage_ev[k]);
             (void)hipHostFree(s->stage[k]);
         }
+    if (s->seg_side) {
+        (void)hipStreamSynchronize(s->seg_side);
+        for (int k = 0; k < 5; ++k) if (s->seg_ev[k]) (void)hipEventDestroy(s->seg_ev[k]);
+        (void)hipStreamDestroy(s->seg_side);
+    }
     if (s->pack) {
         if (s->pack_busy) (void)hipEventSynchronize(s->pack_ev);
         (void)hipEventDestroy(s->pack_ev);

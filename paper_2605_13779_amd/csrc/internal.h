@@ -170,7 +170,8 @@ struct SegArgs {
     int32_t inl_on;
     uint32_t inl[kSegInline];
 };
-hipError_t launch_seg_mfma(const SegArgs &a, hipStream_t st);
+hipError_t launch_seg_shrink(const SegArgs &a, hipStream_t st);
+hipError_t launch_seg_expand(const SegArgs &a, hipStream_t st);
 int seg_unit();
 int seg_shrink_capacity();
 int seg_expand_capacity();
@@ -179,7 +180,7 @@ int seg_expand_capacity();
 // tests set them; the launch code reads each knob it needs once per call.
 enum Knob {
     kRowsPollLimit, kRowsRankBound, kRowsItemsTarget, kRowsMode, kRowsWaves, kRowsPrefetch, kPlanGeneral, kPlanSeparate,
-    kPlanPipeline, kSegExpandGroups, kSegTableCopy, kSegShrinkWgs, kSegNoMfma, kSegFused, kUploadPieceKb, kDownRowsShrink,
+    kPlanPipeline, kSegExpandGroups, kSegTableCopy, kSegShrinkWgs, kSegNoMfma, kSegOverlap, kUploadPieceKb, kDownRowsShrink,
     kKnobCount
 };
 int tuning(Knob k);             // api.hip

@@ -457,14 +457,18 @@ int seg_expand_capacity()
     return cap;
 }
 
-hipError_t launch_seg_mfma(const SegArgs &a, hipStream_t st)
+hipError_t launch_seg_shrink(const SegArgs &a, hipStream_t st)
 {
     if (a.n_tiles <= 0 || a.n_ranges <= 0 || a.n_groups <= 0) return hipSuccess;
     if (a.n_swg < 1 || a.upt != (a.d_in + KU - 1) / KU) return hipErrorInvalidValue;
     const unsigned gs = (unsigned)((a.n_swg + 7) / 8 * 8);
     seg_shrink_kernel<<<dim3(gs), dim3(NT), 0, st>>>(a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_seg_expand(const SegArgs &a, hipStream_t st)
+{
+    if (a.n_tiles <= 0 || a.n_ranges <= 0 || a.n_groups <= 0) return hipSuccess;
     const unsigned ge = (unsigned)(((int64_t)a.n_groups * a.n_slices + 7) / 8 * 8);
     seg_expand_kernel<<<dim3(ge), dim3(NT), 0, st>>>(a);
     return hipGetLastError();

@@ -274,9 +274,11 @@ def test_decode_parts_when_partners_never_answer(M, oracle):
         P.check_close(b, ref, c.name + (" (grouped)" if k >= len(cases) else ""))
         P.check_untouched(b, c.y0, c.token_slot < 0, c.name)
         # (an item on its own adds the k-slices of d_in in one sweep instead of slice by slice: the two
-        # results may differ in the last bit of an output, never by more)
-        wa, wb = P.widen(a), P.widen(b)
-        assert np.all(np.abs(wa - wb) <= 2.0 ** -7 * np.maximum(np.abs(wa), np.abs(wb))), c.name
+        # fp32 sums differ by a few units of their last place, so the outputs may differ in their last
+        # bit -- or, where y0 and the delta cancel, by that much of the magnitude that cancelled)
+        wa, wb, w0 = P.widen(a), P.widen(b), P.widen(c.y0)
+        bad = np.argwhere(np.abs(wa - wb) > 2.0 ** -7 * np.maximum(np.abs(wa), np.abs(wb)) + 2.0 ** -16 * np.abs(w0))
+        assert len(bad) == 0, (c.name, len(bad), [(tuple(i), float(wa[tuple(i)]), float(wb[tuple(i)])) for i in bad[:5]])
     for site in sites:
         site.check()
 
@@ -605,6 +607,29 @@ def test_segmented_many_tiles_in_batches(M, oracle):
                    seg_off=seg_off, seg_slot=seg_slot, std_a=0.05, std_b=0.05)
     site = dense_site(M, c)
     check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0))
+
+
+@pytest.mark.parametrize("n_sub", [2, 3])
+def test_segmented_batches_in_flight(M, oracle, n_sub):
+    """The rank-64 prefill with several batches in flight (shrinks on the site's second stream, one
+    batch ahead of the expands, the partial-result buffers used in halves): the same rows against
+    the oracle, twice in a row on one site (the buffers and events are used again), and the same
+    bits both times."""
+    g = W.rng(52)
+    lens = [1500] + g.integers(1, 110, size=200).tolist()
+    T = int(sum(lens))
+    seg_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    seg_slot = g.integers(-1, 6, size=len(lens)).astype(np.int32)
+    c = W.seg_case("seg_in_flight", 4200 + n_sub, T, len(lens), 272, 136, 6, 64, 128.0, ranks=[64, 64, 0, 48, 64, 17],
+                   seg_off=seg_off, seg_slot=seg_slot, std_a=0.05, std_b=0.05)
+    site = dense_site(M, c)
+    M.set_tuning("seg_overlap", n_sub)
+    try:
+        check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0))
+        a = run_seg(M, site, c, c.y0)
+        assert np.array_equal(a, run_seg(M, site, c, c.y0))
+    finally:
+        M.set_tuning("seg_overlap", 0)
 
 
 @pytest.mark.parametrize("seed", [1, 2])
