@@ -212,8 +212,10 @@ typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 // error flag raised when a bounded wait gives up.
 constexpr int kSpinLimit = 1 << 18;
 constexpr uint32_t kTagPoison = 0xffffffffu;   // exchange switched off after a bounded wait gave up (see tag_advance)
-constexpr int kPollLimit = 4096;  // polls of an exchange word before a reader computes the value itself (a partner can start late,
-                                  // e.g. when its part of the chip comes out of an idle state; results do not depend on the outcome)
+// Polls of an exchange word before a reader computes the value itself (a partner can start late).
+// The two ways of getting the value add the same terms in a different order, so an output can differ
+// by one rounding step between them; both are within the tolerance of the result.
+constexpr int kPollLimit = 4096;
 
 __device__ __forceinline__ void xch_put(uint64_t *p, float v, uint32_t tag)
 {
