@@ -920,11 +920,13 @@ def check_moe_down(M, oracle, c, site, tokens=None, report=None):
 
 
 @pytest.mark.parametrize("T,K,E,S,r", [(37, 2, 4, 3, 8), (200, 4, 16, 5, 4), (64, 8, 8, 2, 16), (9, 1, 1, 2, 2), (50, 3, 6, 4, 1),
-                                       (300, 2, 5, 2, 8), (70, 2, 4, 2, 32), (40, 2, 3, 2, 64), (260, 4, 40, 2, 16)])
+                                       (300, 2, 5, 2, 8), (70, 2, 4, 2, 32), (40, 2, 3, 2, 64), (260, 4, 40, 2, 16),
+                                       (300, 2, 4, 70, 8), (64, 4, 300, 2, 8), (33, 16, 520, 1, 4)])
 def test_moe_down_small(M, oracle, T, K, E, S, r):
     """Down projection with the routing-weight combine: ragged widths, tokens without adapter, an
-    empty slot, K from 1 to 8, every padded rank, odd expert counts (a half-filled last contraction
-    step), slots with more tokens than one tile holds, several chunks of the contraction axis."""
+    empty slot, K from 1 to 16, every padded rank, odd expert counts (a half-filled last contraction
+    step), slots with more tokens than one tile holds, several chunks of the contraction axis, more
+    slots than a wave has lanes, expert counts whose tables take most of a compute unit's LDS."""
     ranks = [r] * S
     if S > 2:
         ranks[1] = 0
