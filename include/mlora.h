@@ -212,6 +212,8 @@ int32_t moe_lora_apply_multi(mlora_site *const *sites, int32_t n_sites, const ml
  * of row t, Bcat_s is the slot's per-expert B tensors stacked along the contraction axis, as the
  * packed tables store them.  Pairs that the plan left out (expert ids outside [0, n_experts), slots
  * not ready when the plan was built) add nothing, whatever the workspace holds.
+ * A token's K expert ids must be distinct (as a top-k routing gives them): of two pairs of one token
+ * on the same expert only one would be added.
  * Limits: K <= 16, and 32 * (n_experts + 4 * K * max(r_pad, 8)) bytes of tables must fit the LDS
  * of a compute unit (n_experts = 1024 at rank 8 and K = 8 does; MLORA_E_UNSUPPORTED otherwise).
  * Errors: as moe_lora_apply_planned; MLORA_E_INVALID on null pointers. */
