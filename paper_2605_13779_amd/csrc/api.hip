@@ -1151,15 +1151,24 @@ int32_t lora_apply_segmented(mlora_site *s, const void *x, int64_t ldx, void *y,
             for (int32_t c = 0; c < kChunk; ++c) tab.push_back(r0 + (c < n ? c : n - 1));
         }
     }
-    const int32_t n_units = (int32_t)(tab.size() / kRec);
+    const int64_t n_units = (int64_t)(tab.size() / kRec);
     if (n_units == 0) return MLORA_OK;
-    if ((int64_t)(n_units + 1) * kRec > (int64_t)s->seg_cap * 3) return MLORA_E_UNSUPPORTED;
-    rc = stage_table(s, tab, st);
-    if (rc) return rc;
-    RowsArgs a = rows_args(s, x, ldx, y, ldy);
-    a.chunks = s->seg_dev;
-    a.grid_chunks = n_units;
-    return ok(launch_rows(a, st)) ? MLORA_OK : MLORA_E_HIP;
+    // the records go to the site's device area in batches that fit it (one copy + one launch each; the
+    // stream orders a batch's copy behind the launch that read the batch before it)
+    const int64_t per_batch = (int64_t)s->seg_cap * 3 / kRec - 1;
+    if (per_batch < 1) return MLORA_E_UNSUPPORTED;
+    std::vector<int32_t> piece;
+    for (int64_t u0 = 0; u0 < n_units; u0 += per_batch) {
+        const int64_t n = n_units - u0 < per_batch ? n_units - u0 : per_batch;
+        if (n < n_units) piece.assign(tab.begin() + u0 * kRec, tab.begin() + (u0 + n) * kRec);
+        rc = stage_table(s, n < n_units ? piece : tab, st);
+        if (rc) return rc;
+        RowsArgs a = rows_args(s, x, ldx, y, ldy);
+        a.chunks = s->seg_dev;
+        a.grid_chunks = (int32_t)n;
+        if (!ok(launch_rows(a, st))) return MLORA_E_HIP;
+    }
+    return MLORA_OK;
 }
 
 int32_t moe_lora_apply_packed(mlora_site *s, const void *x, int64_t ldx, void *y, int64_t ldy,

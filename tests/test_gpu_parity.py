@@ -666,6 +666,23 @@ def test_prefill_random_segment_structures(M, oracle, seed):
         site.close()
 
 
+def test_segmented_small_rank_beyond_one_table(M, oracle):
+    """A small-rank segmented call with more 4-row chunks than the site's table area holds (24,575 per
+    batch) goes through in several batches: long and short segments, some without adapter, every row
+    against the oracle."""
+    g = W.rng(53)
+    lens = [40000, 3, 25000, 1] + g.integers(1, 900, size=120).tolist()
+    T = int(sum(lens))                                 # about 120,000 rows, about 30,000 chunks
+    seg_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    seg_slot = g.integers(-1, 3, size=len(lens)).astype(np.int32)
+    seg_slot[0], seg_slot[2] = 0, 2
+    c = W.seg_case("seg_long", 4300, T, len(lens), 16, 24, 3, 4, 8.0, seg_off=seg_off, seg_slot=seg_slot,
+                   std_a=0.3, std_b=0.3)
+    assert (T + 3) // 4 > 24575
+    site = dense_site(M, c)
+    check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0))
+
+
 def test_segmented_rejects_bad_offsets(M):
     site = M.Site(64, 64, 64, 2)
     x = torch.zeros((10, 64), dtype=torch.bfloat16, device="cuda")
