@@ -63,7 +63,7 @@ std::atomic<int32_t> g_knob[kKnobCount];
 const char *const kKnobName[kKnobCount] = {
     "rows_poll_limit", "rows_rank_bound", "rows_items_target", "rows_mode", "rows_waves", "rows_prefetch", "plan_general",
     "plan_separate", "plan_pipeline", "seg_expand_groups", "seg_table_copy", "seg_shrink_wgs", "seg_no_mfma", "seg_overlap",
-    "upload_piece_kb", "down_rows_shrink"};
+    "upload_piece_kb"};
 
 // Host-side record of a slot's rank (the kernels read the device table; this only tells the launch
 // code whether any slot is padded, i.e. whether rank-bounded reads of A can save traffic).
@@ -970,7 +970,7 @@ int32_t moe_lora_apply_down(mlora_site *s, const mlora_plan *plan, const void *x
     d.T = T; d.K = plan->top_k; d.E = s->E; d.n_slots = plan->n_slots; d.d_out = s->d.d_out; d.r_pad = s->r_pad;
     d.x = (const uint16_t *)x; d.ldx = ldx; d.a_tab = s->a_tab; d.scale = s->scale; d.pair_w = pair_w; d.d_in = s->d.d_in;
     // first launch: per (slot, expert) group, h = w * (alpha / r) * A x for the group's pairs
-    if (moe_down_shrinks_by_group(s->r_pad) && !tuning(kDownRowsShrink)) {
+    if (moe_down_shrinks_by_group(s->r_pad)) {
         if (!ok(launch_moe_down_shrink(d, st))) return MLORA_E_HIP;
     } else {
         RowsArgs a = rows_args(s, x, ldx, y, ldy);

@@ -180,7 +180,7 @@ int seg_expand_capacity();
 // tests set them; the launch code reads each knob it needs once per call.
 enum Knob {
     kRowsPollLimit, kRowsRankBound, kRowsItemsTarget, kRowsMode, kRowsWaves, kRowsPrefetch, kPlanGeneral, kPlanSeparate,
-    kPlanPipeline, kSegExpandGroups, kSegTableCopy, kSegShrinkWgs, kSegNoMfma, kSegOverlap, kUploadPieceKb, kDownRowsShrink,
+    kPlanPipeline, kSegExpandGroups, kSegTableCopy, kSegShrinkWgs, kSegNoMfma, kSegOverlap, kUploadPieceKb,
     kKnobCount
 };
 int tuning(Knob k);             // api.hip

@@ -142,7 +142,11 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         const int jg = w % C::JG, ks = w / C::JG;
         // ---- which chunk, which part of it ----
         int chunk, kslice = 0, out0 = 0, out1 = a.d_out;
-        bool do_shrink = true, do_expand = a.h_out == nullptr;      // (h_out: the first launch of the MoE down projection only shrinks)
+        // The first launch of the MoE down projection only shrinks (a.h_out); it comes here for padded ranks
+        // above 16 only, so the kernels of the smaller ranks do not carry that mode.
+        constexpr bool HMODE = RP >= 32 && !XCH && !RI;
+        const bool h_only = HMODE && a.h_out != nullptr;
+        bool do_shrink = true, do_expand = !h_only;
         int part_i = 0;
         if (a.tile_par > 1) {
             // workgroups are dealt round-robin to the 8 XCDs: keep the parts of one chunk (they share
@@ -152,7 +156,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
             part_i = idx - grp8 * a.tile_par;
             chunk = grp8 * 8 + (item & 7);
             out0 = part_i * a.out_per_part; out1 = min(a.d_out, out0 + a.out_per_part);
-            do_expand = out0 < out1 && a.h_out == nullptr;
+            do_expand = out0 < out1 && !h_only;
             if (chunk >= a.grid_chunks) continue;
         } else {
             // neighbouring chunks can belong to one adapter (and expert): keep them on one XCD, where
@@ -225,13 +229,12 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         const uint16_t *Bg = a.b_tab + (int64_t)key * a.d_out * RP;
         // MoE down projection, first launch: no expand here; the chunk's scaled h, times the row's
         // routing weight, goes to a.h_out (the weights travel with the flight)
-        const bool h_only = a.h_out != nullptr;
         uint16_t *yrow[kChunk];
         float wrow[kChunk];
 #pragma unroll
         for (int c = 0; c < kChunk; ++c) {
             yrow[c] = a.y + (int64_t)row[c] * a.ldy;
-            wrow[c] = h_only ? a.row_w[row[c] + lane_zero] : 1.f;
+            if constexpr (HMODE) wrow[c] = h_only ? a.row_w[row[c] + lane_zero] : 1.f;
         }
         // Matrix-core expand: the result comes out with lane l holding row l%4 of the chunk and the four
         // outputs of its block (see below), so a lane reads and writes 8 contiguous bytes of its own row:
@@ -379,7 +382,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         const bool h_thread = tid < kChunk * RP && hc < cnt;
         if (!xitem) {
             if (tid < kChunk * RP) hs[hc][hj] = own * scale;
-            if (h_only) {
+            if constexpr (HMODE) if (h_only) {
                 // weighted, scaled h of row hc as a bf16 head (truncated) and tail (rounded) in one word:
                 // 16 bits of it reach the matrix cores of the second launch; rows of an empty slot are skipped there too
                 if (h_thread && rank > 0) {

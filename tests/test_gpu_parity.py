@@ -999,18 +999,6 @@ def test_moe_down_pairs_the_plan_left_out(M, oracle):
     assert not np.array_equal(got[slots2 >= 0], c.y0[slots2 >= 0])
 
 
-def test_moe_down_shrink_through_the_chunk_kernels(M, oracle):
-    """Ranks above 16 take the first launch through the chunk kernels; the switch sends a rank-8 site
-    the same way, and the result must meet the oracle like the wave-per-group launch does."""
-    c = W.moe_down_case("down_rows_shrink", 5397, 120, 4, 16, 136, 200, 3, 8, 16.0, std_a=0.05, std_b=0.05)
-    site = moe_site(M, c)
-    M.set_tuning("down_rows_shrink", 1)
-    try:
-        check_moe_down(M, oracle, c, site)
-    finally:
-        M.set_tuning("down_rows_shrink", 0)
-
-
 def test_moe_down_limits(M, oracle):
     """Sixteen experts per token is the most the down projection takes; more is refused before any launch."""
     c = W.moe_down_case("down_k16", 5395, 40, 16, 32, 72, 136, 3, 4, 8.0, std_a=0.05, std_b=0.05)
