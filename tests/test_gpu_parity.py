@@ -999,6 +999,51 @@ def test_moe_down_pairs_the_plan_left_out(M, oracle):
     assert not np.array_equal(got[slots2 >= 0], c.y0[slots2 >= 0])
 
 
+@pytest.mark.parametrize("seed", [1, 2])
+def test_moe_down_random_routing(M, oracle, seed):
+    """Down projection over seeded draws of token count, expert count (up to 200), top-k (up to 16), slot
+    count (up to 40, so that many slots hold no or one token), rank, widths; tokens without a slot,
+    empty slots, and masked routing entries (ids of -1 and ids past the last expert), which must add
+    nothing.  Every token goes to the oracle."""
+    rng = np.random.default_rng(8800 + seed)
+    for it in range(10):
+        T, E = int(rng.integers(1, 400)), int(rng.choice([1, 2, 3, 5, 8, 16, 33, 64, 128, 200]))
+        K = int(rng.integers(1, min(E, 16) + 1))
+        S = int(rng.choice([1, 2, 3, 7, 40]))
+        r_max = int(rng.choice([1, 2, 4, 5, 8, 16, 24, 32, 64]))
+        ranks = [int(rng.integers(0, r_max + 1)) for _ in range(S)]
+        ranks[int(rng.integers(0, S))] = r_max
+        d_in, d_out = int(rng.integers(1, 30)) * 8, int(rng.integers(1, 60)) * 8
+        print(f"down_rand{seed}_{it}: T {T} K {K} E {E} S {S} r_max {r_max} ranks {ranks[:8]} d_in {d_in} d_out {d_out}", flush=True)
+        c = W.moe_down_case(f"down_rand{seed}_{it}", 8850 + 16 * seed + it, T, K, E, d_in, d_out, S, r_max,
+                            (rng.random(S) * 30 + 1).round(2), ranks=ranks, std_a=0.05, std_b=0.05)
+        c.token_slot[::6] = -1
+        site = moe_site(M, c)
+        if it % 2 == 0:
+            check_moe_down(M, oracle, c, site)
+            continue
+        # masked routing entries: dropped by the plan; the oracle gets them as weight 0 on expert 0
+        masked = c.topk.copy()
+        masked[rng.random(masked.shape) < 0.15] = -1
+        masked[rng.random(masked.shape) < 0.05] = E + int(rng.integers(0, 3))
+        dropped = (masked < 0) | (masked >= E)
+        ref = oracle.apply_moe_down(c.x, c.y0, c.A, c.B, c.rank, c.alpha, np.where(dropped, 0, masked).astype(np.int32),
+                                    np.where(dropped, 0.0, c.w).astype(np.float32), c.token_slot)
+        x, y = P.dev_bf16(c.x), P.dev_bf16(c.y0)
+        ts = torch.from_numpy(c.token_slot).cuda()
+        plan = M.Plan(c.T * c.K, c.n_slots * c.E)
+        M.moe_plan_route(plan, torch.from_numpy(masked).cuda(), ts, c.n_slots, c.E, ready_from=site)
+        ws = torch.empty(M.moe_down_workspace_bytes(c.T, c.K, c.d_out), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)
+        M.moe_lora_apply_down(site, plan, x, torch.from_numpy(c.w).cuda(), ts, ws, y)
+        torch.cuda.synchronize()
+        got = P.host_bits(y)
+        P.check_close(got, ref, c.name)
+        eff = np.array([s_ >= 0 and c.rank[s_] > 0 for s_ in c.token_slot])
+        P.check_untouched(got, c.y0, ~eff, c.name)
+        site.close()
+
+
 def test_moe_down_limits(M, oracle):
     """Sixteen experts per token is the most the down projection takes; more is refused before any launch."""
     c = W.moe_down_case("down_k16", 5395, 40, 16, 32, 72, 136, 3, 4, 8.0, std_a=0.05, std_b=0.05)
