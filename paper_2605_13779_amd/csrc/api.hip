@@ -61,7 +61,7 @@ constexpr int32_t kSegHpBlocks = (int32_t)((kSegXchBytes - kXchBytes - kSegCount
 
 std::atomic<int32_t> g_knob[kKnobCount];
 const char *const kKnobName[kKnobCount] = {
-    "rows_poll_limit", "rows_rank_bound", "rows_items_target", "rows_mode", "rows_waves", "rows_prefetch", "plan_general",
+    "rows_poll_limit", "rows_rank_bound", "rows_items_target", "rows_mode", "rows_waves", "plan_general",
     "plan_separate", "plan_pipeline", "seg_expand_groups", "seg_table_copy", "seg_shrink_wgs", "seg_no_mfma", "seg_overlap",
     "upload_piece_kb"};
 

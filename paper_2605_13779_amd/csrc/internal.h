@@ -179,7 +179,7 @@ int seg_expand_capacity();
 // Launch-shape overrides (mlora_set_tuning): one relaxed atomic per knob, 0 = automatic.  Sweeps and
 // tests set them; the launch code reads each knob it needs once per call.
 enum Knob {
-    kRowsPollLimit, kRowsRankBound, kRowsItemsTarget, kRowsMode, kRowsWaves, kRowsPrefetch, kPlanGeneral, kPlanSeparate,
+    kRowsPollLimit, kRowsRankBound, kRowsItemsTarget, kRowsMode, kRowsWaves, kPlanGeneral, kPlanSeparate,
     kPlanPipeline, kSegExpandGroups, kSegTableCopy, kSegShrinkWgs, kSegNoMfma, kSegOverlap, kUploadPieceKb,
     kKnobCount
 };
