@@ -63,7 +63,7 @@ std::atomic<int32_t> g_knob[kKnobCount];
 const char *const kKnobName[kKnobCount] = {
     "rows_poll_limit", "rows_rank_bound", "rows_items_target", "rows_mode", "rows_waves", "plan_general",
     "plan_separate", "plan_pipeline", "seg_expand_groups", "seg_table_copy", "seg_shrink_wgs", "seg_no_mfma", "seg_overlap",
-    "upload_piece_kb"};
+    "upload_piece_kb", "seg_fused"};
 
 // Host-side record of a slot's rank (the kernels read the device table; this only tells the launch
 // code whether any slot is padded, i.e. whether rank-bounded reads of A can save traffic).
@@ -248,6 +248,14 @@ int32_t stage_table(mlora_site *s, const std::vector<int32_t> &tab, hipStream_t 
     return MLORA_OK;
 }
 
+// The last quarter of the tile-counter block holds what the one-launch form of the prefill needs: 128
+// words of control (epoch, error word, sign-in counters), then one flag per tile of a batch.
+uint32_t *seg_ctrl_of(const mlora_site *s)
+{
+    return (uint32_t *)((char *)s->xch + kXchBytes) + (kSegCountBytes / 4 - 1024 - 128);
+}
+static_assert(kSegMaxTiles <= 1024 && kSegMaxTiles * 4 + (1024 + 128) * 4 <= (int)kSegCountBytes, "counters, control words and flags share the block");
+
 // Batches of the rank-64 prefill with their shrinks on the site's second stream, one batch ahead of the
 // expands on the caller's stream.  Batch i uses half i % 2 of the partial-result buffers, so shrink
 // i + 2 waits for expand i.  The second stream forks from the caller's stream and is joined back into it
@@ -378,6 +386,8 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
         a.hcount = (int32_t *)((char *)s->xch + kXchBytes);
         a.hfin = (uint16_t *)((char *)a.hcount + kSegCountBytes);
         a.hpart = (float *)((char *)a.hfin + (size_t)kSegMaxTiles * 16384);
+        a.hctrl = seg_ctrl_of(s);                      // (one-launch form: epoch, error word, sign-ins; then a flag per tile)
+        a.hflag = a.hctrl + 128;
         a.hcount += (size_t)half * (kSegCountBytes / 4 / halves);
         a.hfin += (size_t)half * (kSegMaxTiles / halves) * 8192;
         a.hpart += (size_t)half * hp_blocks * 4096;
@@ -428,7 +438,10 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
             rc = stage_table(s, tab, st);
             if (rc) return rc;
         }
-        if (!ok(launch_seg_shrink(a, st)) || !ok(launch_seg_expand(a, st))) return MLORA_E_HIP;
+        // "seg_fused": both halves in one launch (the expand's workgroups wait for the flags of their tiles)
+        if (tuning(kSegFused) && (a.n_swg + 7) / 8 * 8 <= seg_fused_capacity()) {
+            if (!ok(launch_seg_fused(a, st))) return MLORA_E_HIP;
+        } else if (!ok(launch_seg_shrink(a, st)) || !ok(launch_seg_expand(a, st))) return MLORA_E_HIP;
     }
     return MLORA_OK;
 }
@@ -530,6 +543,7 @@ int32_t mlora_site_create(const mlora_site_desc *d, void *a_tab, void *b_tab, vo
     if (ok(e) && s->ctrl) {
         e = launch_fill_i32((int32_t *)s->ctrl, 0, (int64_t)((kCtrlBytes + (s->r_pad == 64 ? kSegXchBytes : kXchBytes)) / 4), 0);   // tag 0 = never written
         if (ok(e)) e = launch_fill_i32((int32_t *)s->ctrl, 1, 1, 0);                               // first launch tag
+        if (ok(e) && s->r_pad == 64) e = launch_fill_i32((int32_t *)seg_ctrl_of(s), 1, 1, 0);      // ... and the prefill's first epoch
     }
     if (!ok(e) || !ok(hipGetLastError()) || !ok(hipStreamSynchronize(0))) { delete s; return MLORA_E_HIP; }
     *out = s;
@@ -708,6 +722,15 @@ int32_t mlora_site_check(mlora_site *s, void *stream)
         (void)launch_fill_i32((int32_t *)s->ctrl, 0, (int64_t)(kCtrlBytes / 4), (hipStream_t)stream);
         (void)launch_fill_i32((int32_t *)s->ctrl, 1, 1, (hipStream_t)stream);
         return MLORA_E_HIP;
+    }
+    if (s->r_pad == 64 && s->xch) {
+        // the one-launch prefill keeps its own control words (a wait for a tile's flag that gave up)
+        uint32_t *sc = seg_ctrl_of(s);
+        if (!ok(hipMemcpy(&flag, sc + 1, sizeof flag, hipMemcpyDeviceToHost))) return MLORA_E_HIP;
+        if (flag) {
+            (void)launch_fill_i32((int32_t *)sc + 1, 0, 127, (hipStream_t)stream);   // error word and sign-ins; the epoch goes on
+            return MLORA_E_HIP;
+        }
     }
     return MLORA_OK;
 }

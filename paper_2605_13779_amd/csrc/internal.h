@@ -160,6 +160,8 @@ struct SegArgs {
     float *hpart;            // [n_swg + n_tiles][64 rows][64] fp32 partial shrink results, one block per (workgroup, tile) piece
     uint16_t *hfin;          // [n_tiles][64 rows][64 bf16 heads | 64 bf16 tails] scaled shrink result
     int32_t *hcount;         // [n_tiles] pieces that have arrived; zero between launches
+    uint32_t *hctrl;         // one-launch form: [0] epoch, [1] error word, [8..72) sign-ins
+    uint32_t *hflag;         // one-launch form: [n_tiles] epoch of the launch that completed the tile's h
     int32_t upt;             // units of d_in per tile (a unit is seg_unit() elements)
     int32_t n_swg;           // workgroups of the shrink launch; n_swg * 3 <= n_tiles * upt
     int32_t n_slices;        // output slices of 512
@@ -172,6 +174,8 @@ struct SegArgs {
 };
 hipError_t launch_seg_shrink(const SegArgs &a, hipStream_t st);
 hipError_t launch_seg_expand(const SegArgs &a, hipStream_t st);
+hipError_t launch_seg_fused(const SegArgs &a, hipStream_t st);
+int seg_fused_capacity();
 int seg_unit();
 int seg_shrink_capacity();
 int seg_expand_capacity();
@@ -180,7 +184,7 @@ int seg_expand_capacity();
 // tests set them; the launch code reads each knob it needs once per call.
 enum Knob {
     kRowsPollLimit, kRowsRankBound, kRowsItemsTarget, kRowsMode, kRowsWaves, kPlanGeneral, kPlanSeparate,
-    kPlanPipeline, kSegExpandGroups, kSegTableCopy, kSegShrinkWgs, kSegNoMfma, kSegOverlap, kUploadPieceKb,
+    kPlanPipeline, kSegExpandGroups, kSegTableCopy, kSegShrinkWgs, kSegNoMfma, kSegOverlap, kUploadPieceKb, kSegFused,
     kKnobCount
 };
 int tuning(Knob k);             // api.hip

@@ -22,7 +22,8 @@
 //           16-byte pieces.
 //
 // The stream order between the two launches is the only dependency between workgroups that anyone
-// waits for.  What the tiling buys: per 64 rows the shrink pulls one copy of the adapter's A rows
+// waits for.  (A one-launch form of the same two bodies exists behind a switch: seg_fused_kernel, where
+// the expand's workgroups wait for per-tile flags instead.)  What the tiling buys: per 64 rows the shrink pulls one copy of the adapter's A rows
 // through the CU's L1, and the expand pulls B_s once per run instead of once per 32 rows; with
 // 32-row tiles that re-read both, adapter bytes were more than half of all L1 traffic.
 #include "internal.h"
@@ -42,7 +43,12 @@ constexpr int kWaitVm0 = 0x0F70; // s_waitcnt vmcnt(0) with the other counters l
 constexpr int ES = 512;           // outputs per expand slice (64 per wave)
 constexpr int H_LD = 72;          // padded row stride of the bf16 h tiles, in elements
 constexpr int ST_LD = 68;         // padded row stride of a wave's 16 x 64 staging tile, in floats
+constexpr int SHRINK_LDS = 2 * STAGE_BYTES;                          // two stage buffers, used in turn
+constexpr int EXPAND_H_BYTES = 2 * 2 * 32 * H_LD * 2;                // two buffers of bf16 heads and tails of a 32-row block
+constexpr int EXPAND_LDS = EXPAND_H_BYTES + NW * 16 * ST_LD * 4;    // ... and a staging tile per wave
+constexpr int kFlagSpin = 1 << 20;                                  // polls of a tile's flag (one launch: never reached)
 static_assert(RED_BYTES <= STAGE_BYTES, "partials reuse the staging area");
+static_assert(sizeof(SegArgs) + 8 <= 4096, "kernel arguments (with the one-launch form's block count) stay within 4 KB");
 }
 
 __device__ __forceinline__ f32x16_t mfma32(const uint4 &a, const uint4 &b, f32x16_t c)
@@ -94,10 +100,9 @@ __device__ __forceinline__ int seg_group_off(const SegArgs &a, int g)
 
 // Workgroups are dealt round-robin to the 8 XCDs; work ids are laid out so that an XCD gets a
 // contiguous range of them (neighbouring ids share adapter bytes, which then sit in that XCD's L2).
-__device__ __forceinline__ int xcd_contiguous_id()
+__device__ __forceinline__ int xcd_contiguous_id(int block, int n_blocks)
 {
-    const int per_xcd = (int)gridDim.x >> 3;
-    return ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    return (block & 7) * (n_blocks >> 3) + (block >> 3);
 }
 
 // Shrink.  The work is the list of all (tile, k-unit) pairs, tile-major (a k-unit is KU elements of
@@ -120,13 +125,13 @@ struct ShrinkShare {
     __device__ int owner(int64_t u) const { return (int)(((u + 1) * n + U - 1) / U) - 1; }
 };
 
-__global__ __launch_bounds__(NT, 4)
-void seg_shrink_kernel(const SegArgs a)
+// FUSED: the expand runs in the same launch, on other XCDs too, so h is written with device-scope stores
+// and each tile's flag is set to the launch's epoch once its h is complete.
+template <bool FUSED>
+__device__ __forceinline__ void seg_shrink_body(const SegArgs &a, const int b, unsigned char *buf2, const uint32_t epoch)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char buf2[2 * STAGE_BYTES];   // two stage buffers, used in turn
     __shared__ int s_last;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, kh = lane >> 5;
-    const int b = xcd_contiguous_id();
     if (b >= a.n_swg) return;
     const ShrinkShare sh{(int64_t)a.n_tiles * a.upt, a.n_swg};
     const int64_t u0 = (int64_t)b * sh.U / sh.n, u1 = (int64_t)(b + 1) * sh.U / sh.n;
@@ -244,8 +249,24 @@ void seg_shrink_kernel(const SegArgs a)
                     hi[k] = f2bf(f[k]);
                     lo[k] = f2bf(f[k] - __uint_as_float(hi[k] << 16));
                 }
-                *(uint2 *)(hf + row * 128 + c4 * 4) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
-                *(uint2 *)(hf + row * 128 + 64 + c4 * 4) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+                const uint64_t hw = (uint64_t)(hi[2] | (hi[3] << 16)) << 32 | (hi[0] | (hi[1] << 16));
+                const uint64_t lw = (uint64_t)(lo[2] | (lo[3] << 16)) << 32 | (lo[0] | (lo[1] << 16));
+                if constexpr (FUSED) {
+                    __hip_atomic_store((uint64_t *)(hf + row * 128 + c4 * 4), hw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store((uint64_t *)(hf + row * 128 + 64 + c4 * 4), lw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    *(uint64_t *)(hf + row * 128 + c4 * 4) = hw;
+                    *(uint64_t *)(hf + row * 128 + 64 + c4 * 4) = lw;
+                }
+            }
+        }
+        if constexpr (FUSED) {
+            // the tile's h has been acknowledged at device scope before its flag shows the epoch
+            // (tiles without adapter get their flag too: nobody reads their h, but nobody waits in vain)
+            if (last) {
+                __builtin_amdgcn_s_waitcnt(kWaitVm0);
+                __syncthreads();
+                if (tid == 0) __hip_atomic_store(a.hflag + c_tile, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         // Every path through here ends with nothing in flight, and the compiler is told so (a wait it
@@ -296,16 +317,25 @@ void seg_shrink_kernel(const SegArgs a)
     if (rest > 1) consume(s1);
 }
 
+__global__ __launch_bounds__(NT, 4)
+void seg_shrink_kernel(const SegArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds[SHRINK_LDS];
+    seg_shrink_body<false>(a, xcd_contiguous_id((int)blockIdx.x, (int)gridDim.x), lds, 0u);
+}
+
 // Loads are issued unconditionally (clamped addresses): the compiler can wait for one load while
 // younger ones stay in flight only if it knows how many were issued after it; a load under a
 // run-time condition turns every later wait into a full drain.
-__global__ __launch_bounds__(NT, 4)
-void seg_expand_kernel(const SegArgs a)
+// FUSED: the shrink runs in the same launch; a piece's rows are worked on once the flags of the tiles
+// they lie in show the launch's epoch (B_s and the first y pieces are requested before the wait), and h
+// is read with device-scope loads.
+template <bool FUSED>
+__device__ __forceinline__ void seg_expand_body(const SegArgs &a, const int id, unsigned char *lds, const uint32_t epoch)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t hh[2][32 * H_LD], hl[2][32 * H_LD];
-    __shared__ __attribute__((aligned(16))) float stg_all[NW][16 * ST_LD];
+    uint16_t *const hh0 = (uint16_t *)lds, *const hl0 = hh0 + 2 * 32 * H_LD;
+    float *const stg_all0 = (float *)(lds + EXPAND_H_BYTES);
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, kh = lane >> 5;
-    const int id = xcd_contiguous_id();
     if (id >= a.n_groups * a.n_slices) return;
     // The output slices of one group of rows are neighbours (same XCD, started together): between
     // them they sweep whole rows of y, which the memory side serves better than the same slice of
@@ -334,10 +364,17 @@ void seg_expand_kernel(const SegArgs a)
     uint4 hv;
     auto h_fetch = [&](int blk) {
         const int r = min(blk * 32 + hrow, nrows - 1);
-        hv = *(const uint4 *)(hf0 + (int64_t)r * 128);
+        if constexpr (FUSED) {
+            const uint64_t *src = (const uint64_t *)(hf0 + (int64_t)r * 128);
+            const uint64_t v0 = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint64_t v1 = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            hv = make_uint4((uint32_t)v0, (uint32_t)(v0 >> 32), (uint32_t)v1, (uint32_t)(v1 >> 32));
+        } else {
+            hv = *(const uint4 *)(hf0 + (int64_t)r * 128);
+        }
     };
     auto h_store = [&](int buf_i) {
-        uint16_t *dst = hpc < 8 ? hh[buf_i] + hrow * H_LD + hpc * 8 : hl[buf_i] + hrow * H_LD + (hpc - 8) * 8;
+        uint16_t *dst = hpc < 8 ? hh0 + buf_i * (32 * H_LD) + hrow * H_LD + hpc * 8 : hl0 + buf_i * (32 * H_LD) + hrow * H_LD + (hpc - 8) * 8;
         *(uint4 *)dst = hv;
     };
 
@@ -346,7 +383,7 @@ void seg_expand_kernel(const SegArgs a)
     const int og = lane & 7, tr = lane >> 3;
     const int oc = min(o_w + og * 8, a.d_out - 8);
     const bool col_ok = o_w + og * 8 < a.d_out;
-    float *stg = stg_all[w];
+    float *stg = stg_all0 + w * (16 * ST_LD);
     uint4 yv[2][2];
     auto y_fetch = [&](int blk, auto half_c) {
         constexpr int half = decltype(half_c)::value;
@@ -371,8 +408,8 @@ void seg_expand_kernel(const SegArgs a)
             for (int cb = 0; cb < 4; ++cb) acc[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
-                const uint4 hA = *(const uint4 *)(hh[cur] + (half * 16 + mm) * H_LD + ks * 32 + kq * 8);
-                const uint4 lA = *(const uint4 *)(hl[cur] + (half * 16 + mm) * H_LD + ks * 32 + kq * 8);
+                const uint4 hA = *(const uint4 *)(hh0 + cur * (32 * H_LD) + (half * 16 + mm) * H_LD + ks * 32 + kq * 8);
+                const uint4 lA = *(const uint4 *)(hl0 + cur * (32 * H_LD) + (half * 16 + mm) * H_LD + ks * 32 + kq * 8);
 #pragma unroll
                 for (int cb = 0; cb < 4; ++cb) {
                     acc[cb] = mfma16(hA, bv[cb][ks], acc[cb]);
@@ -419,13 +456,77 @@ void seg_expand_kernel(const SegArgs a)
         row0 = rr.row0; nrows = rr.rows;
         hf0 = a.hfin + (int64_t)rr.tile0 * 128 + hpc * 8;
         const int n_blk = (nrows + 31) >> 5;
-        h_fetch(0);
-        y_fetch(0, std::integral_constant<int, 0>{});
-        y_fetch(0, std::integral_constant<int, 1>{});
+        if constexpr (FUSED) {
+            y_fetch(0, std::integral_constant<int, 0>{});
+            y_fetch(0, std::integral_constant<int, 1>{});
+            if (tid == 0) {                        // the tiles these rows lie in: h complete?
+                int spins = 0;
+                for (int ti = rr.tile0 >> 6; ti <= (rr.tile0 + nrows - 1) >> 6; ++ti)
+                    while (__hip_atomic_load(a.hflag + ti, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+                        if (++spins > kFlagSpin) { __hip_atomic_store(a.hctrl + 1, 3u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
+                        __builtin_amdgcn_s_sleep(8);
+                    }
+            }
+            __syncthreads();
+            h_fetch(0);
+        } else {
+            h_fetch(0);
+            y_fetch(0, std::integral_constant<int, 0>{});
+            y_fetch(0, std::integral_constant<int, 1>{});
+        }
         h_store(0);
         __syncthreads();
         for (int blk = 0; blk + 1 < n_blk; ++blk) block(blk, std::true_type{});
         block(n_blk - 1, std::false_type{});
+    }
+}
+
+__global__ __launch_bounds__(NT, 4)
+void seg_expand_kernel(const SegArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds[EXPAND_LDS];
+    seg_expand_body<false>(a, xcd_contiguous_id((int)blockIdx.x, (int)gridDim.x), lds, 0u);
+}
+
+// Both halves in one launch: the first n_sblocks workgroups shrink, the others expand.  All shrink
+// workgroups are resident from the start (the host keeps their number within what the GPU holds), they
+// never wait for anybody, and an expand workgroup waits only for flags that they set: nothing can
+// deadlock, and the waits are bounded all the same (on giving up a workgroup raises the site's error
+// word and goes on).  The epoch that the flags carry lives in device memory and is advanced by the
+// launch's last workgroup (as the exchange tag of the decode launches is), so that a replayed graph,
+// which repeats the kernel arguments, still gets a fresh one.
+__global__ __launch_bounds__(NT, 4)
+void seg_fused_kernel(const SegArgs a, const int n_sblocks)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds[SHRINK_LDS > EXPAND_LDS ? SHRINK_LDS : EXPAND_LDS];
+    __shared__ uint32_t s_epoch;
+    const int blk = (int)blockIdx.x, n_blk = (int)gridDim.x;
+    if (threadIdx.x == 0) {
+        const uint32_t e = tag_read(a.hctrl);
+        s_epoch = e;
+        (void)__hip_atomic_fetch_add(a.hctrl + 8 + (blk & 63), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    const uint32_t epoch = s_epoch;
+    if (blk < n_sblocks) seg_shrink_body<true>(a, xcd_contiguous_id(blk, n_sblocks), lds, epoch);
+    else seg_expand_body<true>(a, xcd_contiguous_id(blk - n_sblocks, n_blk - n_sblocks), lds, epoch);
+    if (blk == n_blk - 1 && threadIdx.x < 64) {
+        // every workgroup has signed in (all are past their first instructions or done): next epoch
+        const int lane = (int)threadIdx.x;
+        uint32_t total = 0;
+        for (int spins = 0; spins < kSpinLimit; ++spins) {
+            int c = (int)__hip_atomic_load(a.hctrl + 8 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) c += __shfl_xor(c, d, 64);
+            total = (uint32_t)c;
+            if (total >= (uint32_t)n_blk) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+        __hip_atomic_store(a.hctrl + 8 + lane, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (lane == 0) {
+            if (total < (uint32_t)n_blk) __hip_atomic_store(a.hctrl + 1, 3u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // never expected
+            __hip_atomic_store(a.hctrl, epoch + 1 == 0u ? 1u : epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
@@ -455,6 +556,31 @@ int seg_expand_capacity()
         cap = per_cu * cus;
     }
     return cap;
+}
+
+int seg_fused_capacity()
+{
+    static int cap = 0;
+    if (cap == 0) {
+        int per_cu = 0, cus = 0, dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, seg_fused_kernel, NT, 0) != hipSuccess) return 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cap = per_cu * cus;
+    }
+    return cap;
+}
+
+// Shrink and expand of one batch in one launch (a.hctrl / a.hflag set; a.n_swg within seg_fused_capacity()).
+hipError_t launch_seg_fused(const SegArgs &a, hipStream_t st)
+{
+    if (a.n_tiles <= 0 || a.n_ranges <= 0 || a.n_groups <= 0) return hipSuccess;
+    if (a.n_swg < 1 || a.upt != (a.d_in + KU - 1) / KU || !a.hctrl || !a.hflag) return hipErrorInvalidValue;
+    const int gs = (a.n_swg + 7) / 8 * 8;
+    if (gs > seg_fused_capacity()) return hipErrorInvalidValue;
+    const int ge = (int)(((int64_t)a.n_groups * a.n_slices + 7) / 8 * 8);
+    seg_fused_kernel<<<dim3((unsigned)(gs + ge)), dim3(NT), 0, st>>>(a, gs);
+    return hipGetLastError();
 }
 
 hipError_t launch_seg_shrink(const SegArgs &a, hipStream_t st)

@@ -632,6 +632,30 @@ def test_segmented_batches_in_flight(M, oracle, n_sub):
         M.set_tuning("seg_overlap", 0)
 
 
+def test_segmented_in_one_launch(M, oracle):
+    """The rank-64 prefill as ONE launch (the expand's workgroups wait for the flags of their tiles):
+    several batches per call, long and short segments, rows without adapter, an empty slot; every
+    row against the oracle, three calls in a row on one site (a fresh epoch each time), same bits
+    every time, and the site reports no wait that gave up."""
+    g = W.rng(54)
+    lens = [2500] + g.integers(1, 110, size=260).tolist()
+    T = int(sum(lens))
+    seg_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    seg_slot = g.integers(-1, 6, size=len(lens)).astype(np.int32)
+    c = W.seg_case("seg_one_launch", 4400, T, len(lens), 272, 136, 6, 64, 128.0, ranks=[64, 64, 0, 48, 64, 17],
+                   seg_off=seg_off, seg_slot=seg_slot, std_a=0.05, std_b=0.05)
+    site = dense_site(M, c)
+    M.set_tuning("seg_fused", 1)
+    try:
+        check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0))
+        a = run_seg(M, site, c, c.y0)
+        assert np.array_equal(a, run_seg(M, site, c, c.y0))
+        site.check()
+    finally:
+        M.set_tuning("seg_fused", 0)
+    assert np.array_equal(a, run_seg(M, site, c, c.y0)), "the pair of launches and the one launch differ"
+
+
 @pytest.mark.parametrize("seed", [1, 2])
 def test_prefill_random_segment_structures(M, oracle, seed):
     """Rank-64 prefill on segment structures nobody picked by hand: segments of 0 .. 200 rows, runs
