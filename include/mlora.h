@@ -304,7 +304,12 @@ int32_t mlora_resident_complete(mlora_resident *r, int64_t catalog_id, int32_t o
 int32_t mlora_resident_pin(mlora_resident *r, int32_t slot, int32_t pinned);
 int32_t mlora_resident_stats(mlora_resident *r, int64_t *out /* [MLORA_RESIDENT_STATS] */);
 
-/* Tuning knobs read by the launch heuristics (0 = automatic).  Host-side, process-wide. */
+/* Switches read where a launch is shaped (0 = automatic / default).  Host-side, process-wide; meant for
+ * sweeps and for tests that force a path.  Names: rows_poll_limit, rows_rank_bound, rows_items_target,
+ * rows_mode, rows_waves (decode / MoE launches); plan_general, plan_separate, plan_pipeline (planners);
+ * seg_expand_groups, seg_table_copy, seg_shrink_wgs, seg_no_mfma, seg_overlap (batches of the rank-64
+ * prefill in flight on a second stream), seg_fused (that prefill as one launch); upload_piece_kb.
+ * MLORA_E_INVALID for any other name. */
 int32_t mlora_set_tuning(const char *name, int32_t value);
 
 #ifdef __cplusplus
