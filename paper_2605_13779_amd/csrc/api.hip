@@ -438,8 +438,9 @@ int32_t segmented_mfma(mlora_site *s, const void *x, int64_t ldx, void *y, int64
             rc = stage_table(s, tab, st);
             if (rc) return rc;
         }
-        // "seg_fused": both halves in one launch (the expand's workgroups wait for the flags of their tiles)
-        if (tuning(kSegFused) && (a.n_swg + 7) / 8 * 8 <= seg_fused_capacity()) {
+        // both halves in one launch (the expand's workgroups wait for the flags of their tiles); "seg_fused" = -1:
+        // the pair of launches
+        if (tuning(kSegFused) >= 0 && (a.n_swg + 7) / 8 * 8 <= seg_fused_capacity()) {
             if (!ok(launch_seg_fused(a, st))) return MLORA_E_HIP;
         } else if (!ok(launch_seg_shrink(a, st)) || !ok(launch_seg_expand(a, st))) return MLORA_E_HIP;
     }

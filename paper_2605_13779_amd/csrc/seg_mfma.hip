@@ -1,4 +1,5 @@
-// Rank-64 segmented (prefill) LoRA apply on the gfx950 matrix cores, as two launches.
+// Rank-64 segmented (prefill) LoRA apply on the gfx950 matrix cores: a shrink half and an expand half, run
+// as one launch (seg_fused_kernel, the default) or as two.
 //
 // All rows of a segment use one adapter (a request's prompt is one contiguous run), so both halves
 // are dense contractions on the matrix cores (v_mfma_f32_32x32x16_bf16 in the shrink,
@@ -21,9 +22,9 @@
 //           through a wave-private LDS tile so that the in-place bf16 add on y moves row-contiguous
 //           16-byte pieces.
 //
-// The stream order between the two launches is the only dependency between workgroups that anyone
-// waits for.  (A one-launch form of the same two bodies exists behind a switch: seg_fused_kernel, where
-// the expand's workgroups wait for per-tile flags instead.)  What the tiling buys: per 64 rows the shrink pulls one copy of the adapter's A rows
+// As two launches, the stream order between them is the only dependency between workgroups that anyone
+// waits for; in the one-launch form the expand's workgroups wait for per-tile flags instead (see
+// seg_fused_kernel).  What the tiling buys: per 64 rows the shrink pulls one copy of the adapter's A rows
 // through the CU's L1, and the expand pulls B_s once per run instead of once per 32 rows; with
 // 32-row tiles that re-read both, adapter bytes were more than half of all L1 traffic.
 #include "internal.h"

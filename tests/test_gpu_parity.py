@@ -633,10 +633,11 @@ def test_segmented_batches_in_flight(M, oracle, n_sub):
 
 
 def test_segmented_in_one_launch(M, oracle):
-    """The rank-64 prefill as ONE launch (the expand's workgroups wait for the flags of their tiles):
-    several batches per call, long and short segments, rows without adapter, an empty slot; every
-    row against the oracle, three calls in a row on one site (a fresh epoch each time), same bits
-    every time, and the site reports no wait that gave up."""
+    """The rank-64 prefill runs as ONE launch by default (the expand's workgroups wait for the flags of
+    their tiles): several batches per call, long and short segments, rows without adapter, an empty
+    slot; every row against the oracle, three calls in a row on one site (a fresh epoch each time),
+    same bits every time, the site reports no wait that gave up, and the pair of launches
+    (seg_fused = -1) gives the same bits."""
     g = W.rng(54)
     lens = [2500] + g.integers(1, 110, size=260).tolist()
     T = int(sum(lens))
@@ -645,15 +646,17 @@ def test_segmented_in_one_launch(M, oracle):
     c = W.seg_case("seg_one_launch", 4400, T, len(lens), 272, 136, 6, 64, 128.0, ranks=[64, 64, 0, 48, 64, 17],
                    seg_off=seg_off, seg_slot=seg_slot, std_a=0.05, std_b=0.05)
     site = dense_site(M, c)
-    M.set_tuning("seg_fused", 1)
+    check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0))
+    a = run_seg(M, site, c, c.y0)
+    assert np.array_equal(a, run_seg(M, site, c, c.y0))
+    site.check()
+    M.set_tuning("seg_fused", -1)
     try:
+        b = run_seg(M, site, c, c.y0)
         check_dense(M, oracle, c, lambda y0: run_seg(M, site, c, y0))
-        a = run_seg(M, site, c, c.y0)
-        assert np.array_equal(a, run_seg(M, site, c, c.y0))
-        site.check()
     finally:
         M.set_tuning("seg_fused", 0)
-    assert np.array_equal(a, run_seg(M, site, c, c.y0)), "the pair of launches and the one launch differ"
+    assert np.array_equal(a, b), "the pair of launches and the one launch differ"
 
 
 @pytest.mark.parametrize("seed", [1, 2])
