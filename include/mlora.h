@@ -306,7 +306,7 @@ int32_t mlora_resident_stats(mlora_resident *r, int64_t *out /* [MLORA_RESIDENT_
 
 /* Switches read where a launch is shaped (0 = automatic / default).  Host-side, process-wide; meant for
  * sweeps and for tests that force a path.  Names: rows_poll_limit, rows_rank_bound, rows_items_target,
- * rows_mode, rows_waves (decode / MoE launches); plan_general, plan_separate, plan_pipeline (planners);
+ * rows_mode, rows_waves, rows_chunk_run (decode / MoE launches); plan_general, plan_separate, plan_pipeline (planners);
  * seg_expand_groups, seg_table_copy, seg_shrink_wgs, seg_no_mfma, seg_overlap (batches of the rank-64
  * prefill in flight on a second stream), seg_fused (-1: that prefill as two launches instead of one);
  * upload_piece_kb.

@@ -63,7 +63,7 @@ std::atomic<int32_t> g_knob[kKnobCount];
 const char *const kKnobName[kKnobCount] = {
     "rows_poll_limit", "rows_rank_bound", "rows_items_target", "rows_mode", "rows_waves", "plan_general",
     "plan_separate", "plan_pipeline", "seg_expand_groups", "seg_table_copy", "seg_shrink_wgs", "seg_no_mfma", "seg_overlap",
-    "upload_piece_kb", "seg_fused"};
+    "upload_piece_kb", "seg_fused", "rows_chunk_run"};
 
 // Host-side record of a slot's rank (the kernels read the device table; this only tells the launch
 // code whether any slot is padded, i.e. whether rank-bounded reads of A can save traffic).

@@ -185,7 +185,7 @@ int seg_expand_capacity();
 enum Knob {
     kRowsPollLimit, kRowsRankBound, kRowsItemsTarget, kRowsMode, kRowsWaves, kPlanGeneral, kPlanSeparate,
     kPlanPipeline, kSegExpandGroups, kSegTableCopy, kSegShrinkWgs, kSegNoMfma, kSegOverlap, kUploadPieceKb, kSegFused,
-    kKnobCount
+    kRowsChunkRun, kKnobCount
 };
 int tuning(Knob k);             // api.hip
 #ifdef MLORA_PROF

@@ -91,7 +91,9 @@ __device__ __forceinline__ void y_pack(const float *f, uint4 &r)
 // Work of workgroup `wg` out of `n_wg` on one site (one launch may cover several sites).
 // XCH: the kernel can pass partial shrink results between workgroups (a.mode 2).
 // RI: the launch has no plan; item i is row i and its slot is a.row_slot[i] (rank 1 and 2 only).
-template <int RP, int NW, bool XCH, bool RI = false>
+// RUN: one item per chunk -- 1 << RUN consecutive chunks go to one XCD (3 everywhere; one instantiation
+// with longer runs exists for measurements, see rows_multi_kernel).
+template <int RP, int NW, bool XCH, bool RI = false, int RUN = 3>
 __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const int n_wg, const int32_t *lrec = nullptr)
 {
     static_assert(!RI || (!XCH && RP <= 2), "row items: small ranks, nothing traded");
@@ -115,7 +117,8 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
     const bool use_x = XCH && a.mode != 0;                   // this site's items exchange partial results
     // Items are numbered over the upper bound of chunks, so an item's chunk record can be fetched
     // together with the live chunk count (and the launch tag) in one round trip.
-    const int n_items = a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : ((a.grid_chunks + 63) & ~63);
+    constexpr int kRunMask = (8 << RUN) - 1;                   // chunks per XCD run times 8 XCDs, minus one
+    const int n_items = a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : ((a.grid_chunks + kRunMask) & ~kRunMask);
 
     // Launches that exchange carry a tag that must differ from launch to launch, also when a
     // captured graph replays the same kernel arguments, so it lives in device memory: every
@@ -163,7 +166,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
             // the second chunk finds the adapter rows in L2 (workgroups are dealt round-robin to 8 XCDs)
             // (runs of 8 chunks per XCD, dealt cyclically, so the unused tail of the records spreads evenly)
             const int idx = item >> 3;
-            chunk = ((idx >> 3) * 8 + (item & 7)) * 8 + (idx & 7);
+            chunk = ((idx >> RUN) * 8 + (item & 7)) * (1 << RUN) + (idx & ((1 << RUN) - 1));
             if (chunk >= a.grid_chunks) continue;
         }
         // The whole record is fetched before its count is looked at (one round trip, not two).
@@ -567,7 +570,7 @@ struct MultiArgs {
     RowsArgs site[kMaxMulti];
 };
 
-template <int RP, int NW, bool XCH>
+template <int RP, int NW, bool XCH, int RUN = 3>
 __global__ __launch_bounds__(NW * 64, (NW >= 8 && RP <= 16) ? 4 : 1)
 void rows_multi_kernel(const MultiArgs m)
 {
@@ -575,7 +578,7 @@ void rows_multi_kernel(const MultiArgs m)
     int s = 0;
 #pragma unroll
     for (int k = 1; k < kMaxMulti; ++k) s += (k < m.n && b >= m.first[k]) ? 1 : 0;
-    rows_body<RP, NW, XCH>(m.site[s], b - m.first[s], m.first[s + 1] - m.first[s]);
+    rows_body<RP, NW, XCH, false, RUN>(m.site[s], b - m.first[s], m.first[s + 1] - m.first[s]);
 }
 
 // The first launch of a decode step can plan for itself: every workgroup sorts the batch's
@@ -664,9 +667,10 @@ static void set_parts(RowsArgs &a, int parts, bool exchange)
     }
 }
 
-static int fused_grid(const RowsArgs &a)
+static int fused_grid(const RowsArgs &a, int run_log2 = 3)
 {
-    return a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : ((a.grid_chunks + 63) & ~63);
+    const int run_mask = (8 << run_log2) - 1;
+    return a.tile_par > 1 ? ((a.grid_chunks + 7) & ~7) * a.tile_par : ((a.grid_chunks + run_mask) & ~run_mask);
 }
 
 // Rank-bounded reads of A cost one dependent read of the slot's rank in front of the item's loads:
@@ -738,6 +742,19 @@ static hipError_t launch_multi_rp(const RowsArgs *sites, int n, hipStream_t st, 
         any_x = any_x || m.site[k].mode == 2;
         m.first[k + 1] = m.first[k] + fused_grid(m.site[k]);
     }
+    // "rows_chunk_run" = 256 (measurements; the rank-8 four-wave launch without parts, i.e. the packed MoE
+    // sites): runs of 256 chunks per XCD instead of 8, so that all chunks of a slot's experts, and with
+    // them the rows of x they share, mostly meet in one L2
+    constexpr int kLongRun = 8;
+    bool long_run = false;
+    if constexpr (RP == 8 && NW == 4) {
+        if (!any_x && !pl && tuning(kRowsChunkRun) == (1 << kLongRun)) {
+            long_run = true;
+            for (int k = 0; k < n; ++k) long_run = long_run && m.site[k].tile_par == 1;
+            if (long_run)
+                for (int k = 0; k < n; ++k) m.first[k + 1] = m.first[k] + fused_grid(m.site[k], kLongRun);
+        }
+    }
     for (int k = n; k < kMaxMulti; ++k) { m.site[k] = m.site[0]; m.first[k + 1] = m.first[n]; }
     if constexpr (NW == 8) {
         if (pl) {
@@ -747,6 +764,12 @@ static hipError_t launch_multi_rp(const RowsArgs *sites, int n, hipStream_t st, 
         }
     }
     if (pl) return hipErrorInvalidValue;
+    if constexpr (RP == 8 && NW == 4) {
+        if (long_run) {
+            rows_multi_kernel<RP, NW, false, kLongRun><<<dim3((unsigned)m.first[n]), dim3(NW * 64), 0, st>>>(m);
+            return hipGetLastError();
+        }
+    }
     if (any_x) rows_multi_kernel<RP, NW, true><<<dim3((unsigned)m.first[n]), dim3(NW * 64), 0, st>>>(m);
     else rows_multi_kernel<RP, NW, false><<<dim3((unsigned)m.first[n]), dim3(NW * 64), 0, st>>>(m);
     return hipGetLastError();

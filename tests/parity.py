@@ -68,3 +68,15 @@ def noop_must_fail(y0_bits, delta_ref, touched_rows):
     except AssertionError:
         return
     raise AssertionError("delta check would accept a no-op kernel")
+
+
+def summed_magnitude(c):
+    """Per output of a dense case: alpha / r * sum_j |B_oj| sum_i |x_i| |A_ji| -- what the fp32 sums of
+    shrink and expand add up in absolute value.  Two correct ways of ordering those sums differ by a
+    few 2^-24 of it."""
+    mag = np.zeros(c.y0.shape)
+    xa, Aa, Ba = (np.abs(widen(v)).astype(np.float64) for v in (c.x, c.A, c.B))
+    for t in np.nonzero(c.token_slot >= 0)[0]:
+        sl = c.token_slot[t]
+        mag[t] = (c.alpha[sl] / c.rank[sl]) * (Ba[sl] @ (Aa[sl] @ xa[t]))
+    return mag

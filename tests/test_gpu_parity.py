@@ -233,7 +233,8 @@ def test_decode_multi_site_launch(M, oracle):
         single = P.host_bits(y1)
         P.check_close(single, ref, c.name + " (own launch)")
         wa, wb = P.widen(single), P.widen(got)
-        assert np.all(np.abs(wa - wb) <= 2.0 ** -7 * np.maximum(np.abs(wa), np.abs(wb))), c.name   # one bf16 step at most
+        # one bf16 step at most (plus, where y0 and the delta cancel, the rounding noise of the fp32 sums)
+        assert np.all(np.abs(wa - wb) <= 2.0 ** -7 * np.maximum(np.abs(wa), np.abs(wb)) + 2.0 ** -22 * P.summed_magnitude(c)), c.name
         assert np.mean(single != got) < 0.02, c.name
         dref = oracle.apply_decode(c.x, np.zeros_like(c.y0), c.A, c.B, c.rank, c.alpha, c.token_slot)
         P.noop_must_fail(c.y0, dref, np.nonzero(c.token_slot >= 0)[0])
@@ -274,10 +275,11 @@ def test_decode_parts_when_partners_never_answer(M, oracle):
         P.check_close(b, ref, c.name + (" (grouped)" if k >= len(cases) else ""))
         P.check_untouched(b, c.y0, c.token_slot < 0, c.name)
         # (an item on its own adds the k-slices of d_in in one sweep instead of slice by slice: the two
-        # fp32 sums differ by a few units of their last place, so the outputs may differ in their last
-        # bit -- or, where y0 and the delta cancel, by that much of the magnitude that cancelled)
-        wa, wb, w0 = P.widen(a), P.widen(b), P.widen(c.y0)
-        bad = np.argwhere(np.abs(wa - wb) > 2.0 ** -7 * np.maximum(np.abs(wa), np.abs(wb)) + 2.0 ** -16 * np.abs(w0))
+        # fp32 sums carry different rounding errors, each a few 2^-24 of the magnitudes that were added,
+        # so the outputs may differ in their last bit -- or, where y0 and the delta cancel, by that much
+        # of what was summed: 2^-22 of sum_j |B_oj| sum_i |x_i A_ji| * alpha / r)
+        wa, wb = P.widen(a), P.widen(b)
+        bad = np.argwhere(np.abs(wa - wb) > 2.0 ** -7 * np.maximum(np.abs(wa), np.abs(wb)) + 2.0 ** -22 * P.summed_magnitude(c))
         assert len(bad) == 0, (c.name, len(bad), [(tuple(i), float(wa[tuple(i)]), float(wb[tuple(i)])) for i in bad[:5]])
     for site in sites:
         site.check()
