@@ -824,6 +824,37 @@ def test_moe_gate_up_in_one_launch(M, oracle):
         M.lora_apply_decode_multi(sites[:2], plan, xs[:2], ys[:2])      # a route plan is not a decode plan
 
 
+def test_moe_gate_up_with_long_chunk_runs(M, oracle):
+    """The measurement switch rows_chunk_run = 256 (runs of 256 chunks per XCD in the grouped rank-8
+    MoE launch) only changes which workgroup takes which chunk: same bits as the default dealing,
+    over more chunks than one round of runs holds and a ragged tail."""
+    T, K, E, S = 2601, 4, 8, 4
+    base = W.moe_case("route", 5500, T, K, E, 64, 64, S, 8, 16.0)
+    base.token_slot[::7] = -1
+    cases = []
+    for i in range(2):
+        c = W.moe_case(f"run{i}", 5501 + i, T, K, E, 256, 136, S, 8, 16.0, std_a=0.05, std_b=0.05)
+        c.topk, c.token_slot = base.topk, base.token_slot
+        cases.append(c)
+    sites = [moe_site(M, c) for c in cases]
+    plan = M.Plan(T * K, S * E)
+    M.moe_plan_route(plan, torch.from_numpy(base.topk).cuda(), torch.from_numpy(base.token_slot).cuda(), S, E)
+    xs = [P.dev_bf16(c.x) for c in cases]
+    ys = [P.dev_bf16(c.y0) for c in cases]
+    M.moe_lora_apply_multi(sites, plan, xs, ys)
+    M.set_tuning("rows_chunk_run", 256)
+    try:
+        zs = [P.dev_bf16(c.y0) for c in cases]
+        M.moe_lora_apply_multi(sites, plan, xs, zs)
+        torch.cuda.synchronize()
+    finally:
+        M.set_tuning("rows_chunk_run", 0)
+    for c, y, z in zip(cases, ys, zs):
+        ref = oracle.apply_moe(c.x, c.y0, c.A, c.B, c.rank, c.alpha, c.topk, c.token_slot)
+        P.check_close(P.host_bits(z), ref, c.name)
+        assert torch.equal(y, z), c.name
+
+
 def test_rank_bounded_reads_of_padded_slots(M, oracle):
     """Slots of different true rank in one padded table: with rank-bounded reads a wave fetches
     only the slot's real rows of A (forced on and off here; by default the launch code enables it
