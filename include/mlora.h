@@ -206,8 +206,9 @@ int32_t moe_lora_apply_multi(mlora_site *const *sites, int32_t n_sites, const ml
  *   workspace: DEVICE, moe_down_workspace_bytes(T, K, d_out) bytes (T * K * MLORA_MAX_RANK 32-bit
  *   words), 16-byte aligned, overwritten.
  * Two launches.  The first leaves in the workspace, for every pair of the plan, the rank-r vector
- * h[p] = pair_w[p] * (alpha / r) * A x[p] as bf16 head and tail (one wave per (slot, expert) group,
- * so that an adapter's A rows are read once).  The second is, per slot, the dense contraction
+ * h[p] = pair_w[p] * (alpha / r) * A x[p] as bf16 head and tail (one wave per chunk of up to four
+ * pairs of a (slot, expert) group; the chunks of a group run side by side, so an adapter's A rows
+ * leave memory once).  The second is, per slot, the dense contraction
  * Y_s += H_s * Bcat_s on the matrix cores: H_s holds h[(t, k)] in the r columns of expert e(t, k)
  * of row t, Bcat_s is the slot's per-expert B tensors stacked along the contraction axis, as the
  * packed tables store them.  Pairs that the plan left out (expert ids outside [0, n_experts), slots

@@ -993,8 +993,9 @@ int32_t moe_lora_apply_down(mlora_site *s, const mlora_plan *plan, const void *x
     d.tok_sorted = plan->pv.tok_sorted; d.tok_off = plan->pv.tok_off;
     d.T = T; d.K = plan->top_k; d.E = s->E; d.n_slots = plan->n_slots; d.d_out = s->d.d_out; d.r_pad = s->r_pad;
     d.x = (const uint16_t *)x; d.ldx = ldx; d.a_tab = s->a_tab; d.scale = s->scale; d.pair_w = pair_w; d.d_in = s->d.d_in;
-    // first launch: per (slot, expert) group, h = w * (alpha / r) * A x for the group's pairs
-    if (moe_down_shrinks_by_group(s->r_pad)) {
+    d.chunks = plan->pv.chunks; d.chunk_bound = plan->grid_chunks;
+    // first launch: per chunk of a (slot, expert) group, h = w * (alpha / r) * A x for the chunk's pairs
+    if (moe_down_shrinks_by_wave(s->r_pad)) {
         if (!ok(launch_moe_down_shrink(d, st))) return MLORA_E_HIP;
     } else {
         RowsArgs a = rows_args(s, x, ldx, y, ldy);

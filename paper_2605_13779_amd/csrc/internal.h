@@ -126,14 +126,16 @@ struct MoeDownArgs {
     int32_t T, K, E, n_slots, d_out, r_pad;
     int32_t n_mtiles;            // upper bound on the number of token tiles: T / tile + n_slots
     int32_t n_ntiles;            // output tiles per token tile
-    // first launch (one wave per group) only:
+    // first launch (one wave per chunk record) only:
     const uint16_t *x; int64_t ldx;   // one input row per pair
     const uint16_t *a_tab;            // [n_slots][E][r_pad][d_in]
     const float *scale;               // [n_slots] alpha / r
     const float *pair_w;              // [T*K] routing weights
     int32_t d_in;
+    const int32_t *chunks;            // the plan's chunk records (kRec ints: key, count, -, -, the chunk's pairs)
+    int32_t chunk_bound;              // records to look at (those past the live chunks have count 0)
 };
-bool moe_down_shrinks_by_group(int r_pad);
+bool moe_down_shrinks_by_wave(int r_pad);
 hipError_t launch_moe_down_shrink(const MoeDownArgs &a, hipStream_t st);
 hipError_t launch_moe_down(const MoeDownArgs &a, hipStream_t st);
 int moe_down_tile_rows(int r_pad, int K, int E);   // 0: this shape does not fit

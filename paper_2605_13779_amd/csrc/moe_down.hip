@@ -1,10 +1,10 @@
-// MoE down projection: shrink per (slot, expert) group, then expand + routing-weight combine on the
-// matrix cores.
+// MoE down projection: shrink per chunk of a (slot, expert) group, then expand + routing-weight combine
+// on the matrix cores.
 //
 // Per-expert LoRA tensors sit on the expert down projection too (Sections 3.4 and 4.4): pair
 // p = (t, k) has its own input row and its delta is added, times the routing weight, into the ONE
-// output row of token t.  The first launch (one wave per (slot, expert) group, so that each
-// adapter's A rows are read once; ranks above 16 go through the chunk kernels of rows.hip) leaves,
+// output row of token t.  The first launch (one wave per chunk of up to four pairs of a (slot, expert)
+// group; ranks above 16 go through the chunk kernels of rows.hip) leaves,
 // per pair, the rank-r vector  h[p] = w[p] * (alpha / r) * A_{s,e} x[p]  (fp32 split into a bf16
 // head and tail).  What is left is, per slot s,
 //
@@ -314,78 +314,90 @@ void moe_down_kernel(const MoeDownArgs a)
     }
 }
 
-// First launch for padded ranks up to 16: one wave per (slot, expert) group.  The lanes split d_in
-// in 16-byte units; the group's pairs go through in passes of four (their x rows against the
-// adapter's A rows, fp32 sums per lane, one transposing reduction over the wave per pass), and
-// pair p's  h = w[p] * (alpha / r) * A x[p]  is left as bf16 head | tail words.  A group is a few
-// pairs, so what a wave costs is its three dependent round trips (offsets -> pair ids -> rows);
-// with a wave per group they all travel at once.
+// First launch for padded ranks up to 16: one wave per chunk record of the plan (up to four pairs of
+// one (slot, expert) group, their ids inside the record).  The lanes split d_in in 16-byte units; the
+// chunk's x rows go against the adapter's A rows (fp32 sums per lane, one transposing reduction over
+// the wave), and pair p's  h = w[p] * (alpha / r) * A x[p]  is left as bf16 head | tail words.  What a
+// wave costs is its dependent round trips (record -> rows; a second flight when d_in is above 512);
+// with a wave per chunk they all travel at once and the launch runs at the memory system's rate.
+// A group of more than four pairs is several neighbouring records, hence neighbouring waves that run
+// at the same time and find the adapter's rows in L2 after the first of them.  (One wave per GROUP,
+// walking the group's pairs four at a time, came back for A a few microseconds later, when the rows
+// had left L2 again: 18 MB of 94 MB fetched at the c4 shapes, 21.3 against 17.5 us.)
+// Workgroup b sits on XCD b % 8: two workgroups of an XCD share a run of 8 records.
 template <int RP>
 __global__ __launch_bounds__(256)
 void moe_down_shrink_kernel(const MoeDownArgs a)
 {
-    constexpr int CB = 4, NV = CB * RP;
+    constexpr int CB = kChunk, NV = CB * RP;
+    static_assert(kChunk == 4 && kRec == 8, "record layout: two 16-byte loads");
     const int lane = (int)threadIdx.x & 63;
-    const int g = __builtin_amdgcn_readfirstlane((int)blockIdx.x * 4 + ((int)threadIdx.x >> 6));
-    if (g >= a.n_slots * a.E) return;
+    const int b = (int)blockIdx.x, q = b >> 3;
+    const int c = __builtin_amdgcn_readfirstlane((((q >> 1) * 8 + (b & 7)) * 2 + (q & 1)) * 4 + ((int)threadIdx.x >> 6));
+    if (c >= a.chunk_bound) return;
+    const int4 *rec = (const int4 *)(a.chunks + (int64_t)c * kRec);
+    const int4 r0 = rec[0], r1 = rec[1];
+    const int key = __builtin_amdgcn_readfirstlane(r0.x), cnt = __builtin_amdgcn_readfirstlane(r0.y);
+    if (cnt <= 0) return;                                                 // past the live chunks
+    int p[CB];
+    p[0] = __builtin_amdgcn_readfirstlane(r1.x); p[1] = __builtin_amdgcn_readfirstlane(r1.y);
+    p[2] = __builtin_amdgcn_readfirstlane(r1.z); p[3] = __builtin_amdgcn_readfirstlane(r1.w);
+#pragma unroll
+    for (int i = 1; i < CB; ++i) p[i] = i < cnt ? p[i] : p[0];
     const int U = a.d_in >> 3;
-    const uint4 *Ag = (const uint4 *)(a.a_tab + (int64_t)g * RP * a.d_in);
-    // the adapter's first units leave before anything is known about the group: two of the three
-    // dependent round trips (offsets, pair ids) pass while they travel
+    const int s = key / a.E;
+    const uint4 *Ag = (const uint4 *)(a.a_tab + (int64_t)key * RP * a.d_in);
+    const uint4 *xp[CB];
+#pragma unroll
+    for (int i = 0; i < CB; ++i) xp[i] = (const uint4 *)(a.x + (int64_t)p[i] * a.ldx);
     uint4 av[RP], xv[CB];
-    auto load_a = [&](int u0) __attribute__((always_inline)) {
+    auto load_flight = [&](int u0) __attribute__((always_inline)) {
         const int u = u0 + lane, uc = u < U ? u : 0;
 #pragma unroll
         for (int j = 0; j < RP; ++j) av[j] = Ag[(int64_t)j * U + uc];
+#pragma unroll
+        for (int i = 0; i < CB; ++i) if (i < cnt) xv[i] = xp[i][uc];
     };
-    load_a(0);
-    const int q0 = a.group_off[g], q1 = a.group_off[g + 1];
-    const int s = g / a.E;
-    if (q1 <= q0 || a.rank[s] <= 0) return;
+    load_flight(0);
+    const int p_l = lane == 1 ? p[1] : (lane == 2 ? p[2] : (lane == 3 ? p[3] : p[0]));
+    const float w_l = lane < cnt ? a.pair_w[p_l] : 0.f;
+    const int r_s = a.rank[s];
     const float scale = a.scale[s];
-    for (int qb = q0; qb < q1; qb += CB) {
-        const int cnt = min(CB, q1 - qb);
-        const int p_l = lane < cnt ? a.sorted[qb + lane] : 0;
-        const float w_l = lane < cnt ? a.pair_w[p_l] : 0.f;
-        const uint4 *xp[CB];
+    float acc[NV];
 #pragma unroll
-        for (int c = 0; c < CB; ++c) xp[c] = (const uint4 *)(a.x + (int64_t)__builtin_amdgcn_readlane(p_l, c) * a.ldx);
-        float acc[NV];
+    for (int i = 0; i < NV; ++i) acc[i] = 0.f;
+    for (int u0 = 0; u0 < U; u0 += 64) {
+        if (u0 > 0) load_flight(u0);
+        const bool in = u0 + lane < U;
 #pragma unroll
-        for (int i = 0; i < NV; ++i) acc[i] = 0.f;
-        if (qb > q0 && U > 64) load_a(0);                                 // (a later pass of a wide site starts over)
-        for (int u0 = 0; u0 < U; u0 += 64) {
-            const int u = u0 + lane, uc = u < U ? u : 0;
-            if (u0 > 0) load_a(u0);
+        for (int i = 0; i < CB; ++i) {
+            if (i >= cnt) continue;
+            const uint4 xz = in ? xv[i] : make_uint4(0, 0, 0, 0);
 #pragma unroll
-            for (int c = 0; c < CB; ++c) if (c < cnt) xv[c] = xp[c][uc];
-#pragma unroll
-            for (int c = 0; c < CB; ++c) {
-                if (c >= cnt) continue;
-                const uint4 xz = u < U ? xv[c] : make_uint4(0, 0, 0, 0);
-#pragma unroll
-                for (int j = 0; j < RP; ++j) acc[c * RP + j] = dot8(xz, av[j], acc[c * RP + j]);
-            }
+            for (int j = 0; j < RP; ++j) acc[i * RP + j] = dot8(xz, av[j], acc[i * RP + j]);
         }
-        wave_sum_transpose<NV>(acc, lane);
-        const int idx = bitrev<Log2<NV>::v>(lane & (NV - 1)), c = idx / RP, j = idx - c * RP;
-        const int pc = __shfl(p_l, c, 64);
-        const float wc = __shfl(w_l, c, 64);
-        if (lane < NV && c < cnt) {
-            const float f = acc[0] * scale * wc;
-            const uint32_t hi = __float_as_uint(f) & 0xffff0000u;             // head truncated, tail rounded
-            a.h[(int64_t)pc * RP + j] = (hi >> 16) | (f2bf(f - __uint_as_float(hi)) << 16);
-        }
+    }
+    if (r_s <= 0) return;                                                 // the slot holds no adapter at this site
+    wave_sum_transpose<NV>(acc, lane);
+    const int idx = bitrev<Log2<NV>::v>(lane & (NV - 1)), ci = idx / RP, j = idx - ci * RP;
+    const int pc = __shfl(p_l, ci, 64);
+    const float wc = __shfl(w_l, ci, 64);
+    if (lane < NV && ci < cnt) {
+        const float f = acc[0] * scale * wc;
+        const uint32_t hi = __float_as_uint(f) & 0xffff0000u;                 // head truncated, tail rounded
+        a.h[(int64_t)pc * RP + j] = (hi >> 16) | (f2bf(f - __uint_as_float(hi)) << 16);
     }
 }
 
-bool moe_down_shrinks_by_group(int r_pad) { return r_pad <= 16; }
+bool moe_down_shrinks_by_wave(int r_pad) { return r_pad <= 16; }
 
 hipError_t launch_moe_down_shrink(const MoeDownArgs &a, hipStream_t st)
 {
     const int64_t groups = (int64_t)a.n_slots * a.E;
     if (groups <= 0 || a.T <= 0) return hipSuccess;
-    const dim3 grid((unsigned)((groups + 3) / 4)), block(256);
+    if (!a.chunks || a.chunk_bound <= 0) return hipErrorInvalidValue;
+    // 64 records per round of the eight XCDs (two workgroups of four waves each per XCD)
+    const dim3 grid((unsigned)(((int64_t)a.chunk_bound + 63) / 64 * 16)), block(256);
     switch (a.r_pad) {
         case 1:  moe_down_shrink_kernel<1><<<grid, block, 0, st>>>(a); break;
         case 2:  moe_down_shrink_kernel<2><<<grid, block, 0, st>>>(a); break;
