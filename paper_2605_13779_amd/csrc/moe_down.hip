@@ -22,7 +22,8 @@
 //
 // A workgroup owns a tile of up to 96 tokens of one slot and 128 outputs; each of its 4 waves owns
 // 32 outputs and streams its rows of B straight from the tables in operand layout (lane = output,
-// 8 consecutive ranks: one 16-byte load), two chunks of 8 contraction steps ahead.  H is never
+// 8 consecutive ranks: one 16-byte load), one chunk of 8 contraction steps ahead (two ahead measured
+// slower: more of B in flight than the memory system serves only queues in front of the rest).  H is never
 // written out densely.  The tile's h vectors are fetched once into LDS, split into bf16 head and
 // tail in operand layout (K vectors per token, plus one vector of zeros), beside a byte table
 // inv[token][expert] = which of the token's K pairs went to that expert (0xff: none).  A lane's
@@ -150,7 +151,7 @@ void moe_down_kernel(const MoeDownArgs a)
         else if constexpr (RP == 2) return make_uint4(*(const uint32_t *)src, 0u, 0u, 0u);
         else return make_uint4(*(const uint16_t *)src, 0u, 0u, 0u);
     };
-    uint4 bq[3][NST];
+    uint4 bq[2][NST];
     auto load_chunk_b = [&](int c, auto bufc, uint32_t mask) __attribute__((always_inline)) {
         constexpr int bi = decltype(bufc)::value;
 #pragma unroll
@@ -174,7 +175,6 @@ void moe_down_kernel(const MoeDownArgs a)
         if (st == 0 && c < n_chunks) live_l[c] = (uint8_t)(bits >> (lane & 56));
     }
     load_chunk_b(0, IntC<0>{}, range_mask(0));     // on their way while the tile's tables are built
-    load_chunk_b(1, IntC<1>{}, range_mask(1));
     for (int i = tid; i < TM * L.inv_ld / 8; i += NTD) ((uint2 *)inv)[i] = make_uint2(0xffffffffu, 0xffffffffu);
     if (tid < RPE / 8) { ((uint4 *)(hch + zero_row * RPE))[tid] = make_uint4(0, 0, 0, 0); ((uint4 *)(hcl + zero_row * RPE))[tid] = make_uint4(0, 0, 0, 0); }
     __syncthreads();
@@ -250,9 +250,9 @@ void moe_down_kernel(const MoeDownArgs a)
     auto chunk = [&](int c, auto bufc) __attribute__((always_inline)) {
         constexpr int bi = decltype(bufc)::value;
         {
-            const int c2 = c + 2;
+            const int c2 = c + 1;
             const uint32_t m2 = __builtin_amdgcn_readfirstlane(c2 < n_chunks ? (uint32_t)live_l[c2] : 0u);
-            load_chunk_b(c2, IntC<(bi + 2) % 3>{}, m2);
+            load_chunk_b(c2, IntC<(bi + 1) % 2>{}, m2);
         }
         const uint32_t mask = __builtin_amdgcn_readfirstlane((uint32_t)live_l[c]);
         if (mask == 0u) return;
@@ -282,10 +282,9 @@ void moe_down_kernel(const MoeDownArgs a)
             }
         }
     };
-    for (int c = 0; c < n_chunks; c += 3) {
+    for (int c = 0; c < n_chunks; c += 2) {
         chunk(c, IntC<0>{});
         if (c + 1 < n_chunks) chunk(c + 1, IntC<1>{});
-        if (c + 2 < n_chunks) chunk(c + 2, IntC<2>{});
     }
 
     // ---- accumulators -> staging block (the tables are dead) -> y, whole 16-byte row pieces ----
