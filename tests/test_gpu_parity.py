@@ -661,6 +661,42 @@ def test_segmented_in_one_launch(M, oracle):
     assert np.array_equal(a, b), "the pair of launches and the one launch differ"
 
 
+def test_prefill_graph_replay_keeps_results_right(M, oracle):
+    """The one-launch prefill tells its launches apart by an epoch in device memory, which the launch's
+    last workgroup advances: a captured graph, which replays the same kernel arguments, must get a
+    fresh epoch per replay, also with eager calls on the same site in between.  Inputs change between
+    replays; every replay is compared with the eager result and the oracle."""
+    g = W.rng(57)
+    lens = [150, 1, 64, 0, 97, 33, 260]
+    T = int(sum(lens))
+    seg_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    seg_slot = np.array([0, 2, 1, 0, -1, 2, 1], np.int32)
+    c = W.seg_case("seg_graph", 4500, T, len(lens), 272, 520, 3, 64, 128.0, ranks=[64, 40, 64],
+                   seg_off=seg_off, seg_slot=seg_slot, std_a=0.05, std_b=0.05)
+    site = dense_site(M, c)
+    x, y = P.dev_bf16(c.x), P.dev_bf16(c.y0)
+    M.lora_apply_segmented(site, x, y, c.seg_off, c.seg_slot)      # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        M.lora_apply_segmented(site, x, y, c.seg_off, c.seg_slot)
+    for rep in range(4):
+        xr = W.normal_bf16(W.rng(4600 + rep), c.x.shape, 1.0)
+        x.copy_(P.dev_bf16(xr))
+        y.copy_(P.dev_bf16(c.y0))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = P.host_bits(y)
+        y2 = P.dev_bf16(c.y0)
+        M.lora_apply_segmented(site, x, y2, c.seg_off, c.seg_slot)  # eager, same inputs
+        torch.cuda.synchronize()
+        assert np.array_equal(got, P.host_bits(y2)), f"replay {rep} differs from the eager call"
+        ref = oracle.apply_segmented(xr, c.y0, c.A, c.B, c.rank, c.alpha, c.seg_off, c.seg_slot)
+        P.check_close(got, ref, f"replay {rep}")
+    site.check()
+
+
 @pytest.mark.parametrize("seed", [1, 2])
 def test_prefill_random_segment_structures(M, oracle, seed):
     """Rank-64 prefill on segment structures nobody picked by hand: segments of 0 .. 200 rows, runs
