@@ -1140,6 +1140,50 @@ def test_moe_down_random_routing(M, oracle, seed):
         site.close()
 
 
+def test_moe_step_graph_replay_with_changing_routing(M, oracle):
+    """Route plan, gate projection in place on the pair rows and down projection with the combine,
+    captured once and replayed: the planner's counters must be back at zero for every replay and
+    nothing may survive from the routing of the replay before.  The routing, the slots and the
+    inputs change between replays (same device buffers); every replay goes to the oracle."""
+    T, K, E, S = 150, 4, 12, 3
+    cg = W.moe_case("graph_gate", 6100, T, K, E, 136, 264, S, 8, 16.0, std_a=0.05, std_b=0.05)
+    cd = W.moe_down_case("graph_down", 6101, T, K, E, 264, 136, S, 8, 16.0, std_a=0.05, std_b=0.05)
+    sg, sd = moe_site(M, cg), moe_site(M, cd)
+    topk, ts = torch.from_numpy(cg.topk).cuda(), torch.from_numpy(cg.token_slot).cuda()
+    w = torch.from_numpy(cd.w).cuda()
+    xg, yg = P.dev_bf16(cg.x), P.dev_bf16(cg.y0)
+    xd, yd = P.dev_bf16(cd.x), P.dev_bf16(cd.y0)
+    plan = M.Plan(T * K, S * E)
+    ws = torch.empty(M.moe_down_workspace_bytes(T, K, cd.d_out), dtype=torch.uint8, device="cuda")
+
+    def step():
+        M.moe_plan_route(plan, topk, ts, S, E)
+        M.moe_lora_apply_planned(sg, plan, xg, yg)
+        M.moe_lora_apply_down(sd, plan, xd, w, ts, ws, yd)
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        g = W.rng(6200 + rep)
+        tk = W.topk_routing(g, T, E, K)
+        sl = g.integers(-1, S, size=T).astype(np.int32)
+        if rep == 2:
+            sl[:] = 1                                  # one slot takes every token: most groups of the replay before are empty now
+        xr = W.normal_bf16(W.rng(6300 + rep), cg.x.shape, 1.0)
+        topk.copy_(torch.from_numpy(tk)); ts.copy_(torch.from_numpy(sl))
+        xg.copy_(P.dev_bf16(xr)); yg.copy_(P.dev_bf16(cg.y0)); yd.copy_(P.dev_bf16(cd.y0))
+        ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref_g = oracle.apply_moe(xr, cg.y0, cg.A, cg.B, cg.rank, cg.alpha, tk, sl)
+        P.check_close(P.host_bits(yg), ref_g, f"gate, replay {rep}")
+        ref_d = oracle.apply_moe_down(cd.x, cd.y0, cd.A, cd.B, cd.rank, cd.alpha, tk, cd.w, sl)
+        P.check_close(P.host_bits(yd), ref_d, f"down, replay {rep}")
+
+
 def test_moe_down_limits(M, oracle):
     """Sixteen experts per token is the most the down projection takes; more is refused before any launch."""
     c = W.moe_down_case("down_k16", 5395, 40, 16, 32, 72, 136, 3, 4, 8.0, std_a=0.05, std_b=0.05)
