@@ -506,6 +506,53 @@ def test_graph_replay_keeps_results_right(M, oracle):
     site.check()
 
 
+def test_decode_layer_graph_replay_with_changing_slots(M, oracle):
+    """A layer step as the benchmark issues it (the first launch plans for itself and leaves the plan
+    for the planned and grouped launches behind it), captured once and replayed with another
+    token -> slot map and other inputs each time: the plan of the replay before must not show, the
+    exchange tags must be fresh, every replay goes to the oracle."""
+    T, S = 150, 9
+    shapes = [(2304, 264, 16), (2304, 520, 16), (2304, 264, 16), (2304, 1032, 16), (1032, 2304, 16), (1032, 2056, 16)]
+    slots0 = W.rng(71).integers(-1, S, size=T).astype(np.int32)
+    cases = [W.dense_case(f"lg{i}", 3400 + i, T, di, do, S, r, 32.0, token_slot=slots0, std_a=0.05, std_b=0.05)
+             for i, (di, do, r) in enumerate(shapes)]
+    sites = [dense_site(M, c) for c in cases]
+    ts = torch.from_numpy(slots0.copy()).cuda()
+    xs = [P.dev_bf16(c.x) for c in cases]
+    ys = [P.dev_bf16(c.y0) for c in cases]
+    plan = M.Plan(T, S)
+
+    def step():
+        M.lora_plan_apply_decode_multi(sites[:3], plan, ts, S, xs[:3], ys[:3])
+        M.lora_apply_decode_planned(sites[3], plan, xs[3], ys[3])
+        M.lora_apply_decode_multi(sites[4:], plan, xs[4:], ys[4:])
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        g = W.rng(3500 + rep)
+        sl = g.integers(-1, S, size=T).astype(np.int32)
+        if rep == 1:
+            sl[:] = 4                                  # one slot takes every row
+        if rep == 2:
+            sl[:] = -1; sl[7] = 2                      # a single live row
+        ts.copy_(torch.from_numpy(sl))
+        xr = [W.normal_bf16(W.rng(3600 + 10 * rep + i), c.x.shape, 1.0) for i, c in enumerate(cases)]
+        for x, v, y, c in zip(xs, xr, ys, cases):
+            x.copy_(P.dev_bf16(v)); y.copy_(P.dev_bf16(c.y0))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (c, v, y) in enumerate(zip(cases, xr, ys)):
+            ref = oracle.apply_decode(v, c.y0, c.A, c.B, c.rank, c.alpha, sl)
+            P.check_close(P.host_bits(y), ref, f"{c.name}, replay {rep}")
+            P.check_untouched(P.host_bits(y), c.y0, sl < 0, c.name)
+    for site in sites:
+        site.check()
+
+
 def test_c2_dense_decode_layer(M, oracle):
     """The seven projections at full size, each in a launch of its own and then in the launch
     configuration the benchmark times (the step's first launch plans inside itself for q|k|v, then o,
