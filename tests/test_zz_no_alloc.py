@@ -76,3 +76,27 @@ def test_noalloc_decode_rejects_what_its_array_cannot_hold(M):
         M.lora_apply_decode_noalloc(wide, x[:8], x[:8].clone(), torch.zeros(8, dtype=torch.int32, device="cuda"))
     assert e.value.status == -6
     M.lora_apply_decode_noalloc(site, x[:0], x[:0].clone(), torch.zeros(0, dtype=torch.int32, device="cuda"))   # T = 0
+
+
+def test_noalloc_decode_inside_a_captured_graph(M, oracle):
+    # the callers the entry point is for: once the device's array is set up (first call, outside any
+    # capture), a call can be captured and replayed; inputs change between replays
+    c = W.dense_case("na_graph", 8830, 120, 2304, 264, 7, 16, 32.0, std_a=0.05, std_b=0.05)
+    site = _site(M, c)
+    x, y, ts = P.dev_bf16(c.x), P.dev_bf16(c.y0), torch.from_numpy(c.token_slot.copy()).cuda()
+    M.lora_apply_decode_noalloc(site, x, y, ts)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        M.lora_apply_decode_noalloc(site, x, y, ts)
+    for rep in range(3):
+        xr = W.normal_bf16(W.rng(8840 + rep), c.x.shape, 1.0)
+        sl = W.rng(8850 + rep).integers(-1, 7, size=c.T).astype(np.int32)
+        x.copy_(P.dev_bf16(xr)); y.copy_(P.dev_bf16(c.y0)); ts.copy_(torch.from_numpy(sl))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref = oracle.apply_decode(xr, c.y0, c.A, c.B, c.rank, c.alpha, sl)
+        P.check_close(P.host_bits(y), ref, f"replay {rep}")
+        P.check_untouched(P.host_bits(y), c.y0, sl < 0, c.name)
+    site.check()
