@@ -359,7 +359,10 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
                 }
                 first = false;
             }
-            if (then_tiles) load_more_tiles();
+            if (then_tiles) {
+                if constexpr (C::DEPTH > 1) load_tile(out0, IntC<0>{}, IntC<1>{});     // (see kTilesBehindShrink)
+                load_more_tiles();
+            }
             __syncthreads();
             float s = 0.f;
             if (tid < kChunk * RP && tid / RP < cnt) {
@@ -371,7 +374,13 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         };
         const int u_lo = solo ? 0 : kslice * a.kslice_units, u_hi = solo ? U : min(U, u_lo + a.kslice_units);
         if (do_shrink) load_flight(u_lo, u_lo, u_hi, IntC<1>{});
-        if (do_expand) {                          // the first tile travels with the shrink operands
+        // The first expand tile travels with the shrink operands -- except in the 8-wave matrix-core
+        // kernels, where it leaves with the later tiles once the shrink's operands have been consumed:
+        // the item's first flight is what its whole chain waits for, a wave gets its loads back in the
+        // order it issued them, and the tile's rows of B and y are not needed before the trade is over
+        // (c2 layer step 65.05 -> 64.0 us).
+        constexpr bool kTilesBehindShrink = C::DEPTH > 1;
+        if (do_expand && !(kTilesBehindShrink && do_shrink)) {
             load_tile(out0, IntC<0>{}, IntC<1>{});
             if (!do_shrink) load_more_tiles();
         }
