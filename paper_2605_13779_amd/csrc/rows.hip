@@ -221,8 +221,8 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         // which would put a wait for these two reads in front of the flight.
         int lane_zero;
         asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
-        const int rank = a.meta.rank[slot + lane_zero];
-        const float scale = a.meta.scale[slot + lane_zero];
+        int rank;                  // (requested behind the shrink's operands, which are wanted first)
+        float scale;
 
         const bool xitem = use_x && !solo;
         // ---- one flight: every load of this item is issued here ----
@@ -370,6 +370,8 @@ __device__ __forceinline__ void rows_body(const RowsArgs &a, const int wg, const
         };
         const int u_lo = solo ? 0 : kslice * a.kslice_units, u_hi = solo ? U : min(U, u_lo + a.kslice_units);
         if (do_shrink) load_flight(u_lo, u_lo, u_hi, IntC<1>{});
+        rank = a.meta.rank[slot + lane_zero];
+        scale = a.meta.scale[slot + lane_zero];
         // The first expand tile travels with the shrink operands -- except in the kernels of ranks 8 and
         // 16 (matrix-core expand), where it leaves with the later tiles once the shrink's operands have
         // been consumed: the item's first flight is what its whole chain waits for, a wave gets its loads
