@@ -458,8 +458,6 @@ __device__ __forceinline__ void seg_expand_body(const SegArgs &a, const int id, 
         hf0 = a.hfin + (int64_t)rr.tile0 * 128 + hpc * 8;
         const int n_blk = (nrows + 31) >> 5;
         if constexpr (FUSED) {
-            y_fetch(0, std::integral_constant<int, 0>{});
-            y_fetch(0, std::integral_constant<int, 1>{});
             if (tid == 0) {                        // the tiles these rows lie in: h complete?
                 int spins = 0;
                 for (int ti = rr.tile0 >> 6; ti <= (rr.tile0 + nrows - 1) >> 6; ++ti)
@@ -469,7 +467,11 @@ __device__ __forceinline__ void seg_expand_body(const SegArgs &a, const int id, 
                     }
             }
             __syncthreads();
+            // (h, which is wanted first, is requested first: with the first y pieces on their way from in
+            // front of the wait for the flags, h came back behind them -- 2 us per call at 7168 outputs)
             h_fetch(0);
+            y_fetch(0, std::integral_constant<int, 0>{});
+            y_fetch(0, std::integral_constant<int, 1>{});
         } else {
             h_fetch(0);
             y_fetch(0, std::integral_constant<int, 0>{});
